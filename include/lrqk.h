@@ -1,0 +1,264 @@
+/*
+ * lrqk.h — C ABI of the LRQK decode-step hot path for AMD MI355X (gfx950).
+ *
+ * LRQK ("Low Rank Query and Key" attention) keeps, per head, a rank-r key
+ * factor A_K (l x r) on the GPU and the full-precision K/V rows in host
+ * memory.  One decode step (Alg. 2, steps "proxy attention", "fetch missing",
+ * "merge", followed by Attention(q, K_Omega, V_Omega) of Sec. 4.3) is:
+ *
+ *   a1  proxy scores   s = A_K q_hat^T                     (Alg. 2, top-k line)
+ *   a2  selection      Omega_k = top(s, k) over [0, l-w),  Omega_l = [l-w, l)
+ *                                                          (Sec. 4.1 "active" / "lite" tokens)
+ *   a3  hit/miss       which of Omega_k already sit in the GPU cache, and where
+ *                      the missing ones go                 (Sec. 4.1 hit-and-miss cache)
+ *   a4  fetch          copy only the missing K/V rows host -> GPU cache
+ *                                                          (Alg. 2 "Fetch missing", "merge")
+ *   a5  attention      exact softmax attention of q over the k+w selected rows
+ *                                                          (Sec. 4.3, last sentence)
+ *
+ * Conventions
+ *   - Notation follows the paper: l context length, d head dimension, r rank,
+ *     k active (top-k) tokens, w lite (recent) tokens.  B batch, Hq query heads,
+ *     Hkv key/value heads, G = Hq/Hkv query heads per KV head, C cache slots
+ *     per (batch, query head).
+ *   - A_K, K, V and the lite rows are stored per (batch, KV head) and shared by
+ *     the G query heads of the group; scores, selection, cache state, cache
+ *     rows and outputs are per (batch, query head).  Query head h uses KV head
+ *     h / G.
+ *   - All arrays are dense, row-major, last index fastest, no padding.
+ *   - "device" pointers are HIP device memory on the current device; "host"
+ *     pointers are ordinary process memory; "pinned" is host memory allocated
+ *     with hipHostMalloc (page-locked, device-visible).
+ *   - Every buffer is allocated and owned by the caller.  The library keeps no
+ *     pointer after a call returns, except inside an lrqk_plan.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Unless stated otherwise a call only enqueues work and returns.
+ *   - Every entry point returns an int status: LRQK_OK (0) or a negative
+ *     lrqk_status.  Arguments are validated on the host before anything is
+ *     enqueued; on a validation error nothing is written.
+ *   - Device pointers must be 16-byte aligned.
+ */
+#ifndef LRQK_H
+#define LRQK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LRQK_VERSION 100 /* major*10000 + minor*100 + patch */
+
+typedef enum lrqk_status {
+  LRQK_OK = 0,
+  LRQK_EINVAL = -1, /* null or misaligned pointer, bad enum value, bad handle   */
+  LRQK_ESHAPE = -2, /* sizes inconsistent or outside the supported range         */
+  LRQK_EHIP = -3,   /* a HIP runtime call failed; see lrqk_last_hip_error()      */
+  LRQK_ENOMEM = -4, /* workspace too small, or an allocation in plan_create failed */
+  LRQK_ESTATE = -5  /* the cache state handed in is unusable (see cache_resolve)  */
+} lrqk_status;
+
+enum { LRQK_KV_BF16 = 0, LRQK_KV_F32 = 1 };
+
+/* How lrqk_decode_step / lrqk_fetch_misses move missing rows (step a4). */
+enum {
+  LRQK_FETCH_STAGED = 0, /* miss list -> host, host gathers rows into a pinned staging
+                            buffer, one hipMemcpyAsync on the plan's side stream, then a
+                            scatter kernel into the cache slots                        */
+  LRQK_FETCH_DIRECT = 1  /* a kernel reads the rows straight out of the pinned host store
+                            (device-visible host memory) and writes the cache slots;
+                            no host synchronisation                                    */
+};
+
+/*
+ * Problem sizes of one layer's decode step.
+ *   d        head dimension; only 128 is supported.
+ *   r        rank of the factors, 4 <= r <= 128, multiple of 4.
+ *   k        active tokens picked by proxy score, 1 <= k <= l - w, k <= 4096.
+ *   w        lite tokens = the last w positions, always attended, 0 <= w <= 1024.
+ *   C        cache slots per (batch, query head), k <= C <= 8192.
+ *   kv_dtype element type of K/V rows (host store, cache, lite rows).
+ *   scale    softmax scale applied to q.k (the usual 1/sqrt(d)).
+ * Requirements: B >= 1, Hkv >= 1, Hq a multiple of Hkv, Hq/Hkv <= 8, l >= 1, l < 2^24.
+ */
+typedef struct lrqk_shape {
+  int32_t B, Hq, Hkv, d, l, r, k, w, C;
+  int32_t kv_dtype;
+  float scale;
+} lrqk_shape;
+
+/* Which call a workspace is sized for (lrqk_workspace_bytes). */
+enum { LRQK_WS_SELECT = 1, LRQK_WS_ATTEND = 2 };
+
+int lrqk_version(void);
+const char* lrqk_status_string(int status);
+/* Raw hipError_t of the most recent failing HIP call made by this library in
+ * the calling thread (0 if none). */
+int lrqk_last_hip_error(void);
+
+/* Host-only check of a shape against the limits above. LRQK_OK / LRQK_EINVAL / LRQK_ESHAPE. */
+int lrqk_validate_shape(const lrqk_shape* shape);
+
+/* Bytes of device workspace the given call needs for this shape (0 on a bad
+ * shape or selector).  Workspace contents need no initialisation. */
+size_t lrqk_workspace_bytes(const lrqk_shape* shape, int which);
+
+/*
+ * a1 — proxy attention scores (Alg. 2, "compute proxy attention"; abstract: O(lr) per step).
+ *   scores[b,h,i] = sum_{j<r} A_K[b, h/G, i, j] * q_hat[b, h, j],   i in [0, l)
+ * accumulated in fp32 as one fused-multiply-add chain, j ascending, starting
+ * from 0.0f, so the result is reproducible bit for bit.
+ *   A_K     device, fp32 [B, Hkv, l, r]   read
+ *   q_hat   device, fp32 [B, Hq, r]       read
+ *   scores  device, fp32 [B, Hq, l]       written
+ */
+int lrqk_proxy_scores(const lrqk_shape* shape, const float* A_K, const float* q_hat,
+                      float* scores, void* stream);
+
+/*
+ * a2 — active-token selection (Alg. 2, top(., k); Sec. 4.1: active + lite tokens).
+ * For every (b,h): the k positions in [0, l-w) with the largest score; equal
+ * scores are ordered by lower position first (-0.0f and +0.0f compare equal;
+ * NaN scores are not supported).  Written in ascending position order.  The
+ * lite set [l-w, l) is implicit and never listed.
+ *   scores     device, fp32 [B, Hq, l]   read
+ *   sel_idx    device, int32 [B, Hq, k]  written
+ *   workspace  device, >= lrqk_workspace_bytes(shape, LRQK_WS_SELECT) bytes, 256-byte aligned
+ * LRQK_ENOMEM if ws_bytes is too small.
+ */
+int lrqk_select_topk(const lrqk_shape* shape, const float* scores, int32_t* sel_idx,
+                     void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * Cache state of one layer (all device memory):
+ *   slot_of   int32 [B, Hq, l]  slot holding token i, or -1 if i is not on the GPU
+ *   token_of  int32 [B, Hq, C]  token held by a slot, or -1 if the slot is empty
+ *   last_used int32 [B, Hq, C]  step at which the slot's token was last selected, -1 if empty
+ * slot_of and token_of are mutually inverse on the resident set.
+ * lrqk_cache_init sets all three to -1 (an empty cache).
+ */
+int lrqk_cache_init(const lrqk_shape* shape, int32_t* slot_of, int32_t* token_of,
+                    int32_t* last_used, void* stream);
+
+/*
+ * a3 — hit/miss resolution (Sec. 4.1: only tokens missing from the GPU cache are
+ * fetched; Sec. 5.3 defines the miss rate as fetched rows / selected rows).
+ * The paper's cache holds exactly the k active tokens; with C >= k slots a
+ * replacement rule is needed and this library uses least-recently-selected:
+ *   for each selected token, ascending position: resident -> hit, its slot's
+ *   last_used becomes `step`; otherwise miss.  Victim slots are the slots whose
+ *   last_used != step, ordered by (last_used ascending, slot ascending); the
+ *   j-th miss (ascending position) takes the j-th victim; the evicted token's
+ *   slot_of becomes -1; token_of / slot_of / last_used are updated.
+ * With C == k this is the paper's behaviour (the cache ends up holding Omega_k).
+ *   sel_idx   device int32 [B,Hq,k]  read; ascending, distinct, in [0, l-w)
+ *   step      >= 0 and larger than every last_used currently stored
+ *   slot_of, token_of, last_used     read and updated in place
+ *   sel_slot  device int32 [B,Hq,k]  written: slot of sel_idx[..j] after the step
+ *   hit       device uint8 [B,Hq,k]  written: 1 hit, 0 miss
+ *   miss_tok, miss_slot device int32 [B,Hq,k]  written: first n_miss entries = the
+ *             missing tokens (ascending) and the slots they were given; rest untouched
+ *   n_miss    device int32 [B,Hq]    written
+ * A head whose input breaks the contract (a position outside [0,l), or too
+ * few victims because `step` was reused) does not fault: the offending entries
+ * get sel_slot = -1 and that head's n_miss is written as -1.
+ */
+int lrqk_cache_resolve(const lrqk_shape* shape, const int32_t* sel_idx, int32_t step,
+                       int32_t* slot_of, int32_t* token_of, int32_t* last_used,
+                       int32_t* sel_slot, uint8_t* hit, int32_t* miss_tok, int32_t* miss_slot,
+                       int32_t* n_miss, void* stream);
+
+/*
+ * a5 — exact attention over the selected rows (Sec. 4.3: Attention(q_t, K_Omega, V_Omega)
+ * with the original q, K, V).
+ *   out[b,h,:] = sum_{i in Omega} p_i V_i,  p = softmax_i(scale * q[b,h,:] . K_i)
+ * Omega = the k cache rows named by sel_slot plus the w lite rows.  fp32
+ * accumulation, max-subtracted softmax.  Entries of sel_slot outside [0, C)
+ * are skipped.
+ *   q                device fp32 [B,Hq,d]
+ *   cacheK, cacheV   device kv_dtype [B,Hq,C,d]
+ *   sel_slot         device int32 [B,Hq,k]
+ *   liteK, liteV     device kv_dtype [B,Hkv,w,d] (rows l-w .. l-1; may be NULL when w == 0)
+ *   out              device fp32 [B,Hq,d]   written
+ *   workspace        device, >= lrqk_workspace_bytes(shape, LRQK_WS_ATTEND), 256-byte aligned
+ */
+int lrqk_sparse_attend(const lrqk_shape* shape, const float* q, const void* cacheK,
+                       const void* cacheV, const int32_t* sel_slot, const void* liteK,
+                       const void* liteV, float* out, void* workspace, size_t ws_bytes,
+                       void* stream);
+
+/*
+ * A plan owns what the fused step and the fetch leg need beyond the caller's
+ * buffers: device workspace, a side stream with events, and pinned staging
+ * memory sized for `max_shape` (every later call must use a shape whose
+ * B*Hq, l, k, w, C do not exceed it).  Created on the current device.
+ */
+typedef struct lrqk_plan lrqk_plan;
+int lrqk_plan_create(const lrqk_shape* max_shape, lrqk_plan** plan_out);
+int lrqk_plan_destroy(lrqk_plan* plan);
+
+/*
+ * a4 — fetch the missing rows (Alg. 2: "Fetch missing k_i, v_i from CPU K, V", "merge").
+ * For every (b,h) and j < n_miss[b,h]:
+ *   cacheK[b,h,miss_slot[b,h,j],:] = K_host[b,h/G,miss_tok[b,h,j],:]   (same for V), a bit copy.
+ *   K_host, V_host  pinned host memory, kv_dtype [B,Hkv,l,d]
+ *   miss_tok, miss_slot, n_miss  device, as written by lrqk_cache_resolve
+ *   mode  LRQK_FETCH_STAGED: synchronises `stream` once to read the miss list on the
+ *         host, then copies on the plan's side stream and makes `stream` wait for it.
+ *         LRQK_FETCH_DIRECT: one kernel on `stream`, no host synchronisation.
+ *   total_miss_out  host int64*, optional: total rows fetched (STAGED only; DIRECT writes -1).
+ * Heads with n_miss < 0 are skipped.
+ */
+int lrqk_fetch_misses(lrqk_plan* plan, const lrqk_shape* shape, const void* K_host,
+                      const void* V_host, const int32_t* miss_tok, const int32_t* miss_slot,
+                      const int32_t* n_miss, void* cacheK, void* cacheV, int mode,
+                      int64_t* total_miss_out, void* stream);
+
+/* Buffers of one layer for the fused step. Device unless marked pinned. */
+typedef struct lrqk_layer {
+  const float* A_K;    /* fp32 [B,Hkv,l,r] */
+  const void* K_host;  /* pinned, kv_dtype [B,Hkv,l,d] */
+  const void* V_host;  /* pinned, kv_dtype [B,Hkv,l,d] */
+  const void* liteK;   /* kv_dtype [B,Hkv,w,d] */
+  const void* liteV;   /* kv_dtype [B,Hkv,w,d] */
+  int32_t* slot_of;    /* int32 [B,Hq,l]  in/out */
+  int32_t* token_of;   /* int32 [B,Hq,C]  in/out */
+  int32_t* last_used;  /* int32 [B,Hq,C]  in/out */
+  void* cacheK;        /* kv_dtype [B,Hq,C,d] in/out */
+  void* cacheV;        /* kv_dtype [B,Hq,C,d] in/out */
+} lrqk_layer;
+
+/* Optional device outputs of the fused step (any may be NULL): the integer
+ * results of a2/a3, bit-identical to what the separate calls produce. */
+typedef struct lrqk_step_debug {
+  int32_t* sel_idx;   /* [B,Hq,k] */
+  int32_t* sel_slot;  /* [B,Hq,k] */
+  uint8_t* hit;       /* [B,Hq,k] */
+  int32_t* miss_tok;  /* [B,Hq,k] */
+  int32_t* miss_slot; /* [B,Hq,k] */
+  int32_t* n_miss;    /* [B,Hq]   */
+} lrqk_step_debug;
+
+/*
+ * a1..a5 as one call (Alg. 2 from the proxy-attention line to the attention of
+ * Sec. 4.3; Fig. 2: selection, then a small cache load overlapped with attention).
+ * Scores never leave the library's workspace.  Attention over the hit rows and
+ * the lite rows runs on `stream` while the missing rows travel on the plan's
+ * side stream (STAGED) and are attended afterwards; partial results are merged.
+ *   q_hat  device fp32 [B,Hq,r];  q  device fp32 [B,Hq,d];  out  device fp32 [B,Hq,d]
+ *   step   as in lrqk_cache_resolve
+ *   mode   LRQK_FETCH_STAGED (one host synchronisation per call, to read the miss
+ *          list) or LRQK_FETCH_DIRECT (fully asynchronous)
+ *   dbg    optional
+ *   total_miss_out  host int64*, optional (STAGED: rows fetched; DIRECT: -1)
+ */
+int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
+                     const lrqk_layer* layer, const float* q_hat, const float* q, float* out,
+                     int mode, const lrqk_step_debug* dbg, int64_t* total_miss_out,
+                     void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LRQK_H */
