@@ -1,0 +1,233 @@
+"""ctypes binding of liblrqk.so.  Marshalling only; no arithmetic on this side."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch  # loaded first so that the library binds to the HIP runtime torch uses
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "liblrqk.so")
+_lib = None
+
+LRQK_KV_BF16, LRQK_KV_F32 = 0, 1
+LRQK_FETCH_STAGED, LRQK_FETCH_DIRECT = 0, 1
+LRQK_WS_SELECT, LRQK_WS_ATTEND = 1, 2
+
+
+class LrqkError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = load_library().lrqk_status_string(status).decode()
+        hip = load_library().lrqk_last_hip_error() if status == -3 else 0
+        super().__init__(f"{where}: {msg} (status {status}" + (f", hipError {hip})" if hip else ")"))
+
+
+class Shape(C.Structure):
+    """lrqk_shape."""
+    _fields_ = [(n, C.c_int32) for n in ("B", "Hq", "Hkv", "d", "l", "r", "k", "w", "C", "kv_dtype")]
+    _fields_.append(("scale", C.c_float))
+
+    @classmethod
+    def make(cls, *, B, Hq, Hkv, l, r, k, w, C_slots, d=128, kv_dtype=LRQK_KV_BF16, scale=None):
+        return cls(B, Hq, Hkv, d, l, r, k, w, C_slots, kv_dtype,
+                   float(scale if scale is not None else d ** -0.5))
+
+
+class Layer(C.Structure):
+    """lrqk_layer: raw pointers of one layer's buffers."""
+    _fields_ = [(n, C.c_void_p) for n in ("A_K", "K_host", "V_host", "liteK", "liteV", "slot_of",
+                                          "token_of", "last_used", "cacheK", "cacheV")]
+
+
+class _StepDebug(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("sel_idx", "sel_slot", "hit", "miss_tok", "miss_slot",
+                                          "n_miss")]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load liblrqk.so (built in-tree by `python -m paper_2510_23649_amd.build`)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2510_23649_amd.build` "
+            "(there is no CPU or PyTorch fallback)")
+    lib = C.CDLL(_LIB_PATH)
+    vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    sp = C.POINTER(Shape)
+    sigs = {
+        "lrqk_version": (C.c_int, []),
+        "lrqk_status_string": (C.c_char_p, [C.c_int]),
+        "lrqk_last_hip_error": (C.c_int, []),
+        "lrqk_validate_shape": (C.c_int, [sp]),
+        "lrqk_workspace_bytes": (sz, [sp, C.c_int]),
+        "lrqk_proxy_scores": (C.c_int, [sp, vp, vp, vp, vp]),
+        "lrqk_select_topk": (C.c_int, [sp, vp, vp, vp, sz, vp]),
+        "lrqk_cache_init": (C.c_int, [sp, vp, vp, vp, vp]),
+        "lrqk_cache_resolve": (C.c_int, [sp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
+        "lrqk_sparse_attend": (C.c_int, [sp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
+        "lrqk_plan_create": (C.c_int, [sp, C.POINTER(vp)]),
+        "lrqk_plan_destroy": (C.c_int, [vp]),
+        "lrqk_fetch_misses": (C.c_int, [vp, sp, vp, vp, vp, vp, vp, vp, vp, C.c_int,
+                                        C.POINTER(C.c_int64), vp]),
+        "lrqk_decode_step": (C.c_int, [vp, sp, i32, C.POINTER(Layer), vp, vp, vp, C.c_int,
+                                       C.POINTER(_StepDebug), C.POINTER(C.c_int64), vp]),
+    }
+    for name, (res, args) in sigs.items():
+        fn = getattr(lib, name)   # AttributeError if the library does not export it
+        fn.restype, fn.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+EXPORTS = ["lrqk_version", "lrqk_status_string", "lrqk_last_hip_error", "lrqk_validate_shape",
+           "lrqk_workspace_bytes", "lrqk_proxy_scores", "lrqk_select_topk", "lrqk_cache_init",
+           "lrqk_cache_resolve", "lrqk_sparse_attend", "lrqk_plan_create", "lrqk_plan_destroy",
+           "lrqk_fetch_misses", "lrqk_decode_step"]
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise LrqkError(status, where)
+
+
+def _dev(t: Optional[torch.Tensor], dtype=None):
+    """Device pointer of a contiguous CUDA/HIP tensor (None -> NULL)."""
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _pinned(t: torch.Tensor):
+    if t.is_cuda or not t.is_pinned() or not t.is_contiguous():
+        raise ValueError("expected a contiguous pinned host tensor")
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def lrqk_version() -> int:
+    return load_library().lrqk_version()
+
+
+def lrqk_status_string(status: int) -> str:
+    return load_library().lrqk_status_string(status).decode()
+
+
+def lrqk_last_hip_error() -> int:
+    return load_library().lrqk_last_hip_error()
+
+
+def lrqk_validate_shape(shape: Shape) -> int:
+    return load_library().lrqk_validate_shape(C.byref(shape))
+
+
+def lrqk_workspace_bytes(shape: Shape, which: int) -> int:
+    return load_library().lrqk_workspace_bytes(C.byref(shape), which)
+
+
+def lrqk_proxy_scores(shape, A_K, q_hat, scores, stream=None):
+    _check(load_library().lrqk_proxy_scores(C.byref(shape), _dev(A_K, torch.float32),
+                                            _dev(q_hat, torch.float32),
+                                            _dev(scores, torch.float32), _stream(stream)),
+           "lrqk_proxy_scores")
+
+
+def lrqk_select_topk(shape, scores, sel_idx, workspace, stream=None):
+    _check(load_library().lrqk_select_topk(C.byref(shape), _dev(scores, torch.float32),
+                                           _dev(sel_idx, torch.int32), _dev(workspace),
+                                           workspace.numel() * workspace.element_size(),
+                                           _stream(stream)), "lrqk_select_topk")
+
+
+def lrqk_cache_init(shape, slot_of, token_of, last_used, stream=None):
+    _check(load_library().lrqk_cache_init(C.byref(shape), _dev(slot_of, torch.int32),
+                                          _dev(token_of, torch.int32),
+                                          _dev(last_used, torch.int32), _stream(stream)),
+           "lrqk_cache_init")
+
+
+def lrqk_cache_resolve(shape, sel_idx, step, slot_of, token_of, last_used, sel_slot, hit,
+                       miss_tok, miss_slot, n_miss, stream=None):
+    _check(load_library().lrqk_cache_resolve(
+        C.byref(shape), _dev(sel_idx, torch.int32), int(step), _dev(slot_of, torch.int32),
+        _dev(token_of, torch.int32), _dev(last_used, torch.int32), _dev(sel_slot, torch.int32),
+        _dev(hit, torch.uint8), _dev(miss_tok, torch.int32), _dev(miss_slot, torch.int32),
+        _dev(n_miss, torch.int32), _stream(stream)), "lrqk_cache_resolve")
+
+
+def lrqk_sparse_attend(shape, q, cacheK, cacheV, sel_slot, liteK, liteV, out, workspace,
+                       stream=None):
+    _check(load_library().lrqk_sparse_attend(
+        C.byref(shape), _dev(q, torch.float32), _dev(cacheK), _dev(cacheV),
+        _dev(sel_slot, torch.int32), _dev(liteK), _dev(liteV), _dev(out, torch.float32),
+        _dev(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+        "lrqk_sparse_attend")
+
+
+class Plan:
+    """Owner of an lrqk_plan handle (lrqk_plan_create / lrqk_plan_destroy)."""
+
+    def __init__(self, max_shape: Shape):
+        h = C.c_void_p()
+        _check(load_library().lrqk_plan_create(C.byref(max_shape), C.byref(h)), "lrqk_plan_create")
+        self.handle = h
+
+    def close(self):
+        if getattr(self, "handle", None):
+            load_library().lrqk_plan_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def lrqk_fetch_misses(plan: Plan, shape, K_host, V_host, miss_tok, miss_slot, n_miss, cacheK,
+                      cacheV, mode=LRQK_FETCH_STAGED, stream=None) -> int:
+    total = C.c_int64(0)
+    _check(load_library().lrqk_fetch_misses(
+        plan.handle, C.byref(shape), _pinned(K_host), _pinned(V_host),
+        _dev(miss_tok, torch.int32), _dev(miss_slot, torch.int32), _dev(n_miss, torch.int32),
+        _dev(cacheK), _dev(cacheV), int(mode), C.byref(total), _stream(stream)),
+        "lrqk_fetch_misses")
+    return total.value
+
+
+def make_layer(*, A_K, K_host, V_host, liteK, liteV, slot_of, token_of, last_used, cacheK,
+               cacheV) -> Layer:
+    return Layer(_dev(A_K, torch.float32), _pinned(K_host), _pinned(V_host), _dev(liteK),
+                 _dev(liteV), _dev(slot_of, torch.int32), _dev(token_of, torch.int32),
+                 _dev(last_used, torch.int32), _dev(cacheK), _dev(cacheV))
+
+
+def lrqk_decode_step(plan: Plan, shape, step, layer: Layer, q_hat, q, out,
+                     mode=LRQK_FETCH_STAGED, debug: Optional[dict] = None, stream=None) -> int:
+    dbg = None
+    if debug is not None:
+        dbg = _StepDebug(*[_dev(debug.get(n)) for n in ("sel_idx", "sel_slot", "hit", "miss_tok",
+                                                        "miss_slot", "n_miss")])
+    total = C.c_int64(0)
+    _check(load_library().lrqk_decode_step(
+        plan.handle, C.byref(shape), int(step), C.byref(layer), _dev(q_hat, torch.float32),
+        _dev(q, torch.float32), _dev(out, torch.float32), int(mode),
+        C.byref(dbg) if dbg is not None else None, C.byref(total), _stream(stream)),
+        "lrqk_decode_step")
+    return total.value

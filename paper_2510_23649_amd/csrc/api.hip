@@ -1,0 +1,395 @@
+// C ABI of liblrqk: argument validation, the plan object, the fetch leg's host
+// side and the fused decode step.  Every kernel lives in its own source file;
+// this file only checks, carves workspaces and enqueues.
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "lrqk_internal.h"
+
+namespace lrqk {
+
+static thread_local int g_last_hip_error = 0;
+
+int record_hip_error(hipError_t e) {
+  g_last_hip_error = static_cast<int>(e);
+  (void)hipGetLastError();  // clear the sticky slot so later calls report their own errors
+  return LRQK_EHIP;
+}
+
+static int check_shape(const lrqk_shape* s) {
+  if (!s) return LRQK_EINVAL;
+  if (s->kv_dtype != LRQK_KV_BF16 && s->kv_dtype != LRQK_KV_F32) return LRQK_EINVAL;
+  if (s->B < 1 || s->Hq < 1 || s->Hkv < 1 || s->l < 1) return LRQK_ESHAPE;
+  if (s->Hq % s->Hkv != 0 || s->Hq / s->Hkv > kMaxG) return LRQK_ESHAPE;
+  if (s->d != kD) return LRQK_ESHAPE;
+  if (s->r < 4 || s->r > 128 || s->r % 4 != 0) return LRQK_ESHAPE;
+  if (s->l >= (1 << 24)) return LRQK_ESHAPE;
+  if (s->w < 0 || s->w > kMaxW || s->w > s->l) return LRQK_ESHAPE;
+  if (s->k < 1 || s->k > s->l - s->w || s->k > kMaxK) return LRQK_ESHAPE;
+  if (s->C < s->k || s->C > kMaxC) return LRQK_ESHAPE;
+  if ((long)s->B * s->Hq > 65535) return LRQK_ESHAPE;
+  if (!std::isfinite(s->scale)) return LRQK_ESHAPE;
+  return LRQK_OK;
+}
+
+static bool all_aligned16(std::initializer_list<const void*> ps) {
+  for (const void* p : ps)
+    if (!p || !aligned16(p)) return false;
+  return true;
+}
+
+}  // namespace lrqk
+
+using namespace lrqk;
+
+struct lrqk_plan {
+  lrqk_shape max;
+  int device;
+  int BHq;
+  // device
+  float* scores;
+  void* select_ws;
+  size_t select_bytes;
+  float* partials;
+  size_t partial_bytes;
+  int32_t *sel_idx, *sel_slot, *miss_tok, *miss_slot, *n_miss;
+  uint8_t* hit;
+  void* d_stage;
+  int64_t* d_rowdst;
+  // pinned host
+  int32_t *h_nmiss, *h_miss_tok, *h_miss_slot;
+  void* h_stage;
+  int64_t* h_rowdst;
+  size_t stage_rows;
+  hipStream_t side;
+  hipEvent_t ev_main, ev_side;
+};
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+int lrqk_version(void) { return LRQK_VERSION; }
+
+const char* lrqk_status_string(int status) {
+  switch (status) {
+    case LRQK_OK: return "ok";
+    case LRQK_EINVAL: return "invalid argument (null or misaligned pointer, bad enum or handle)";
+    case LRQK_ESHAPE: return "shape inconsistent or outside the supported range";
+    case LRQK_EHIP: return "HIP runtime error (see lrqk_last_hip_error)";
+    case LRQK_ENOMEM: return "workspace too small or allocation failed";
+    case LRQK_ESTATE: return "unusable cache state";
+    default: return "unknown status";
+  }
+}
+
+int lrqk_last_hip_error(void) { return g_last_hip_error; }
+
+int lrqk_validate_shape(const lrqk_shape* shape) { return check_shape(shape); }
+
+size_t lrqk_workspace_bytes(const lrqk_shape* shape, int which) {
+  if (check_shape(shape) != LRQK_OK) return 0;
+  const int BHq = shape->B * shape->Hq;
+  if (which == LRQK_WS_SELECT) return carve_select_ws(nullptr, BHq, shape->k).bytes;
+  if (which == LRQK_WS_ATTEND) return attend_ws_bytes(BHq, shape->k, shape->w, 1);
+  return 0;
+}
+
+int lrqk_proxy_scores(const lrqk_shape* shape, const float* A_K, const float* q_hat,
+                      float* scores, void* stream) {
+  const int rc = check_shape(shape);
+  if (rc != LRQK_OK) return rc;
+  if (!all_aligned16({A_K, q_hat, scores})) return LRQK_EINVAL;
+  LRQK_HIP(launch_proxy_scores(*shape, A_K, q_hat, scores, static_cast<hipStream_t>(stream)));
+  return LRQK_OK;
+}
+
+int lrqk_select_topk(const lrqk_shape* shape, const float* scores, int32_t* sel_idx,
+                     void* workspace, size_t ws_bytes, void* stream) {
+  const int rc = check_shape(shape);
+  if (rc != LRQK_OK) return rc;
+  if (!all_aligned16({scores, sel_idx}) || !workspace || !aligned256(workspace)) return LRQK_EINVAL;
+  const SelectWs ws = carve_select_ws(workspace, shape->B * shape->Hq, shape->k);
+  if (ws_bytes < ws.bytes) return LRQK_ENOMEM;
+  LRQK_HIP(launch_select_topk(*shape, scores, sel_idx, ws, static_cast<hipStream_t>(stream)));
+  return LRQK_OK;
+}
+
+int lrqk_cache_init(const lrqk_shape* shape, int32_t* slot_of, int32_t* token_of,
+                    int32_t* last_used, void* stream) {
+  const int rc = check_shape(shape);
+  if (rc != LRQK_OK) return rc;
+  if (!all_aligned16({slot_of, token_of, last_used})) return LRQK_EINVAL;
+  LRQK_HIP(launch_cache_init(*shape, slot_of, token_of, last_used,
+                             static_cast<hipStream_t>(stream)));
+  return LRQK_OK;
+}
+
+int lrqk_cache_resolve(const lrqk_shape* shape, const int32_t* sel_idx, int32_t step,
+                       int32_t* slot_of, int32_t* token_of, int32_t* last_used,
+                       int32_t* sel_slot, uint8_t* hit, int32_t* miss_tok, int32_t* miss_slot,
+                       int32_t* n_miss, void* stream) {
+  const int rc = check_shape(shape);
+  if (rc != LRQK_OK) return rc;
+  if (step < 0 || step == INT32_MAX) return LRQK_EINVAL;
+  if (!all_aligned16({sel_idx, slot_of, token_of, last_used, sel_slot, hit, miss_tok, miss_slot,
+                      n_miss}))
+    return LRQK_EINVAL;
+  LRQK_HIP(launch_cache_resolve(*shape, sel_idx, step, slot_of, token_of, last_used, sel_slot,
+                                hit, miss_tok, miss_slot, n_miss,
+                                static_cast<hipStream_t>(stream)));
+  return LRQK_OK;
+}
+
+int lrqk_sparse_attend(const lrqk_shape* shape, const float* q, const void* cacheK,
+                       const void* cacheV, const int32_t* sel_slot, const void* liteK,
+                       const void* liteV, float* out, void* workspace, size_t ws_bytes,
+                       void* stream) {
+  const int rc = check_shape(shape);
+  if (rc != LRQK_OK) return rc;
+  if (!all_aligned16({q, cacheK, cacheV, sel_slot, out}) || !workspace || !aligned256(workspace))
+    return LRQK_EINVAL;
+  if (shape->w > 0 && !all_aligned16({liteK, liteV})) return LRQK_EINVAL;
+  const int BHq = shape->B * shape->Hq;
+  if (ws_bytes < attend_ws_bytes(BHq, shape->k, shape->w, 1)) return LRQK_ENOMEM;
+  const AttendGeom g = attend_geometry(BHq, shape->k, shape->w);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  float* partials = static_cast<float*>(workspace);
+  LRQK_HIP(launch_attend_partial(*shape, kAttendAll, q, cacheK, cacheV, sel_slot, nullptr, nullptr,
+                                 nullptr, liteK, liteV, partials, g.nsplit, g.rows_per_block,
+                                 g.nsplit, 0, st));
+  LRQK_HIP(launch_attend_combine(*shape, partials, g.nsplit, g.nsplit, out, st));
+  return LRQK_OK;
+}
+
+// ---------------------------------------------------------------------------- plan
+
+int lrqk_plan_destroy(lrqk_plan* p) {
+  if (!p) return LRQK_EINVAL;
+  int prev = -1;
+  (void)hipGetDevice(&prev);
+  (void)hipSetDevice(p->device);
+  if (p->side) (void)hipStreamSynchronize(p->side);
+  void* dev[] = {p->scores, p->select_ws, p->partials, p->sel_idx, p->sel_slot, p->miss_tok,
+                 p->miss_slot, p->n_miss, p->hit, p->d_stage, p->d_rowdst};
+  for (void* q : dev)
+    if (q) (void)hipFree(q);
+  void* host[] = {p->h_nmiss, p->h_miss_tok, p->h_miss_slot, p->h_stage, p->h_rowdst};
+  for (void* q : host)
+    if (q) (void)hipHostFree(q);
+  if (p->ev_main) (void)hipEventDestroy(p->ev_main);
+  if (p->ev_side) (void)hipEventDestroy(p->ev_side);
+  if (p->side) (void)hipStreamDestroy(p->side);
+  if (prev >= 0) (void)hipSetDevice(prev);
+  delete p;
+  return LRQK_OK;
+}
+
+int lrqk_plan_create(const lrqk_shape* max_shape, lrqk_plan** plan_out) {
+  if (!plan_out) return LRQK_EINVAL;
+  *plan_out = nullptr;
+  const int rc = check_shape(max_shape);
+  if (rc != LRQK_OK) return rc;
+  lrqk_plan* p = new (std::nothrow) lrqk_plan();
+  if (!p) return LRQK_ENOMEM;
+  std::memset(p, 0, sizeof(*p));
+  p->max = *max_shape;
+  const lrqk_shape& s = p->max;
+  const size_t BHq = (size_t)s.B * s.Hq;
+  p->BHq = (int)BHq;
+  const size_t rowB = (size_t)s.d * kv_elem_bytes(s.kv_dtype);
+  p->select_bytes = carve_select_ws(nullptr, (int)BHq, s.k).bytes;
+  p->partial_bytes = attend_ws_bytes((int)BHq, s.k, s.w, 2);
+  p->stage_rows = BHq * s.k;
+  hipError_t e = hipGetDevice(&p->device);
+  auto dmalloc = [&](void** q, size_t bytes) {
+    if (e == hipSuccess) e = hipMalloc(q, bytes ? bytes : 256);
+  };
+  auto hmalloc = [&](void** q, size_t bytes) {
+    if (e == hipSuccess) e = hipHostMalloc(q, bytes ? bytes : 256, hipHostMallocDefault);
+  };
+  dmalloc((void**)&p->scores, BHq * s.l * sizeof(float));
+  dmalloc(&p->select_ws, p->select_bytes);
+  dmalloc((void**)&p->partials, p->partial_bytes);
+  dmalloc((void**)&p->sel_idx, BHq * s.k * 4);
+  dmalloc((void**)&p->sel_slot, BHq * s.k * 4);
+  dmalloc((void**)&p->miss_tok, BHq * s.k * 4);
+  dmalloc((void**)&p->miss_slot, BHq * s.k * 4);
+  dmalloc((void**)&p->n_miss, BHq * 4);
+  dmalloc((void**)&p->hit, BHq * s.k);
+  dmalloc(&p->d_stage, p->stage_rows * 2 * rowB);
+  dmalloc((void**)&p->d_rowdst, p->stage_rows * 8);
+  hmalloc((void**)&p->h_nmiss, BHq * 4);
+  hmalloc((void**)&p->h_miss_tok, BHq * s.k * 4);
+  hmalloc((void**)&p->h_miss_slot, BHq * s.k * 4);
+  hmalloc(&p->h_stage, p->stage_rows * 2 * rowB);
+  hmalloc((void**)&p->h_rowdst, p->stage_rows * 8);
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&p->side, hipStreamNonBlocking);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_main, hipEventDisableTiming);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_side, hipEventDisableTiming);
+  if (e != hipSuccess) {
+    const int code = (e == hipErrorOutOfMemory) ? LRQK_ENOMEM : record_hip_error(e);
+    lrqk_plan_destroy(p);
+    return code;
+  }
+  *plan_out = p;
+  return LRQK_OK;
+}
+
+static int check_plan_fits(const lrqk_plan* p, const lrqk_shape* s) {
+  if (!p) return LRQK_EINVAL;
+  const lrqk_shape& m = p->max;
+  if ((long)s->B * s->Hq > p->BHq || s->l > m.l || s->k > m.k || s->w > m.w || s->C > m.C ||
+      s->kv_dtype != m.kv_dtype)
+    return LRQK_ESHAPE;
+  // the attention partial buffer is sized from (BHq, k, w) of the plan's shape
+  if (attend_ws_bytes(s->B * s->Hq, s->k, s->w, 2) > p->partial_bytes) return LRQK_ESHAPE;
+  if (carve_select_ws(nullptr, s->B * s->Hq, s->k).bytes > p->select_bytes) return LRQK_ESHAPE;
+  return LRQK_OK;
+}
+
+// Host side of the staged fetch.  `stream` must already hold the resolve kernel.
+// Returns the largest n_miss over heads through *max_nmiss.
+static int staged_fetch(lrqk_plan* p, const lrqk_shape& s, const void* K_host, const void* V_host,
+                        const int32_t* miss_tok, const int32_t* miss_slot, const int32_t* n_miss,
+                        void* cacheK, void* cacheV, hipStream_t stream, bool sync_lists,
+                        int64_t* total_out, int* max_nmiss) {
+  const size_t BHq = (size_t)s.B * s.Hq;
+  const size_t rowB = (size_t)s.d * kv_elem_bytes(s.kv_dtype);
+  if (sync_lists) {
+    LRQK_HIP(hipMemcpyAsync(p->h_nmiss, n_miss, BHq * 4, hipMemcpyDeviceToHost, stream));
+    LRQK_HIP(hipMemcpyAsync(p->h_miss_tok, miss_tok, BHq * s.k * 4, hipMemcpyDeviceToHost, stream));
+    LRQK_HIP(hipMemcpyAsync(p->h_miss_slot, miss_slot, BHq * s.k * 4, hipMemcpyDeviceToHost,
+                            stream));
+    LRQK_HIP(hipStreamSynchronize(stream));
+  }
+  const int G = s.Hq / s.Hkv;
+  const char* Kh = static_cast<const char*>(K_host);
+  const char* Vh = static_cast<const char*>(V_host);
+  char* stage = static_cast<char*>(p->h_stage);
+  int64_t total = 0;
+  int mx = 0;
+  for (size_t bh = 0; bh < BHq; ++bh) {
+    const int nm = p->h_nmiss[bh];
+    if (nm <= 0) continue;
+    const int cnt = nm < s.k ? nm : s.k;
+    if (cnt > mx) mx = cnt;
+    const size_t b = bh / s.Hq, h = bh % s.Hq, kvh = h / G;
+    const char* Ks = Kh + (b * s.Hkv + kvh) * (size_t)s.l * rowB;
+    const char* Vs = Vh + (b * s.Hkv + kvh) * (size_t)s.l * rowB;
+    for (int j = 0; j < cnt; ++j) {
+      const int32_t tok = p->h_miss_tok[bh * s.k + j];
+      const int32_t slot = p->h_miss_slot[bh * s.k + j];
+      if (tok < 0 || tok >= s.l || slot < 0 || slot >= s.C) continue;
+      std::memcpy(stage + (size_t)total * 2 * rowB, Ks + (size_t)tok * rowB, rowB);
+      std::memcpy(stage + (size_t)total * 2 * rowB + rowB, Vs + (size_t)tok * rowB, rowB);
+      p->h_rowdst[total] = (int64_t)bh * s.C + slot;
+      ++total;
+    }
+  }
+  if (max_nmiss) *max_nmiss = mx;
+  if (total_out) *total_out = total;
+  if (total > 0) {
+    LRQK_HIP(hipMemcpyAsync(p->d_stage, p->h_stage, (size_t)total * 2 * rowB,
+                            hipMemcpyHostToDevice, p->side));
+    LRQK_HIP(hipMemcpyAsync(p->d_rowdst, p->h_rowdst, (size_t)total * 8, hipMemcpyHostToDevice,
+                            p->side));
+    LRQK_HIP(launch_scatter_staged(s, p->d_stage, p->d_rowdst, total, cacheK, cacheV, p->side));
+    LRQK_HIP(hipEventRecord(p->ev_side, p->side));
+    LRQK_HIP(hipStreamWaitEvent(stream, p->ev_side, 0));
+  }
+  return LRQK_OK;
+}
+
+int lrqk_fetch_misses(lrqk_plan* plan, const lrqk_shape* shape, const void* K_host,
+                      const void* V_host, const int32_t* miss_tok, const int32_t* miss_slot,
+                      const int32_t* n_miss, void* cacheK, void* cacheV, int mode,
+                      int64_t* total_miss_out, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != LRQK_OK) return rc;
+  if (mode != LRQK_FETCH_STAGED && mode != LRQK_FETCH_DIRECT) return LRQK_EINVAL;
+  if (!all_aligned16({K_host, V_host, miss_tok, miss_slot, n_miss, cacheK, cacheV}))
+    return LRQK_EINVAL;
+  rc = check_plan_fits(plan, shape);
+  if (rc != LRQK_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (mode == LRQK_FETCH_DIRECT) {
+    LRQK_HIP(launch_fetch_direct(*shape, K_host, V_host, miss_tok, miss_slot, n_miss, cacheK,
+                                 cacheV, st));
+    if (total_miss_out) *total_miss_out = -1;
+    return LRQK_OK;
+  }
+  return staged_fetch(plan, *shape, K_host, V_host, miss_tok, miss_slot, n_miss, cacheK, cacheV,
+                      st, true, total_miss_out, nullptr);
+}
+
+int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
+                     const lrqk_layer* L, const float* q_hat, const float* q, float* out,
+                     int mode, const lrqk_step_debug* dbg, int64_t* total_miss_out,
+                     void* stream) {
+  int rc = check_shape(shape);
+  if (rc != LRQK_OK) return rc;
+  if (!L || step < 0 || step == INT32_MAX) return LRQK_EINVAL;
+  if (mode != LRQK_FETCH_STAGED && mode != LRQK_FETCH_DIRECT) return LRQK_EINVAL;
+  if (!all_aligned16({L->A_K, L->K_host, L->V_host, L->slot_of, L->token_of, L->last_used,
+                      L->cacheK, L->cacheV, q_hat, q, out}))
+    return LRQK_EINVAL;
+  if (shape->w > 0 && !all_aligned16({L->liteK, L->liteV})) return LRQK_EINVAL;
+  rc = check_plan_fits(plan, shape);
+  if (rc != LRQK_OK) return rc;
+  const lrqk_shape& s = *shape;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int BHq = s.B * s.Hq;
+
+  int32_t* sel_idx = (dbg && dbg->sel_idx) ? dbg->sel_idx : plan->sel_idx;
+  int32_t* sel_slot = (dbg && dbg->sel_slot) ? dbg->sel_slot : plan->sel_slot;
+  uint8_t* hit = (dbg && dbg->hit) ? dbg->hit : plan->hit;
+  int32_t* miss_tok = (dbg && dbg->miss_tok) ? dbg->miss_tok : plan->miss_tok;
+  int32_t* miss_slot = (dbg && dbg->miss_slot) ? dbg->miss_slot : plan->miss_slot;
+  int32_t* n_miss = (dbg && dbg->n_miss) ? dbg->n_miss : plan->n_miss;
+  if (!all_aligned16({sel_idx, sel_slot, hit, miss_tok, miss_slot, n_miss})) return LRQK_EINVAL;
+
+  const SelectWs ws = carve_select_ws(plan->select_ws, BHq, s.k);
+  LRQK_HIP(launch_proxy_scores(s, L->A_K, q_hat, plan->scores, st));
+  LRQK_HIP(launch_select_topk(s, plan->scores, sel_idx, ws, st));
+  LRQK_HIP(launch_cache_resolve(s, sel_idx, step, L->slot_of, L->token_of, L->last_used, sel_slot,
+                                hit, miss_tok, miss_slot, n_miss, st));
+  const AttendGeom g = attend_geometry(BHq, s.k, s.w);
+  const int parts_per_head = g.nsplit + ceil_div(s.k, g.rows_per_block);
+
+  if (mode == LRQK_FETCH_DIRECT) {
+    LRQK_HIP(launch_fetch_direct(s, L->K_host, L->V_host, miss_tok, miss_slot, n_miss, L->cacheK,
+                                 L->cacheV, st));
+    LRQK_HIP(launch_attend_partial(s, kAttendAll, q, L->cacheK, L->cacheV, sel_slot, nullptr,
+                                   nullptr, nullptr, L->liteK, L->liteV, plan->partials, g.nsplit,
+                                   g.rows_per_block, parts_per_head, 0, st));
+    LRQK_HIP(launch_attend_combine(s, plan->partials, parts_per_head, g.nsplit, out, st));
+    if (total_miss_out) *total_miss_out = -1;
+    return LRQK_OK;
+  }
+
+  // STAGED: bring the miss list to the host (the one synchronisation of the step) ...
+  const size_t nb = (size_t)BHq;
+  LRQK_HIP(hipMemcpyAsync(plan->h_nmiss, n_miss, nb * 4, hipMemcpyDeviceToHost, st));
+  LRQK_HIP(hipMemcpyAsync(plan->h_miss_tok, miss_tok, nb * s.k * 4, hipMemcpyDeviceToHost, st));
+  LRQK_HIP(hipMemcpyAsync(plan->h_miss_slot, miss_slot, nb * s.k * 4, hipMemcpyDeviceToHost, st));
+  LRQK_HIP(hipStreamSynchronize(st));
+  // ... attend the rows already resident and the lite rows while the host packs the misses
+  LRQK_HIP(launch_attend_partial(s, kAttendHitsAndLite, q, L->cacheK, L->cacheV, sel_slot, hit,
+                                 nullptr, nullptr, L->liteK, L->liteV, plan->partials, g.nsplit,
+                                 g.rows_per_block, parts_per_head, 0, st));
+  int max_nmiss = 0;
+  rc = staged_fetch(plan, s, L->K_host, L->V_host, miss_tok, miss_slot, n_miss, L->cacheK,
+                    L->cacheV, st, false, total_miss_out, &max_nmiss);
+  if (rc != LRQK_OK) return rc;
+  const int nblk_miss = ceil_div(max_nmiss, g.rows_per_block);
+  LRQK_HIP(launch_attend_partial(s, kAttendMisses, q, L->cacheK, L->cacheV, sel_slot, hit,
+                                 miss_slot, n_miss, L->liteK, L->liteV, plan->partials, nblk_miss,
+                                 g.rows_per_block, parts_per_head, g.nsplit, st));
+  LRQK_HIP(launch_attend_combine(s, plan->partials, parts_per_head, g.nsplit + nblk_miss, out, st));
+  return LRQK_OK;
+}
+
+#pragma GCC visibility pop
+}  // extern "C"

@@ -1,0 +1,89 @@
+// Internal declarations shared by the HIP sources of liblrqk (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lrqk.h"
+
+namespace lrqk {
+
+constexpr int kWave = 64;           // CDNA wavefront width
+constexpr int kD = 128;             // supported head dimension
+constexpr int kMaxG = 8;            // query heads per KV head
+constexpr int kMaxK = 4096;         // active tokens per head
+constexpr int kMaxC = 8192;         // cache slots per head
+constexpr int kMaxW = 1024;         // lite tokens
+constexpr int kBins = 4096;         // first-level histogram: top 12 bits of the order key
+constexpr int kBinShift = 20;
+constexpr int kCandCap = 4096;      // candidates of the threshold bin kept per head
+
+// Record a failing HIP call for lrqk_last_hip_error(); returns LRQK_EHIP.
+int record_hip_error(hipError_t e);
+
+#define LRQK_HIP(call)                                          \
+  do {                                                          \
+    hipError_t e__ = (call);                                    \
+    if (e__ != hipSuccess) return ::lrqk::record_hip_error(e__); \
+  } while (0)
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline int next_pow2(int x) {
+  int p = 1;
+  while (p < x) p <<= 1;
+  return p;
+}
+inline size_t kv_elem_bytes(int kv_dtype) { return kv_dtype == LRQK_KV_BF16 ? 2 : 4; }
+
+// Layout of the selection workspace (all offsets multiples of 256 bytes).
+struct SelectWs {
+  uint32_t* hist;      // [BHq][kBins]
+  uint32_t* counters;  // [BHq][8]: 0 ticket_hist, 1 ticket_collect, 2 n_out, 3 n_cand, 4 bin, 5 n_above
+  int32_t* out_list;   // [BHq][k]      unordered positions in bins above the threshold bin
+  uint64_t* cand;      // [BHq][kCandCap]  (key << 32 | ~pos) of the threshold bin
+  size_t bytes;
+};
+SelectWs carve_select_ws(void* base, int BHq, int k);
+
+// Layout of the attention workspace: partial softmax states.
+// One partial = [m, s, pad, pad, acc[128]] = 132 floats.
+constexpr int kPartialStride = 132;
+struct AttendGeom {
+  int rows_per_block;  // rows of Omega handled by one workgroup
+  int nsplit;          // workgroups per head for k + w rows
+};
+AttendGeom attend_geometry(int BHq, int k, int w);
+size_t attend_ws_bytes(int BHq, int k, int w, int phases);
+
+// ---- kernel launchers (each validates nothing; callers have done so) -------------------
+hipError_t launch_proxy_scores(const lrqk_shape& s, const float* A_K, const float* q_hat,
+                               float* scores, hipStream_t st);
+hipError_t launch_select_topk(const lrqk_shape& s, const float* scores, int32_t* sel_idx,
+                              const SelectWs& ws, hipStream_t st);
+hipError_t launch_cache_init(const lrqk_shape& s, int32_t* slot_of, int32_t* token_of,
+                             int32_t* last_used, hipStream_t st);
+hipError_t launch_cache_resolve(const lrqk_shape& s, const int32_t* sel_idx, int32_t step,
+                                int32_t* slot_of, int32_t* token_of, int32_t* last_used,
+                                int32_t* sel_slot, uint8_t* hit, int32_t* miss_tok,
+                                int32_t* miss_slot, int32_t* n_miss, hipStream_t st);
+// which rows of Omega an attention launch covers
+enum AttendMode { kAttendAll = 0, kAttendHitsAndLite = 1, kAttendMisses = 2 };
+hipError_t launch_attend_partial(const lrqk_shape& s, int mode, const float* q, const void* cacheK,
+                                 const void* cacheV, const int32_t* sel_slot, const uint8_t* hit,
+                                 const int32_t* miss_slot, const int32_t* n_miss,
+                                 const void* liteK, const void* liteV, float* partials,
+                                 int nblocks, int rows_per_block, int parts_per_head,
+                                 int part_offset, hipStream_t st);
+hipError_t launch_attend_combine(const lrqk_shape& s, const float* partials, int parts_per_head,
+                                 int nparts, float* out, hipStream_t st);
+hipError_t launch_fetch_direct(const lrqk_shape& s, const void* K_host, const void* V_host,
+                               const int32_t* miss_tok, const int32_t* miss_slot,
+                               const int32_t* n_miss, void* cacheK, void* cacheV, hipStream_t st);
+// rows staged contiguously as [row][K bytes | V bytes]; row_dst[i] = (bh * C + slot)
+hipError_t launch_scatter_staged(const lrqk_shape& s, const void* staging, const int64_t* row_dst,
+                                 int64_t n_rows, void* cacheK, void* cacheV, hipStream_t st);
+
+}  // namespace lrqk

@@ -1,0 +1,293 @@
+// a5 — exact softmax attention of one query over the k + w selected rows
+// (Sec. 4.3: Attention(q_t, K_Omega, V_Omega) with the original q, K, V).
+//
+// One query row per head and 2*d flops per K/V element pair: the step is bound by
+// the HBM reads of the selected rows (a random gather of d-element rows from the
+// cache plus the contiguous lite rows).  Layout of the work:
+//   * the k + w rows of a head are split over `nsplit` workgroups so that batch-1
+//     steps still fill the chip; a workgroup of 4 wavefronts handles a contiguous
+//     range of the row list;
+//   * a row is read by 16 lanes, each taking one 16-byte (bf16) or 32-byte (fp32)
+//     chunk of the K row and the same chunk of the V row, so a wavefront reads 4
+//     rows per load instruction in full 256/512-byte segments; four such groups
+//     of loads are issued before any is consumed;
+//   * q.K is finished with a 16-lane rotate-and-add; every 16-lane group keeps its
+//     own running (max, sum, acc[8 per lane]) so no cross-group traffic is needed
+//     until the end, where the 4 groups and then the 4 wavefronts are merged;
+//   * each workgroup writes one partial (m, s, acc[128]); a second small kernel
+//     merges the partials of a head.
+// Arithmetic is fp32 throughout; exp is exp2 on log2(e)-scaled logits.
+#include "lrqk_internal.h"
+
+namespace lrqk {
+namespace {
+
+constexpr int kAttThreads = 256;
+constexpr int kRowsPerPass = 16;  // 4 wavefronts x 4 row groups
+constexpr int kUnroll = 4;        // passes whose loads are in flight together
+constexpr float kLog2e = 1.4426950408889634f;
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __int_as_float(
+      __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+// sum over the 16 lanes of a DPP row; every lane of the row ends with the total
+__device__ __forceinline__ float row16_allreduce_sum(float v) {
+  v += dpp_f32<0x128>(v);  // row_ror:8
+  v += dpp_f32<0x124>(v);  // row_ror:4
+  v += dpp_f32<0x122>(v);  // row_ror:2
+  v += dpp_f32<0x121>(v);  // row_ror:1
+  return v;
+}
+
+struct Chunk8 {
+  float v[8];
+};
+
+__device__ __forceinline__ Chunk8 unpack_bf16x8(const uint4 u) {
+  Chunk8 c;
+  c.v[0] = __uint_as_float(u.x << 16);
+  c.v[1] = __uint_as_float(u.x & 0xffff0000u);
+  c.v[2] = __uint_as_float(u.y << 16);
+  c.v[3] = __uint_as_float(u.y & 0xffff0000u);
+  c.v[4] = __uint_as_float(u.z << 16);
+  c.v[5] = __uint_as_float(u.z & 0xffff0000u);
+  c.v[6] = __uint_as_float(u.w << 16);
+  c.v[7] = __uint_as_float(u.w & 0xffff0000u);
+  return c;
+}
+
+// Loads the lane's 8-element chunk of a row.  BF16: 16 bytes; F32: 32 bytes.
+template <bool BF16>
+struct RowChunk;
+template <>
+struct RowChunk<true> {
+  uint4 raw;
+  __device__ __forceinline__ void load(const void* row, int c) {
+    raw = reinterpret_cast<const uint4*>(row)[c];
+  }
+  __device__ __forceinline__ Chunk8 get() const { return unpack_bf16x8(raw); }
+};
+template <>
+struct RowChunk<false> {
+  float4 a, b;
+  __device__ __forceinline__ void load(const void* row, int c) {
+    a = reinterpret_cast<const float4*>(row)[2 * c];
+    b = reinterpret_cast<const float4*>(row)[2 * c + 1];
+  }
+  __device__ __forceinline__ Chunk8 get() const {
+    Chunk8 o;
+    o.v[0] = a.x; o.v[1] = a.y; o.v[2] = a.z; o.v[3] = a.w;
+    o.v[4] = b.x; o.v[5] = b.y; o.v[6] = b.z; o.v[7] = b.w;
+    return o;
+  }
+};
+
+template <bool BF16>
+__global__ __launch_bounds__(kAttThreads) void attend_partial_kernel(
+    int mode, const float* __restrict__ q, const void* __restrict__ cacheK,
+    const void* __restrict__ cacheV, const int32_t* __restrict__ sel_slot,
+    const uint8_t* __restrict__ hit, const int32_t* __restrict__ miss_slot,
+    const int32_t* __restrict__ n_miss, const void* __restrict__ liteK,
+    const void* __restrict__ liteV, float* __restrict__ partials, int Hq, int Hkv, int C, int k,
+    int w, int rows_per_block, int parts_per_head, int part_offset, float scale) {
+  constexpr size_t ROWB = kD * (BF16 ? 2 : 4);
+  __shared__ float wm[4], wsum[4];
+  __shared__ float wacc[4][kD];
+
+  const int bh = blockIdx.y;
+  const int b = bh / Hq, h = bh - b * Hq;
+  const int kvh = h / (Hq / Hkv);
+  const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
+  const int grp = lane >> 4, c = lane & 15;
+
+  const char* __restrict__ Kc = static_cast<const char*>(cacheK) + (size_t)bh * C * ROWB;
+  const char* __restrict__ Vc = static_cast<const char*>(cacheV) + (size_t)bh * C * ROWB;
+  const char* __restrict__ Kl =
+      static_cast<const char*>(liteK) + ((size_t)b * Hkv + kvh) * (size_t)w * ROWB;
+  const char* __restrict__ Vl =
+      static_cast<const char*>(liteV) + ((size_t)b * Hkv + kvh) * (size_t)w * ROWB;
+  const int32_t* __restrict__ slots =
+      (mode == kAttendMisses ? miss_slot : sel_slot) + (size_t)bh * k;
+  const uint8_t* __restrict__ hits = hit ? hit + (size_t)bh * k : nullptr;
+
+  int n_rows;  // length of this head's row list
+  if (mode == kAttendMisses) {
+    const int nm = n_miss[bh];
+    n_rows = nm < 0 ? 0 : min(nm, k);
+  } else {
+    n_rows = k + w;
+  }
+
+  float qv[8];
+  {
+    const float4 q0 = reinterpret_cast<const float4*>(q + (size_t)bh * kD)[2 * c];
+    const float4 q1 = reinterpret_cast<const float4*>(q + (size_t)bh * kD)[2 * c + 1];
+    const float f = scale * kLog2e;  // logits are kept in log2 units
+    qv[0] = q0.x * f; qv[1] = q0.y * f; qv[2] = q0.z * f; qv[3] = q0.w * f;
+    qv[4] = q1.x * f; qv[5] = q1.y * f; qv[6] = q1.z * f; qv[7] = q1.w * f;
+  }
+
+  float m = -INFINITY, ssum = 0.0f;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+  const int row_begin = blockIdx.x * rows_per_block;
+  const int row_end = min(n_rows, row_begin + rows_per_block);
+  for (int base = row_begin; base < row_end; base += kRowsPerPass * kUnroll) {
+    const void* kp[kUnroll];
+    const void* vp[kUnroll];
+    bool ok[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int j = base + u * kRowsPerPass + wv * 4 + grp;
+      ok[u] = j < row_end;
+      kp[u] = nullptr;
+      vp[u] = nullptr;
+      if (ok[u]) {
+        if (mode != kAttendMisses && j >= k) {
+          kp[u] = Kl + (size_t)(j - k) * ROWB;
+          vp[u] = Vl + (size_t)(j - k) * ROWB;
+        } else {
+          const int32_t s = slots[j];
+          ok[u] = s >= 0 && s < C && !(mode == kAttendHitsAndLite && hits[j] == 0);
+          kp[u] = Kc + (size_t)s * ROWB;
+          vp[u] = Vc + (size_t)s * ROWB;
+        }
+      }
+    }
+    RowChunk<BF16> kc[kUnroll], vc[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+      if (ok[u]) {
+        kc[u].load(kp[u], c);
+        vc[u].load(vp[u], c);
+      }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      float part = 0.0f;
+      Chunk8 kk = kc[u].get();
+#pragma unroll
+      for (int i = 0; i < 8; ++i) part = __builtin_fmaf(qv[i], ok[u] ? kk.v[i] : 0.0f, part);
+      const float logit = row16_allreduce_sum(part);  // all lanes take part in the DPP ops
+      if (ok[u]) {
+        const float m_new = fmaxf(m, logit);
+        const float corr = exp2f(m - m_new);  // m = -inf on the first row gives 0
+        const float p = exp2f(logit - m_new);
+        ssum = ssum * corr + p;
+        Chunk8 vv = vc[u].get();
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_fmaf(p, vv.v[i], acc[i] * corr);
+        m = m_new;
+      }
+    }
+  }
+
+  // merge the 4 row groups of the wavefront (lanes c, c+16, c+32, c+48)
+  float mw = fmaxf(m, __shfl_xor(m, 16));
+  mw = fmaxf(mw, __shfl_xor(mw, 32));
+  const float f = (m == -INFINITY) ? 0.0f : exp2f(m - mw);
+  ssum *= f;
+  ssum += __shfl_xor(ssum, 16);
+  ssum += __shfl_xor(ssum, 32);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    float a = acc[i] * f;
+    a += __shfl_xor(a, 16);
+    a += __shfl_xor(a, 32);
+    acc[i] = a;
+  }
+  if (lane < 16) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) wacc[wv][8 * c + i] = acc[i];
+    if (lane == 0) {
+      wm[wv] = mw;
+      wsum[wv] = ssum;
+    }
+  }
+  __syncthreads();
+  // merge the 4 wavefronts; thread j < 128 owns output dimension j
+  if (t < kD) {
+    const float M = fmaxf(fmaxf(wm[0], wm[1]), fmaxf(wm[2], wm[3]));
+    float a = 0.0f, s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float g = (wm[i] == -INFINITY) ? 0.0f : exp2f(wm[i] - M);
+      a += wacc[i][t] * g;
+      s += wsum[i] * g;
+    }
+    float* __restrict__ P =
+        partials + ((size_t)bh * parts_per_head + part_offset + blockIdx.x) * kPartialStride;
+    P[4 + t] = a;
+    if (t == 0) {
+      P[0] = M;
+      P[1] = s;
+    }
+  }
+}
+
+__global__ __launch_bounds__(kD) void attend_combine_kernel(const float* __restrict__ partials,
+                                                            int parts_per_head, int nparts,
+                                                            float* __restrict__ out) {
+  const int bh = blockIdx.x, t = threadIdx.x;
+  const float* __restrict__ P = partials + (size_t)bh * parts_per_head * kPartialStride;
+  float M = -INFINITY;
+  for (int p = 0; p < nparts; ++p) M = fmaxf(M, P[(size_t)p * kPartialStride]);
+  float a = 0.0f, s = 0.0f;
+  for (int p = 0; p < nparts; ++p) {
+    const float mp = P[(size_t)p * kPartialStride];
+    const float g = (mp == -INFINITY) ? 0.0f : exp2f(mp - M);
+    a += P[(size_t)p * kPartialStride + 4 + t] * g;
+    s += P[(size_t)p * kPartialStride + 1] * g;
+  }
+  out[(size_t)bh * kD + t] = s > 0.0f ? a / s : 0.0f;
+}
+
+}  // namespace
+
+AttendGeom attend_geometry(int BHq, int k, int w) {
+  const int rows = k + w;
+  AttendGeom g;
+  g.rows_per_block = kRowsPerPass * kUnroll;  // 64
+  // fewer, larger workgroups once there are plenty of them
+  while (g.rows_per_block < 512 && (long)ceil_div(rows, g.rows_per_block * 2) * BHq >= 2048)
+    g.rows_per_block *= 2;
+  g.nsplit = ceil_div(rows, g.rows_per_block);
+  return g;
+}
+
+size_t attend_ws_bytes(int BHq, int k, int w, int phases) {
+  const AttendGeom g = attend_geometry(BHq, k, w);
+  const int parts = g.nsplit + (phases > 1 ? ceil_div(k, g.rows_per_block) : 0);
+  return round_up((size_t)BHq * parts * kPartialStride * sizeof(float), 256);
+}
+
+hipError_t launch_attend_partial(const lrqk_shape& s, int mode, const float* q, const void* cacheK,
+                                 const void* cacheV, const int32_t* sel_slot, const uint8_t* hit,
+                                 const int32_t* miss_slot, const int32_t* n_miss,
+                                 const void* liteK, const void* liteV, float* partials,
+                                 int nblocks, int rows_per_block, int parts_per_head,
+                                 int part_offset, hipStream_t st) {
+  if (nblocks <= 0) return hipSuccess;
+  const dim3 grid(nblocks, s.B * s.Hq);
+  if (s.kv_dtype == LRQK_KV_BF16)
+    hipLaunchKernelGGL((attend_partial_kernel<true>), grid, dim3(kAttThreads), 0, st, mode, q,
+                       cacheK, cacheV, sel_slot, hit, miss_slot, n_miss, liteK, liteV, partials,
+                       s.Hq, s.Hkv, s.C, s.k, s.w, rows_per_block, parts_per_head, part_offset,
+                       s.scale);
+  else
+    hipLaunchKernelGGL((attend_partial_kernel<false>), grid, dim3(kAttThreads), 0, st, mode, q,
+                       cacheK, cacheV, sel_slot, hit, miss_slot, n_miss, liteK, liteV, partials,
+                       s.Hq, s.Hkv, s.C, s.k, s.w, rows_per_block, parts_per_head, part_offset,
+                       s.scale);
+  return hipGetLastError();
+}
+
+hipError_t launch_attend_combine(const lrqk_shape& s, const float* partials, int parts_per_head,
+                                 int nparts, float* out, hipStream_t st) {
+  hipLaunchKernelGGL(attend_combine_kernel, dim3(s.B * s.Hq), dim3(kD), 0, st, partials,
+                     parts_per_head, nparts, out);
+  return hipGetLastError();
+}
+
+}  // namespace lrqk

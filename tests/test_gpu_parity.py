@@ -1,0 +1,350 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element,
+on seeded synthetic inputs.  Needs an MI355X: every test is marked `gpu`.
+
+Bars: integer results (selection, hit/miss map, slots, miss lists, cache maps,
+fetched rows) bit-exact; proxy scores bit-exact with the oracle's fp32 fma chain;
+attention output max-abs error <= 2e-3 with bf16 K/V and <= 1e-5 with fp32 K/V.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    import paper_2510_23649_amd as L
+    from gpu_harness import (DEV, DeviceLayer, StepBuffers, compare_resolution, compare_state,
+                             shape_of, workspace)
+
+from gen import get_config, make_layer, QueryStream, as_numpy
+from oracle import lrqk_oracle as orc
+from helpers import check_topk_sets
+
+TOL = {"bf16": 2e-3, "f32": 1e-5}
+
+
+def small_cfg(**kw):
+    base = dict(B=2, Hq=8, Hkv=2, l=3000, r=32, k=200, w=24, C=320, n_heavy=16, pool_mult=4,
+                phase_spread=1.0, prefill="warm", rho=0.9)
+    base.update(kw)
+    return get_config("c1").with_(**base)
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------------------- a1
+
+@pytest.mark.parametrize("r,G,l,B,Hkv", [
+    (32, 4, 4096, 1, 8), (32, 4, 5000, 2, 2), (16, 4, 1031, 1, 2), (64, 4, 2049, 1, 2),
+    (32, 7, 3001, 2, 1), (32, 1, 777, 1, 3), (32, 2, 255, 1, 2), (32, 8, 512, 1, 1),
+    (16, 7, 300, 1, 1), (64, 1, 1000, 1, 1),
+    (4, 4, 1000, 1, 2), (8, 3, 1500, 2, 2), (48, 5, 999, 1, 2), (128, 8, 700, 1, 1), (100, 6, 130, 1, 1),
+])
+def test_proxy_scores_bit_exact(r, G, l, B, Hkv):
+    say(f"proxy_scores r={r} G={G} l={l} B={B} Hkv={Hkv}")
+    rng = np.random.default_rng(r * 1000 + G * 10 + l)
+    Hq = Hkv * G
+    A_K = rng.standard_normal((B, Hkv, l, r)).astype(np.float32)
+    q_hat = rng.standard_normal((B, Hq, r)).astype(np.float32)
+    shp = L.Shape.make(B=B, Hq=Hq, Hkv=Hkv, l=l, r=r, k=1, w=0, C_slots=1)
+    scores = torch.full((B, Hq, l), float("nan"), device=DEV)
+    L.lrqk_proxy_scores(shp, torch.from_numpy(A_K).to(DEV), torch.from_numpy(q_hat).to(DEV), scores)
+    torch.cuda.synchronize()
+    _, s32 = orc.proxy_scores(A_K, q_hat)
+    assert np.array_equal(scores.cpu().numpy().view(np.uint32), s32.view(np.uint32))
+
+
+# ------------------------------------------------------------------------------- a2
+
+def run_select(scores_np, k, w):
+    B, Hq, l = scores_np.shape
+    shp = L.Shape.make(B=B, Hq=Hq, Hkv=Hq, l=l, r=4, k=k, w=w, C_slots=max(k, 1))
+    ws = workspace(L.lrqk_workspace_bytes(shp, L.LRQK_WS_SELECT))
+    sel = torch.full((B, Hq, k), -1, dtype=torch.int32, device=DEV)
+    L.lrqk_select_topk(shp, torch.from_numpy(scores_np).to(DEV), sel, ws)
+    torch.cuda.synchronize()
+    return sel.cpu().numpy()
+
+
+@pytest.mark.parametrize("l,w,k,B,Hq", [
+    (4096, 16, 256, 1, 8), (10000, 64, 1024, 2, 3), (70001, 64, 2048, 1, 4), (300, 0, 300, 1, 2),
+    (257, 1, 1, 1, 2), (5000, 1000, 4000, 1, 2), (131072, 64, 2048, 1, 2), (4097, 0, 4096, 1, 1),
+])
+def test_select_topk_random(l, w, k, B, Hq):
+    say(f"select_topk random l={l} w={w} k={k} B={B} Hq={Hq}")
+    rng = np.random.default_rng(l + k)
+    s = (rng.standard_normal((B, Hq, l)) * 11.3).astype(np.float32)
+    s[:, :, l - w:] = 1e6      # the lite window must never be listed
+    got = run_select(s, k, w)
+    assert np.array_equal(got, orc.select_topk(s, k, w))
+
+
+def test_select_topk_ties_zeros_and_massive_duplicates():
+    say("select_topk ties / signed zeros / all-equal (threshold-bin overflow path)")
+    rng = np.random.default_rng(5)
+    l, w, k = 20000, 32, 1500
+    s = np.empty((1, 6, l), np.float32)
+    s[0, 0] = np.round(rng.standard_normal(l) * 4) / 4            # heavy exact ties
+    s[0, 1] = 3.25                                                # all equal: lowest positions win
+    s[0, 2] = rng.choice(np.array([0.0, -0.0], np.float32), l)    # +0 and -0 are equal
+    s[0, 3] = -np.abs(rng.standard_normal(l)).astype(np.float32)  # all negative
+    s[0, 4] = rng.choice(np.array([1.0, 1.0 + 2 ** -23, 1.0 - 2 ** -24], np.float32), l)  # one bin, 3 keys
+    s[0, 5] = np.where(rng.random(l) < 0.02, 50.0, 0.5).astype(np.float32)  # few above, rest tied
+    got = run_select(s, k, w)
+    assert np.array_equal(got, orc.select_topk(s, k, w))
+    assert np.array_equal(got[0, 1], np.arange(k))
+
+
+# ------------------------------------------------------------------------------- a3 + a4
+
+@pytest.mark.parametrize("mode", ["staged", "direct"])
+@pytest.mark.parametrize("kvd,C", [("bf16", 320), ("bf16", 200), ("f32", 256)])
+def test_resolve_and_fetch_over_steps(kvd, C, mode):
+    say(f"cache_resolve + fetch_misses kv={kvd} C={C} mode={mode}")
+    cfg = small_cfg(kv_dtype=kvd, C=C)
+    data = make_layer(cfg)
+    dl = DeviceLayer(cfg, data)
+    plan = L.Plan(dl.shape)
+    sb = StepBuffers(cfg)
+    rng = np.random.default_rng(C)
+    pool = rng.permutation(cfg.l - cfg.w)[: 3 * cfg.k]     # selections overlap from step to step
+    fmode = L.LRQK_FETCH_STAGED if mode == "staged" else L.LRQK_FETCH_DIRECT
+    for step in range(6):
+        sel = np.sort(np.stack([np.stack([rng.choice(pool, cfg.k, replace=False)
+                                          for _ in range(cfg.Hq)]) for _ in range(cfg.B)]),
+                      axis=-1).astype(np.int32)
+        sb.sel_idx.copy_(torch.from_numpy(sel))
+        L.lrqk_cache_resolve(dl.shape, sb.sel_idx, step, dl.slot_of, dl.token_of, dl.last_used,
+                             sb.sel_slot, sb.hit, sb.miss_tok, sb.miss_slot, sb.n_miss)
+        total = L.lrqk_fetch_misses(plan, dl.shape, dl.K_host, dl.V_host, sb.miss_tok,
+                                    sb.miss_slot, sb.n_miss, dl.cacheK, dl.cacheV, fmode)
+        ref = orc.cache_resolve(sel, step, dl.ost)
+        assert ref["ok"]
+        orc.fetch(dl.np["K"], dl.np["V"], ref["miss_tok"], ref["miss_slot"], ref["n_miss"],
+                  dl.ocK, dl.ocV)
+        compare_resolution(sb.to_np(), ref, f"step {step}")
+        compare_state(dl, f"step {step}")
+        if mode == "staged":
+            assert total == int(ref["n_miss"].sum())
+        if step > 0:
+            assert 0 < ref["n_miss"].sum() < sel.size     # the case has both hits and misses
+    plan.close()
+
+
+def test_resolve_contract_violations_do_not_fault():
+    say("cache_resolve with a reused step and an out-of-range position")
+    cfg = small_cfg(B=1, Hq=2, Hkv=1, l=500, k=8, w=4, C=8)
+    shp = shape_of(cfg)
+    dl = DeviceLayer(cfg, make_layer(cfg))
+    sb = StepBuffers(cfg)
+    sel = np.array([[[1, 2, 3, 4, 5, 6, 7, 8], [10, 20, 30, 40, 50, 60, 70, 9999]]], np.int32)
+    sb.sel_idx.copy_(torch.from_numpy(sel))
+    L.lrqk_cache_resolve(shp, sb.sel_idx, 3, dl.slot_of, dl.token_of, dl.last_used, sb.sel_slot,
+                         sb.hit, sb.miss_tok, sb.miss_slot, sb.n_miss)
+    got = sb.to_np()
+    assert got["n_miss"][0, 0] == 8 and got["n_miss"][0, 1] == -1
+    assert got["sel_slot"][0, 1, 7] == -1
+    sel2 = np.array([[[11, 12, 13, 14, 15, 16, 17, 18], [1, 2, 3, 4, 5, 6, 7, 8]]], np.int32)
+    sb.sel_idx.copy_(torch.from_numpy(sel2))
+    L.lrqk_cache_resolve(shp, sb.sel_idx, 3, dl.slot_of, dl.token_of, dl.last_used, sb.sel_slot,
+                         sb.hit, sb.miss_tok, sb.miss_slot, sb.n_miss)     # same step again
+    got = sb.to_np()
+    assert got["n_miss"][0, 0] == -1           # every slot is protected: no victims
+    assert (got["sel_slot"][0, 0] == -1).all()
+
+
+# ------------------------------------------------------------------------------- a5
+
+@pytest.mark.parametrize("kvd", ["bf16", "f32"])
+@pytest.mark.parametrize("k,w,C,B,Hq,Hkv", [
+    (200, 24, 320, 2, 8, 2), (1, 0, 1, 1, 1, 1), (64, 0, 64, 1, 4, 4), (2048, 64, 4096, 1, 8, 2),
+    (33, 1000, 40, 1, 7, 1), (1000, 13, 1000, 2, 4, 2),
+])
+def test_sparse_attend(kvd, k, w, C, B, Hq, Hkv):
+    say(f"sparse_attend kv={kvd} k={k} w={w} C={C} B={B} Hq={Hq} Hkv={Hkv}")
+    rng = np.random.default_rng(k + w)
+    d = 128
+    tdt = torch.bfloat16 if kvd == "bf16" else torch.float32
+    g = torch.Generator().manual_seed(k * 7 + w)
+    cK = torch.randn(B, Hq, C, d, generator=g).to(tdt)
+    cV = torch.randn(B, Hq, C, d, generator=g).to(tdt)
+    lK = torch.randn(B, Hkv, w, d, generator=g).to(tdt)
+    lV = torch.randn(B, Hkv, w, d, generator=g).to(tdt)
+    q = (torch.randn(B, Hq, d, generator=g) * 1.5).float()
+    sel_slot = np.stack([np.stack([rng.permutation(C)[:k] for _ in range(Hq)])
+                         for _ in range(B)]).astype(np.int32)
+    if k > 4:
+        sel_slot[0, 0, 3] = -1          # skipped rows
+        sel_slot[0, 0, 4] = C + 5
+    shp = L.Shape.make(B=B, Hq=Hq, Hkv=Hkv, l=max(k + w, C) + 8, r=4, k=k, w=w, C_slots=C,
+                       kv_dtype=L.LRQK_KV_BF16 if kvd == "bf16" else L.LRQK_KV_F32)
+    ws = workspace(L.lrqk_workspace_bytes(shp, L.LRQK_WS_ATTEND))
+    out = torch.full((B, Hq, d), float("nan"), device=DEV)
+    L.lrqk_sparse_attend(shp, q.to(DEV), cK.to(DEV), cV.to(DEV), torch.from_numpy(sel_slot).to(DEV),
+                         lK.to(DEV) if w else None, lV.to(DEV) if w else None, out, ws)
+    torch.cuda.synchronize()
+    lKn = as_numpy(lK) if w else np.zeros((B, Hkv, 0, d), as_numpy(cK).dtype)
+    lVn = as_numpy(lV) if w else np.zeros((B, Hkv, 0, d), as_numpy(cK).dtype)
+    ref = orc.sparse_attend(q.numpy(), as_numpy(cK), as_numpy(cV), sel_slot, lKn, lVn,
+                            float(shp.scale))
+    err = np.abs(out.cpu().numpy().astype(np.float64) - ref).max()
+    say(f"   max abs err {err:.3e}")
+    assert err <= TOL[kvd]
+
+
+def test_sparse_attend_closed_forms():
+    say("sparse_attend: equal keys -> mean of V; dominant logit -> that row")
+    d, C, k = 128, 300, 300
+    g = torch.Generator().manual_seed(11)
+    q = torch.randn(1, 1, d, generator=g)
+    V = torch.randn(1, 1, C, d, generator=g)
+    K = torch.randn(1, 1, 1, d, generator=g).expand(1, 1, C, d).contiguous()
+    shp = L.Shape.make(B=1, Hq=1, Hkv=1, l=C, r=4, k=k, w=0, C_slots=C, kv_dtype=L.LRQK_KV_F32)
+    ws = workspace(L.lrqk_workspace_bytes(shp, L.LRQK_WS_ATTEND))
+    sel = torch.arange(k, dtype=torch.int32, device=DEV).reshape(1, 1, k)
+    out = torch.empty(1, 1, d, device=DEV)
+    L.lrqk_sparse_attend(shp, q.to(DEV), K.to(DEV), V.to(DEV), sel, None, None, out, ws)
+    assert np.abs(out.cpu().numpy()[0, 0] - V[0, 0].double().mean(0).numpy()).max() < 1e-5
+    K2 = 0.01 * torch.randn(1, 1, C, d, generator=g)
+    K2[0, 0, 123] = 300.0 * q[0, 0] / (q[0, 0] @ q[0, 0])     # logit 300/sqrt(128) above the rest
+    L.lrqk_sparse_attend(shp, q.to(DEV), K2.to(DEV), V.to(DEV), sel, None, None, out, ws)
+    assert np.abs(out.cpu().numpy()[0, 0] - V[0, 0, 123].numpy()).max() < 1e-5
+
+
+# ------------------------------------------------------------------------------- a1..a5
+
+def run_steps_against_oracle(cfg, n_steps, mode, identity=False, data=None, check_unfused=True):
+    """Drive lrqk_decode_step for n_steps and compare every step with the oracle."""
+    data = data or make_layer(cfg)
+    dl = DeviceLayer(cfg, data, identity=identity)
+    plan = L.Plan(dl.shape)
+    lay = dl.struct()
+    qs = QueryStream(data)
+    sb = StepBuffers(cfg)
+    out = torch.empty((cfg.B, cfg.Hq, cfg.d), device=DEV)
+    fmode = L.LRQK_FETCH_STAGED if mode == "staged" else L.LRQK_FETCH_DIRECT
+    miss_rates = []
+    for step in range(1, n_steps + 1):
+        q, q_hat = qs.next()
+        qd, qhd = q.to(DEV), q_hat.to(DEV)
+        if check_unfused and step == 1:
+            unfused = run_unfused(cfg, dl, qd, qhd, step)      # on copies of the state
+        total = L.lrqk_decode_step(plan, dl.shape, step, lay, qhd, qd, out, fmode, sb.debug())
+        got = sb.to_np()
+        ref = orc.decode_step(dl.np["A_K"], as_numpy(q_hat), as_numpy(q), dl.np["K"], dl.np["V"],
+                              dl.ost, dl.ocK, dl.ocV, step, cfg.k, cfg.w, cfg.scale)
+        assert ref["ok"]
+        assert np.array_equal(got["sel_idx"], ref["sel_idx"]), (
+            f"step {step}: selection differs; near-tie heads: "
+            f"{check_topk_sets(got['sel_idx'], ref['sel_idx'], ref['s64'], cfg.w)}")
+        compare_resolution(got, ref, f"step {step}")
+        compare_state(dl, f"step {step}")
+        err = np.abs(out.cpu().numpy().astype(np.float64) - ref["out"]).max()
+        say(f"   step {step}: miss rate {ref['miss_rate']:.3f}  max abs err {err:.3e}")
+        assert err <= TOL[cfg.kv_dtype], f"step {step}: attention error {err}"
+        if mode == "staged":
+            assert total == int(ref["n_miss"].sum())
+        if check_unfused and step == 1:
+            for name in ("sel_idx", "sel_slot", "hit", "n_miss"):
+                assert np.array_equal(unfused[name], got[name]), f"fused/unfused {name} differ"
+            assert np.abs(unfused["out"] - out.cpu().numpy()).max() <= 1e-5
+        miss_rates.append(ref["miss_rate"])
+    plan.close()
+    return miss_rates
+
+
+def run_unfused(cfg, dl, q, q_hat, step):
+    """a1, a2, a3, a4, a5 as five separate calls on clones of the cache state."""
+    shp = dl.shape
+    scores = torch.empty((cfg.B, cfg.Hq, cfg.l), device=DEV)
+    sb = StepBuffers(cfg)
+    slot_of, token_of, last_used = dl.slot_of.clone(), dl.token_of.clone(), dl.last_used.clone()
+    cK, cV = dl.cacheK.clone(), dl.cacheV.clone()
+    plan = L.Plan(shp)
+    L.lrqk_proxy_scores(shp, dl.A_K, q_hat, scores)
+    L.lrqk_select_topk(shp, scores, sb.sel_idx, workspace(L.lrqk_workspace_bytes(shp, L.LRQK_WS_SELECT)))
+    L.lrqk_cache_resolve(shp, sb.sel_idx, step, slot_of, token_of, last_used, sb.sel_slot, sb.hit,
+                         sb.miss_tok, sb.miss_slot, sb.n_miss)
+    L.lrqk_fetch_misses(plan, shp, dl.K_host, dl.V_host, sb.miss_tok, sb.miss_slot, sb.n_miss,
+                        cK, cV, L.LRQK_FETCH_STAGED)
+    out = torch.empty((cfg.B, cfg.Hq, cfg.d), device=DEV)
+    L.lrqk_sparse_attend(shp, q, cK, cV, sb.sel_slot, dl.liteK, dl.liteV, out,
+                         workspace(L.lrqk_workspace_bytes(shp, L.LRQK_WS_ATTEND)))
+    res = sb.to_np()
+    res["out"] = out.cpu().numpy()
+    plan.close()
+    return res
+
+
+@pytest.mark.parametrize("mode", ["staged", "direct"])
+@pytest.mark.parametrize("kvd", ["bf16", "f32"])
+def test_decode_step_small(kvd, mode):
+    say(f"decode_step small kv={kvd} mode={mode}")
+    rates = run_steps_against_oracle(small_cfg(kv_dtype=kvd), 5, mode)
+    assert rates[0] == 1.0 and rates[-1] < 1.0
+
+
+@pytest.mark.parametrize("mode", ["staged", "direct"])
+def test_decode_step_full_selection_is_dense_attention(mode):
+    say(f"decode_step with k + w = l ({mode}): equals dense attention")
+    from helpers import dense_attention
+    cfg = small_cfg(B=1, Hq=4, Hkv=2, l=700, k=636, w=64, C=636, kv_dtype="f32")
+    data = make_layer(cfg)
+    dl = DeviceLayer(cfg, data)
+    plan = L.Plan(dl.shape)
+    q, q_hat = QueryStream(data).next()
+    out = torch.empty((cfg.B, cfg.Hq, cfg.d), device=DEV)
+    L.lrqk_decode_step(plan, dl.shape, 0, dl.struct(), q_hat.to(DEV), q.to(DEV), out,
+                       L.LRQK_FETCH_STAGED if mode == "staged" else L.LRQK_FETCH_DIRECT)
+    want = dense_attention(as_numpy(q), dl.np["K"], dl.np["V"], cfg.scale)
+    assert np.abs(out.cpu().numpy() - want).max() <= 1e-5
+    plan.close()
+
+
+def test_config1_all_hits():
+    say("config 1: l=4096 r=32 k=256 w=16, identity cache (all hits)")
+    cfg = get_config("c1")
+    rates = run_steps_against_oracle(cfg, 2, "staged", identity=True)
+    assert rates == [0.0, 0.0]
+
+
+@pytest.mark.parametrize("mode", ["staged", "direct"])
+def test_config2_shape(mode):
+    say(f"config 2: l=32768 k=1024 w=64 C=2048 ({mode})")
+    run_steps_against_oracle(get_config("c2"), 4, mode, check_unfused=False)
+
+
+@pytest.mark.parametrize("r", [16, 32, 64])
+def test_config3_one_layer_full_size(r):
+    say(f"config 3, one layer at full size: l=131072 k=2048 w=64 C=4096 r={r}")
+    run_steps_against_oracle(get_config("c3", r=r, layers=1), 3, "staged", check_unfused=False)
+
+
+def test_config4_qwen_shape_reduced_batch():
+    say("config 4 shape (28 q / 4 kv heads, G = 7), batch 2 of 8")
+    run_steps_against_oracle(get_config("c4", B=2), 3, "direct", check_unfused=False)
+
+
+def test_rerun_is_deterministic():
+    say("two runs of the same steps give identical bits")
+    cfg = small_cfg()
+    data = make_layer(cfg)
+    outs = []
+    for _ in range(2):
+        dl = DeviceLayer(cfg, data)
+        plan = L.Plan(dl.shape)
+        qs = QueryStream(data)
+        out = torch.empty((cfg.B, cfg.Hq, cfg.d), device=DEV)
+        acc = []
+        for step in range(3):
+            q, q_hat = qs.next()
+            L.lrqk_decode_step(plan, dl.shape, step, dl.struct(), q_hat.to(DEV), q.to(DEV), out,
+                               L.LRQK_FETCH_DIRECT)
+            acc.append(out.cpu().numpy().copy())
+        outs.append((np.stack(acc), dl.state_np()))
+        plan.close()
+    assert np.array_equal(outs[0][0].view(np.uint32), outs[1][0].view(np.uint32))
+    for name in ("slot_of", "token_of", "last_used", "cacheK", "cacheV"):
+        assert np.array_equal(outs[0][1][name], outs[1][1][name])
