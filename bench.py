@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the LRQK decode-step hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3] [--r 32]
+                    [--mode staged|direct] [--layers N] [--no-cpu-baseline]
+
+A *step* is one pass of the whole hot path (proxy scores -> top-k -> hit/miss ->
+fetch -> exact attention, i.e. one lrqk_decode_step call) for one layer.  The
+default workload is the 128K-context LLaMA-3-8B-shaped decode (32 layers, 32 query /
+8 KV heads, d = 128, l = 131072, r = 32, k = 2048, 64 lite tokens, 4096 cache slots per
+head, batch 1); consecutive steps walk through the 32 layers, so the data touched
+between two visits of a layer (> 5 GB) is far larger than any on-chip cache.  All
+inputs are seeded synthetic tensors already resident (A_K, caches in HBM; K/V store in
+pinned host memory) when the timed region starts.  The caches are primed with two
+untimed passes over all layers ("seeded from the previous steps' selections").
+
+Prints ONE JSON line: metric/value = layer-steps per second, plus
+  roofline      achieved HBM bandwidth of the dominant kernel (the proxy-score stream
+                over A_K) from HIP-event timing of that kernel alone on the same layers;
+  cpu_baseline  the plain CPU oracle timed on the host cores on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+# HBM traffic of one proxy-score launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
+# scaled by the same counters on a plain copy kernel; bytes per launch.  See profiles/.
+MEASURED_TRAFFIC = {}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--workload", default="c3")
+    ap.add_argument("--r", type=int, default=32)
+    ap.add_argument("--layers", type=int, default=None)
+    ap.add_argument("--mode", choices=["staged", "direct"], default="staged")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2510_23649_amd as L
+    from paper_2510_23649_amd import build as hip_build
+    from gen import get_config, make_layer, QueryStream, as_numpy
+
+    if not hip_build.is_built():
+        hip_build.build()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda"
+
+    cfg = get_config(args.workload, r=args.r)
+    if args.layers:
+        cfg = cfg.with_(layers=args.layers)
+    nl = cfg.layers
+    shape = L.Shape.make(B=cfg.B, Hq=cfg.Hq, Hkv=cfg.Hkv, l=cfg.l, r=cfg.r, k=cfg.k, w=cfg.w,
+                         C_slots=cfg.C, d=cfg.d, scale=cfg.scale,
+                         kv_dtype=L.LRQK_KV_BF16 if cfg.kv_dtype == "bf16" else L.LRQK_KV_F32)
+    mode = L.LRQK_FETCH_STAGED if args.mode == "staged" else L.LRQK_FETCH_DIRECT
+
+    def log(msg):
+        print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+    # ---------------------------------------------------------------- inputs (untimed)
+    t0 = time.time()
+    layers, streams = [], []
+    oracle_layer = None
+    for li in range(nl):
+        data = make_layer(cfg, li, device=dev)
+        layers.append(L.LayerBuffers(shape, data.A_K, data.K, data.V))
+        streams.append(QueryStream(data))
+        if li == 0 and not args.no_cpu_baseline:
+            oracle_layer = dict(A_K=as_numpy(data.A_K), K=as_numpy(data.K), V=as_numpy(data.V))
+        data.K = data.V = data.A_K = None
+        if li % 8 == 7:
+            log(f"generated {li + 1}/{nl} layers ({time.time() - t0:.1f}s)")
+    torch.cuda.synchronize()
+    plan = L.Plan(shape)
+    out = torch.empty((cfg.B, cfg.Hq, cfg.d), device=dev)
+    n_miss = torch.zeros((cfg.B, cfg.Hq), dtype=torch.int32, device=dev)
+    dbg = dict(n_miss=n_miss)
+    step_no = [0] * nl
+
+    def run_step(li, q, q_hat, debug=None):
+        step_no[li] += 1
+        return L.lrqk_decode_step(plan, shape, step_no[li], layers[li].struct, q_hat, q, out,
+                                  mode, debug)
+
+    # prime the caches: two untimed passes over all layers
+    oracle_queries = []
+    for p in range(2):
+        for li in range(nl):
+            q, q_hat = streams[li].next()
+            if li == 0:
+                oracle_queries.append((as_numpy(q), as_numpy(q_hat)))
+            run_step(li, q, q_hat)
+    torch.cuda.synchronize()
+    log(f"caches primed ({time.time() - t0:.1f}s)")
+
+    # queries of the warm-up and timed steps, resident before timing starts
+    n_pre = args.warmup + 2 * args.steps
+    queries = []
+    for i in range(n_pre):
+        q, q_hat = streams[i % nl].next()
+        queries.append((q, q_hat))
+    torch.cuda.synchronize()
+
+    # ---------------------------------------------------------------- timed region
+    for i in range(args.warmup):
+        run_step(i % nl, *queries[i])
+    torch.cuda.synchronize()
+    tot_miss = 0
+    t_start = time.perf_counter()
+    for i in range(args.warmup, args.warmup + args.steps):
+        tm = run_step(i % nl, *queries[i])
+        tot_miss += max(tm, 0)
+    torch.cuda.synchronize()
+    t_end = time.perf_counter()
+    elapsed = t_end - t_start
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = args.steps / elapsed
+    log(f"timed {args.steps} steps: {ms_per_step * 1e3:.1f} us/step")
+
+    # ---------------------------------------------------------------- per-phase breakdown
+    plan.profile(args.steps)
+    for i in range(args.warmup + args.steps, args.warmup + 2 * args.steps):
+        run_step(i % nl, *queries[i], debug=dbg)
+    phases_ms, n_prof = plan.profile_read()
+    plan.profile(0)
+    phases_us = {k: 1e3 * v / max(n_prof, 1) for k, v in phases_ms.items()}
+    torch.cuda.synchronize()
+    last_nmiss = n_miss.clamp(min=0).sum().item()
+    miss_rate = (tot_miss / (args.steps * cfg.B * cfg.Hq * cfg.k) if args.mode == "staged"
+                 else last_nmiss / (cfg.B * cfg.Hq * cfg.k))
+
+    # ---------------------------------------------------------------- dominant kernel alone
+    scores = torch.empty((cfg.B, cfg.Hq, cfg.l), device=dev)
+    for i in range(8):
+        L.lrqk_proxy_scores(shape, layers[i % nl].A_K, queries[i][1], scores)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n_k = max(args.steps, 64)
+    e0.record()
+    for i in range(n_k):
+        L.lrqk_proxy_scores(shape, layers[i % nl].A_K, queries[i % n_pre][1], scores)
+    e1.record()
+    torch.cuda.synchronize()
+    k1_us = 1e3 * e0.elapsed_time(e1) / n_k
+    a_k_bytes = cfg.B * cfg.Hkv * cfg.l * cfg.r * 4 + cfg.B * cfg.Hq * cfg.r * 4
+    k1_gbs = a_k_bytes / (k1_us * 1e-6) / 1e9
+
+    step_bytes = (a_k_bytes + 2 * 2 * cfg.d * (cfg.B * cfg.Hq * cfg.k + cfg.B * cfg.Hkv * cfg.w)
+                  + 2 * cfg.B * cfg.Hq * cfg.d * 4 + 2 * cfg.B * cfg.Hq * cfg.k * 4)
+    gpu_us = sum(phases_us.values())
+
+    # ---------------------------------------------------------------- CPU oracle baseline
+    cpu = None
+    if oracle_layer is not None:
+        from oracle import lrqk_oracle as orc
+        st = orc.CacheState(cfg.B, cfg.Hq, cfg.l, cfg.C)
+        cK = np.zeros((cfg.B, cfg.Hq, cfg.C, cfg.d), oracle_layer["K"].dtype)
+        cV = np.zeros_like(cK)
+        done, t_cpu = 0, 0.0
+        qi = 0
+        while t_cpu < args.cpu_seconds and done < 64:
+            qn, qhn = oracle_queries[qi % len(oracle_queries)]
+            qi += 1
+            tc = time.perf_counter()
+            orc.decode_step(oracle_layer["A_K"], qhn, qn, oracle_layer["K"], oracle_layer["V"], st,
+                            cK, cV, done + 1, cfg.k, cfg.w, cfg.scale)
+            t_cpu += time.perf_counter() - tc
+            done += 1
+        cpu = {"value": done / t_cpu, "unit": "layer-steps/s", "cores": orc.num_threads(),
+               "kind": "oracle",
+               "sample": f"{done} consecutive steps of layer 0 of the same workload "
+                         f"({t_cpu:.1f} s of CPU time, gcc -O2 + OpenMP over heads)"}
+
+    result = {
+        "metric": "LRQK decode steps/sec per layer at 128K ctx; achieved HBM GB/s vs peak",
+        "value": value, "unit": "layer-steps/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: LLaMA-3-8B-shaped decode, {nl} layers, "
+                               f"{cfg.Hq}q/{cfg.Hkv}kv heads, d={cfg.d}, l={cfg.l}, r={cfg.r}, "
+                               f"k={cfg.k}, w={cfg.w}, C={cfg.C}, batch {cfg.B}, bf16 K/V, "
+                               f"fp32 factors",
+                   "fetch_mode": args.mode, "step": "one layer's lrqk_decode_step",
+                   "layers_rotated": nl, "miss_rate": miss_rate},
+        "roofline": {"bound": "hbm", "achieved": k1_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": k1_gbs / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC.get(f"{cfg.name}_r{cfg.r}"),
+                     "kernel": "proxy_scores_kernel", "us_per_launch": k1_us,
+                     "algorithmic_bytes_per_launch": a_k_bytes},
+        "cpu_baseline": cpu,
+        "phases_us": phases_us,
+        "step_roofline": {"algorithmic_bytes_per_step": step_bytes,
+                          "gpu_us_per_step_sum_of_phases": gpu_us,
+                          "achieved_GBs_end_to_end": step_bytes / (ms_per_step * 1e-3) / 1e9,
+                          "frac_end_to_end": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+    }
+    plan.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -258,6 +258,21 @@ int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
                      int mode, const lrqk_step_debug* dbg, int64_t* total_miss_out,
                      void* stream);
 
+/*
+ * Instrumentation (not part of the method): per-phase GPU time of lrqk_decode_step,
+ * taken with HIP events recorded on the caller's stream around each phase.
+ * lrqk_plan_profile(plan, n) arms the next n calls of lrqk_decode_step on this plan
+ * (n = 0 switches it off); lrqk_plan_profile_read waits for the recorded steps, adds
+ * up the time between consecutive marks into ms_sum[LRQK_PROFILE_MARKS - 1]
+ * (milliseconds, summed over steps) and re-arms.  Intervals, in order:
+ *   0 proxy scores | 1 selection | 2 hit/miss resolution |
+ *   3 fetch kernel (DIRECT) or miss-list copy + host synchronisation (STAGED) |
+ *   4 attention partials (STAGED: includes the wait for the side-stream copy) | 5 merge
+ */
+#define LRQK_PROFILE_MARKS 7
+int lrqk_plan_profile(lrqk_plan* plan, int n_steps);
+int lrqk_plan_profile_read(lrqk_plan* plan, double* ms_sum, int* n_steps_out);
+
 #ifdef __cplusplus
 }
 #endif

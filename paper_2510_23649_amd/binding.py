@@ -79,6 +79,8 @@ def load_library():
                                         C.POINTER(C.c_int64), vp]),
         "lrqk_decode_step": (C.c_int, [vp, sp, i32, C.POINTER(Layer), vp, vp, vp, C.c_int,
                                        C.POINTER(_StepDebug), C.POINTER(C.c_int64), vp]),
+        "lrqk_plan_profile": (C.c_int, [vp, C.c_int]),
+        "lrqk_plan_profile_read": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int)]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)   # AttributeError if the library does not export it
@@ -90,7 +92,7 @@ def load_library():
 EXPORTS = ["lrqk_version", "lrqk_status_string", "lrqk_last_hip_error", "lrqk_validate_shape",
            "lrqk_workspace_bytes", "lrqk_proxy_scores", "lrqk_select_topk", "lrqk_cache_init",
            "lrqk_cache_resolve", "lrqk_sparse_attend", "lrqk_plan_create", "lrqk_plan_destroy",
-           "lrqk_fetch_misses", "lrqk_decode_step"]
+           "lrqk_fetch_misses", "lrqk_decode_step", "lrqk_plan_profile", "lrqk_plan_profile_read"]
 
 
 def _check(status: int, where: str):
@@ -187,6 +189,20 @@ class Plan:
         h = C.c_void_p()
         _check(load_library().lrqk_plan_create(C.byref(max_shape), C.byref(h)), "lrqk_plan_create")
         self.handle = h
+
+    PHASES = ("proxy_scores", "select_topk", "cache_resolve", "fetch_or_sync", "attend", "combine")
+
+    def profile(self, n_steps: int):
+        """lrqk_plan_profile: time the phases of the next n_steps fused steps (0 = off)."""
+        _check(load_library().lrqk_plan_profile(self.handle, int(n_steps)), "lrqk_plan_profile")
+
+    def profile_read(self):
+        """lrqk_plan_profile_read -> (dict phase -> summed ms, number of steps)."""
+        ms = (C.c_double * 6)()
+        n = C.c_int(0)
+        _check(load_library().lrqk_plan_profile_read(self.handle, ms, C.byref(n)),
+               "lrqk_plan_profile_read")
+        return dict(zip(self.PHASES, list(ms))), n.value
 
     def close(self):
         if getattr(self, "handle", None):

@@ -65,7 +65,26 @@ struct lrqk_plan {
   size_t stage_rows;
   hipStream_t side;
   hipEvent_t ev_main, ev_side;
+  // optional per-phase timing of lrqk_decode_step (lrqk_plan_profile)
+  int prof_cap, prof_n;
+  hipEvent_t* prof_ev;  // [prof_cap][LRQK_PROFILE_MARKS]
 };
+
+static void prof_free(lrqk_plan* p) {
+  if (p->prof_ev) {
+    for (int i = 0; i < p->prof_cap * LRQK_PROFILE_MARKS; ++i)
+      if (p->prof_ev[i]) (void)hipEventDestroy(p->prof_ev[i]);
+    std::free(p->prof_ev);
+  }
+  p->prof_ev = nullptr;
+  p->prof_cap = p->prof_n = 0;
+}
+
+// Record mark `m` of the current profiled step, if profiling is on and a slot is left.
+static inline hipError_t prof_mark(lrqk_plan* p, int m, hipStream_t st) {
+  if (!p->prof_ev || p->prof_n >= p->prof_cap) return hipSuccess;
+  return hipEventRecord(p->prof_ev[p->prof_n * LRQK_PROFILE_MARKS + m], st);
+}
 
 extern "C" {
 #pragma GCC visibility push(default)
@@ -112,7 +131,11 @@ int lrqk_select_topk(const lrqk_shape* shape, const float* scores, int32_t* sel_
   if (!all_aligned16({scores, sel_idx}) || !workspace || !aligned256(workspace)) return LRQK_EINVAL;
   const SelectWs ws = carve_select_ws(workspace, shape->B * shape->Hq, shape->k);
   if (ws_bytes < ws.bytes) return LRQK_ENOMEM;
-  LRQK_HIP(launch_select_topk(*shape, scores, sel_idx, ws, static_cast<hipStream_t>(stream)));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (select_resolve_fits(*shape, false))
+    LRQK_HIP(launch_select_only(*shape, scores, sel_idx, st));
+  else
+    LRQK_HIP(launch_select_topk(*shape, scores, sel_idx, ws, st));
   return LRQK_OK;
 }
 
@@ -178,6 +201,7 @@ int lrqk_plan_destroy(lrqk_plan* p) {
   void* host[] = {p->h_nmiss, p->h_miss_tok, p->h_miss_slot, p->h_stage, p->h_rowdst};
   for (void* q : host)
     if (q) (void)hipHostFree(q);
+  prof_free(p);
   if (p->ev_main) (void)hipEventDestroy(p->ev_main);
   if (p->ev_side) (void)hipEventDestroy(p->ev_side);
   if (p->side) (void)hipStreamDestroy(p->side);
@@ -351,20 +375,35 @@ int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
   if (!all_aligned16({sel_idx, sel_slot, hit, miss_tok, miss_slot, n_miss})) return LRQK_EINVAL;
 
   const SelectWs ws = carve_select_ws(plan->select_ws, BHq, s.k);
+  LRQK_HIP(prof_mark(plan, 0, st));
   LRQK_HIP(launch_proxy_scores(s, L->A_K, q_hat, plan->scores, st));
-  LRQK_HIP(launch_select_topk(s, plan->scores, sel_idx, ws, st));
-  LRQK_HIP(launch_cache_resolve(s, sel_idx, step, L->slot_of, L->token_of, L->last_used, sel_slot,
-                                hit, miss_tok, miss_slot, n_miss, st));
+  LRQK_HIP(prof_mark(plan, 1, st));
+  if (select_resolve_fits(s, true)) {
+    // selection and resolution in one launch; the profile books it all under "selection"
+    LRQK_HIP(launch_select_resolve(s, plan->scores, sel_idx, step, L->slot_of, L->token_of,
+                                   L->last_used, sel_slot, hit, miss_tok, miss_slot, n_miss, st));
+    LRQK_HIP(prof_mark(plan, 2, st));
+  } else {
+    LRQK_HIP(launch_select_topk(s, plan->scores, sel_idx, ws, st));
+    LRQK_HIP(prof_mark(plan, 2, st));
+    LRQK_HIP(launch_cache_resolve(s, sel_idx, step, L->slot_of, L->token_of, L->last_used,
+                                  sel_slot, hit, miss_tok, miss_slot, n_miss, st));
+  }
+  LRQK_HIP(prof_mark(plan, 3, st));
   const AttendGeom g = attend_geometry(BHq, s.k, s.w);
   const int parts_per_head = g.nsplit + ceil_div(s.k, g.rows_per_block);
 
   if (mode == LRQK_FETCH_DIRECT) {
     LRQK_HIP(launch_fetch_direct(s, L->K_host, L->V_host, miss_tok, miss_slot, n_miss, L->cacheK,
                                  L->cacheV, st));
+    LRQK_HIP(prof_mark(plan, 4, st));
     LRQK_HIP(launch_attend_partial(s, kAttendAll, q, L->cacheK, L->cacheV, sel_slot, nullptr,
                                    nullptr, nullptr, L->liteK, L->liteV, plan->partials, g.nsplit,
                                    g.rows_per_block, parts_per_head, 0, st));
+    LRQK_HIP(prof_mark(plan, 5, st));
     LRQK_HIP(launch_attend_combine(s, plan->partials, parts_per_head, g.nsplit, out, st));
+    LRQK_HIP(prof_mark(plan, 6, st));
+    if (plan->prof_ev && plan->prof_n < plan->prof_cap) ++plan->prof_n;
     if (total_miss_out) *total_miss_out = -1;
     return LRQK_OK;
   }
@@ -375,6 +414,7 @@ int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
   LRQK_HIP(hipMemcpyAsync(plan->h_miss_tok, miss_tok, nb * s.k * 4, hipMemcpyDeviceToHost, st));
   LRQK_HIP(hipMemcpyAsync(plan->h_miss_slot, miss_slot, nb * s.k * 4, hipMemcpyDeviceToHost, st));
   LRQK_HIP(hipStreamSynchronize(st));
+  LRQK_HIP(prof_mark(plan, 4, st));
   // ... attend the rows already resident and the lite rows while the host packs the misses
   LRQK_HIP(launch_attend_partial(s, kAttendHitsAndLite, q, L->cacheK, L->cacheV, sel_slot, hit,
                                  nullptr, nullptr, L->liteK, L->liteV, plan->partials, g.nsplit,
@@ -387,7 +427,39 @@ int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
   LRQK_HIP(launch_attend_partial(s, kAttendMisses, q, L->cacheK, L->cacheV, sel_slot, hit,
                                  miss_slot, n_miss, L->liteK, L->liteV, plan->partials, nblk_miss,
                                  g.rows_per_block, parts_per_head, g.nsplit, st));
+  LRQK_HIP(prof_mark(plan, 5, st));
   LRQK_HIP(launch_attend_combine(s, plan->partials, parts_per_head, g.nsplit + nblk_miss, out, st));
+  LRQK_HIP(prof_mark(plan, 6, st));
+  if (plan->prof_ev && plan->prof_n < plan->prof_cap) ++plan->prof_n;
+  return LRQK_OK;
+}
+
+int lrqk_plan_profile(lrqk_plan* plan, int n_steps) {
+  if (!plan || n_steps < 0 || n_steps > 65536) return LRQK_EINVAL;
+  prof_free(plan);
+  if (n_steps == 0) return LRQK_OK;
+  const size_t n = (size_t)n_steps * LRQK_PROFILE_MARKS;
+  plan->prof_ev = static_cast<hipEvent_t*>(std::calloc(n, sizeof(hipEvent_t)));
+  if (!plan->prof_ev) return LRQK_ENOMEM;
+  plan->prof_cap = n_steps;
+  for (size_t i = 0; i < n; ++i) LRQK_HIP(hipEventCreate(&plan->prof_ev[i]));
+  return LRQK_OK;
+}
+
+int lrqk_plan_profile_read(lrqk_plan* plan, double* ms_sum, int* n_steps_out) {
+  if (!plan || !ms_sum || !n_steps_out) return LRQK_EINVAL;
+  for (int m = 0; m < LRQK_PROFILE_MARKS - 1; ++m) ms_sum[m] = 0.0;
+  *n_steps_out = plan->prof_n;
+  for (int i = 0; i < plan->prof_n; ++i) {
+    hipEvent_t* ev = plan->prof_ev + (size_t)i * LRQK_PROFILE_MARKS;
+    LRQK_HIP(hipEventSynchronize(ev[LRQK_PROFILE_MARKS - 1]));
+    for (int m = 0; m < LRQK_PROFILE_MARKS - 1; ++m) {
+      float ms = 0.f;
+      LRQK_HIP(hipEventElapsedTime(&ms, ev[m], ev[m + 1]));
+      ms_sum[m] += ms;
+    }
+  }
+  plan->prof_n = 0;
   return LRQK_OK;
 }
 

@@ -63,6 +63,16 @@ hipError_t launch_proxy_scores(const lrqk_shape& s, const float* A_K, const floa
                                float* scores, hipStream_t st);
 hipError_t launch_select_topk(const lrqk_shape& s, const float* scores, int32_t* sel_idx,
                               const SelectWs& ws, hipStream_t st);
+// One workgroup per head, everything in LDS (select_resolve.hip); usable when the
+// bitmap of l bits and the other buffers fit (select_resolve_fits).
+bool select_resolve_fits(const lrqk_shape& s, bool resolve);
+hipError_t launch_select_only(const lrqk_shape& s, const float* scores, int32_t* sel_idx,
+                              hipStream_t st);
+hipError_t launch_select_resolve(const lrqk_shape& s, const float* scores, int32_t* sel_idx,
+                                 int32_t step, int32_t* slot_of, int32_t* token_of,
+                                 int32_t* last_used, int32_t* sel_slot, uint8_t* hit,
+                                 int32_t* miss_tok, int32_t* miss_slot, int32_t* n_miss,
+                                 hipStream_t st);
 hipError_t launch_cache_init(const lrqk_shape& s, int32_t* slot_of, int32_t* token_of,
                              int32_t* last_used, hipStream_t st);
 hipError_t launch_cache_resolve(const lrqk_shape& s, const int32_t* sel_idx, int32_t step,

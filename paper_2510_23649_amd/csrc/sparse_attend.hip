@@ -226,21 +226,66 @@ __global__ __launch_bounds__(kAttThreads) void attend_partial_kernel(
   }
 }
 
-__global__ __launch_bounds__(kD) void attend_combine_kernel(const float* __restrict__ partials,
-                                                            int parts_per_head, int nparts,
-                                                            float* __restrict__ out) {
-  const int bh = blockIdx.x, t = threadIdx.x;
+constexpr int kCombThreads = 512;
+constexpr int kCombMaxParts = 1024;
+
+// Merge the partial softmax states of one head.  The per-part weights are computed
+// once in LDS; four groups of 128 threads then walk the parts with independent,
+// coalesced loads (thread = output dimension) and are summed through LDS.
+__global__ __launch_bounds__(kCombThreads) void attend_combine_kernel(
+    const float* __restrict__ partials, int parts_per_head, int nparts,
+    float* __restrict__ out) {
+  __shared__ float wgt[kCombMaxParts];
+  __shared__ float red[kCombThreads / 64];
+  __shared__ float accs[kCombThreads / kD][kD];
+  __shared__ float sh_M, sh_S;
+  const int bh = blockIdx.x, t = threadIdx.x, lane = t & 63, wv = t >> 6;
   const float* __restrict__ P = partials + (size_t)bh * parts_per_head * kPartialStride;
-  float M = -INFINITY;
-  for (int p = 0; p < nparts; ++p) M = fmaxf(M, P[(size_t)p * kPartialStride]);
-  float a = 0.0f, s = 0.0f;
-  for (int p = 0; p < nparts; ++p) {
+  // block max of the part maxima
+  float m = -INFINITY;
+  for (int p = t; p < nparts; p += kCombThreads) m = fmaxf(m, P[(size_t)p * kPartialStride]);
+#pragma unroll
+  for (int d = 32; d > 0; d >>= 1) m = fmaxf(m, __shfl_xor(m, d));
+  if (lane == 0) red[wv] = m;
+  __syncthreads();
+  if (t == 0) {
+    float M = red[0];
+    for (int i = 1; i < kCombThreads / 64; ++i) M = fmaxf(M, red[i]);
+    sh_M = M;
+  }
+  __syncthreads();
+  const float M = sh_M;
+  float ssum = 0.0f;
+  for (int p = t; p < nparts; p += kCombThreads) {
     const float mp = P[(size_t)p * kPartialStride];
     const float g = (mp == -INFINITY) ? 0.0f : exp2f(mp - M);
-    a += P[(size_t)p * kPartialStride + 4 + t] * g;
-    s += P[(size_t)p * kPartialStride + 1] * g;
+    wgt[p] = g;
+    ssum += P[(size_t)p * kPartialStride + 1] * g;
   }
-  out[(size_t)bh * kD + t] = s > 0.0f ? a / s : 0.0f;
+#pragma unroll
+  for (int d = 32; d > 0; d >>= 1) ssum += __shfl_xor(ssum, d);
+  __syncthreads();
+  if (lane == 0) red[wv] = ssum;
+  __syncthreads();
+  if (t == 0) {
+    float S = 0.0f;
+    for (int i = 0; i < kCombThreads / 64; ++i) S += red[i];
+    sh_S = S;
+  }
+  const int dim = t & (kD - 1), grp = t / kD;
+  float a = 0.0f;
+#pragma unroll 8
+  for (int p = grp; p < nparts; p += kCombThreads / kD)
+    a = __builtin_fmaf(P[(size_t)p * kPartialStride + 4 + dim], wgt[p], a);
+  accs[grp][dim] = a;
+  __syncthreads();
+  if (t < kD) {
+    float tot = 0.0f;
+#pragma unroll
+    for (int g = 0; g < kCombThreads / kD; ++g) tot += accs[g][t];
+    const float S = sh_S;
+    out[(size_t)bh * kD + t] = S > 0.0f ? tot / S : 0.0f;
+  }
 }
 
 }  // namespace
@@ -285,8 +330,9 @@ hipError_t launch_attend_partial(const lrqk_shape& s, int mode, const float* q, 
 
 hipError_t launch_attend_combine(const lrqk_shape& s, const float* partials, int parts_per_head,
                                  int nparts, float* out, hipStream_t st) {
-  hipLaunchKernelGGL(attend_combine_kernel, dim3(s.B * s.Hq), dim3(kD), 0, st, partials,
-                     parts_per_head, nparts, out);
+  if (nparts > kCombMaxParts) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(attend_combine_kernel, dim3(s.B * s.Hq), dim3(kCombThreads), 0, st,
+                     partials, parts_per_head, nparts, out);
   return hipGetLastError();
 }
 

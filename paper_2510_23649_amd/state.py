@@ -1,0 +1,42 @@
+"""Allocation of one layer's buffers with torch (device memory, pinned host memory).
+
+Plumbing only: this module owns tensors and hands their pointers to the C ABI.
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as L
+
+
+class LayerBuffers:
+    """Device + pinned-host buffers of one layer, as lrqk_decode_step expects them.
+
+    A_K [B,Hkv,l,r] fp32 and K, V [B,Hkv,l,d] (bf16 or fp32) may live on any device;
+    A_K is moved to the GPU, K and V into pinned host memory, the last w rows of K
+    and V (the lite tokens) are also kept on the GPU.  The cache starts empty.
+    """
+
+    def __init__(self, shape: L.Shape, A_K: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
+                 device="cuda"):
+        self.shape = shape
+        B, Hq, Hkv, l, C, d, w = shape.B, shape.Hq, shape.Hkv, shape.l, shape.C, shape.d, shape.w
+        assert tuple(K.shape) == (B, Hkv, l, d) == tuple(V.shape)
+        self.A_K = A_K.to(device).contiguous()
+        self.K_host = torch.empty(K.shape, dtype=K.dtype, pin_memory=True)
+        self.V_host = torch.empty(V.shape, dtype=V.dtype, pin_memory=True)
+        self.K_host.copy_(K)
+        self.V_host.copy_(V)
+        self.liteK = K[:, :, l - w:, :].to(device).contiguous()
+        self.liteV = V[:, :, l - w:, :].to(device).contiguous()
+        i32 = dict(dtype=torch.int32, device=device)
+        self.slot_of = torch.empty((B, Hq, l), **i32)
+        self.token_of = torch.empty((B, Hq, C), **i32)
+        self.last_used = torch.empty((B, Hq, C), **i32)
+        self.cacheK = torch.zeros((B, Hq, C, d), dtype=K.dtype, device=device)
+        self.cacheV = torch.zeros((B, Hq, C, d), dtype=K.dtype, device=device)
+        L.lrqk_cache_init(shape, self.slot_of, self.token_of, self.last_used)
+        self.struct = L.make_layer(A_K=self.A_K, K_host=self.K_host, V_host=self.V_host,
+                                   liteK=self.liteK, liteV=self.liteV, slot_of=self.slot_of,
+                                   token_of=self.token_of, last_used=self.last_used,
+                                   cacheK=self.cacheK, cacheV=self.cacheV)

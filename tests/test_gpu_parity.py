@@ -71,6 +71,8 @@ def run_select(scores_np, k, w):
 @pytest.mark.parametrize("l,w,k,B,Hq", [
     (4096, 16, 256, 1, 8), (10000, 64, 1024, 2, 3), (70001, 64, 2048, 1, 4), (300, 0, 300, 1, 2),
     (257, 1, 1, 1, 2), (5000, 1000, 4000, 1, 2), (131072, 64, 2048, 1, 2), (4097, 0, 4096, 1, 1),
+    (524288, 64, 2048, 1, 2),      # largest power of two handled by the one-workgroup kernel
+    (800003, 64, 2048, 1, 2),      # beyond it: the multi-workgroup kernels
 ])
 def test_select_topk_random(l, w, k, B, Hq):
     say(f"select_topk random l={l} w={w} k={k} B={B} Hq={Hq}")
@@ -301,6 +303,12 @@ def test_decode_step_full_selection_is_dense_attention(mode):
     want = dense_attention(as_numpy(q), dl.np["K"], dl.np["V"], cfg.scale)
     assert np.abs(out.cpu().numpy() - want).max() <= 1e-5
     plan.close()
+
+
+def test_decode_step_very_long_context():
+    say("decode_step at l = 800000 (selection by the multi-workgroup kernels)")
+    cfg = small_cfg(B=1, Hq=2, Hkv=1, l=800000, r=8, k=512, w=64, C=1024, n_heavy=64)
+    run_steps_against_oracle(cfg, 3, "direct", check_unfused=False)
 
 
 def test_config1_all_hits():
