@@ -45,7 +45,7 @@ def main():
     ap.add_argument("--workload", default="c3")
     ap.add_argument("--r", type=int, default=32)
     ap.add_argument("--layers", type=int, default=None)
-    ap.add_argument("--mode", choices=["staged", "direct"], default="staged")
+    ap.add_argument("--mode", choices=["staged", "direct"], default="direct")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
