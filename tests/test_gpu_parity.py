@@ -99,6 +99,27 @@ def test_select_topk_ties_zeros_and_massive_duplicates():
     assert np.array_equal(got[0, 1], np.arange(k))
 
 
+def test_select_topk_sampled_estimate_is_verified_not_trusted():
+    say("select_topk, long heads: inputs built to mislead the 1-in-8 sample, and heavy ties")
+    rng = np.random.default_rng(9)
+    l, w, k = 150000, 64, 2048
+    e = np.arange(l)
+    sampled = ((e // 4096) & 7) == (((e % 4096) // 256) & 7)     # positions the first pass looks at
+    s = np.empty((1, 8, l), np.float32)
+    base = (rng.standard_normal(l) * 11.3).astype(np.float32)
+    s[0, 0] = np.where(sampled, -1.0, base)                      # sample sees one value only
+    s[0, 1] = np.where(sampled, base + 200.0, base)              # sample far above the rest
+    s[0, 2] = np.where(sampled, base - 200.0, base)              # sample far below the rest
+    s[0, 3] = 7.5                                                # every score equal
+    s[0, 4] = np.round(base)                                     # heavy ties around the threshold
+    s[0, 5] = np.where(rng.random(l) < 0.01, 1e3, -1e3)          # 1500 large, rest equal: k cuts the ties
+    s[0, 6] = base
+    s[0, 6, :3000] = 1e4                                         # more than k at the top, all tied
+    s[0, 7] = -np.abs(base) - 1.0
+    got = run_select(s, k, w)
+    assert np.array_equal(got, orc.select_topk(s, k, w))
+
+
 # ------------------------------------------------------------------------------- a3 + a4
 
 @pytest.mark.parametrize("mode", ["staged", "direct"])
