@@ -179,7 +179,7 @@ def main():
         cV = np.zeros_like(cK)
         done, t_cpu = 0, 0.0
         qi = 0
-        while t_cpu < args.cpu_seconds and done < 64:
+        while t_cpu < args.cpu_seconds and done < 2048:
             qn, qhn = oracle_queries[qi % len(oracle_queries)]
             qi += 1
             tc = time.perf_counter()
