@@ -50,6 +50,9 @@ struct lrqk_plan {
   int BHq;
   // device
   float* scores;
+  uint32_t* thr;               // [BHq] sampled threshold bin of each head
+  float* samples;              // [BHq][kThrMaxSamples] sample scores behind thr
+  unsigned long long* filter;  // [BHq][words64] candidate bitmap from the proxy-score pass
   void* select_ws;
   size_t select_bytes;
   float* partials;
@@ -194,7 +197,7 @@ int lrqk_plan_destroy(lrqk_plan* p) {
   (void)hipGetDevice(&prev);
   (void)hipSetDevice(p->device);
   if (p->side) (void)hipStreamSynchronize(p->side);
-  void* dev[] = {p->scores, p->select_ws, p->partials, p->sel_idx, p->sel_slot, p->miss_tok,
+  void* dev[] = {p->scores, p->thr, p->samples, p->filter, p->select_ws, p->partials, p->sel_idx, p->sel_slot, p->miss_tok,
                  p->miss_slot, p->n_miss, p->hit, p->d_stage, p->d_rowdst};
   for (void* q : dev)
     if (q) (void)hipFree(q);
@@ -234,6 +237,9 @@ int lrqk_plan_create(const lrqk_shape* max_shape, lrqk_plan** plan_out) {
     if (e == hipSuccess) e = hipHostMalloc(q, bytes ? bytes : 256, hipHostMallocDefault);
   };
   dmalloc((void**)&p->scores, BHq * s.l * sizeof(float));
+  dmalloc((void**)&p->thr, BHq * 4);
+  dmalloc((void**)&p->samples, BHq * (size_t)kThrMaxSamples * 4);
+  dmalloc((void**)&p->filter, BHq * (size_t)filter_words64(s.l) * 8);
   dmalloc(&p->select_ws, p->select_bytes);
   dmalloc((void**)&p->partials, p->partial_bytes);
   dmalloc((void**)&p->sel_idx, BHq * s.k * 4);
@@ -376,12 +382,22 @@ int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
 
   const SelectWs ws = carve_select_ws(plan->select_ws, BHq, s.k);
   LRQK_HIP(prof_mark(plan, 0, st));
-  LRQK_HIP(launch_proxy_scores(s, L->A_K, q_hat, plan->scores, st));
+  const bool one_wg = select_resolve_fits(s, true);
+  const bool filtered = one_wg && proxy_filter_supported(s);
+  if (filtered) {
+    // sampled threshold, then scores + candidate bitmap in one pass over A_K
+    LRQK_HIP(launch_proxy_threshold(s, L->A_K, q_hat, plan->samples, plan->thr, st));
+    LRQK_HIP(launch_proxy_scores_filter(s, L->A_K, q_hat, plan->scores, plan->thr, plan->filter,
+                                        st));
+  } else {
+    LRQK_HIP(launch_proxy_scores(s, L->A_K, q_hat, plan->scores, st));
+  }
   LRQK_HIP(prof_mark(plan, 1, st));
-  if (select_resolve_fits(s, true)) {
+  if (one_wg) {
     // selection and resolution in one launch; the profile books it all under "selection"
-    LRQK_HIP(launch_select_resolve(s, plan->scores, sel_idx, step, L->slot_of, L->token_of,
-                                   L->last_used, sel_slot, hit, miss_tok, miss_slot, n_miss, st));
+    LRQK_HIP(launch_select_resolve(s, plan->scores, filtered ? plan->filter : nullptr, sel_idx,
+                                   step, L->slot_of, L->token_of, L->last_used, sel_slot, hit,
+                                   miss_tok, miss_slot, n_miss, st));
     LRQK_HIP(prof_mark(plan, 2, st));
   } else {
     LRQK_HIP(launch_select_topk(s, plan->scores, sel_idx, ws, st));

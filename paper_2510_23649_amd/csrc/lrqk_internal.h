@@ -61,6 +61,17 @@ size_t attend_ws_bytes(int BHq, int k, int w, int phases);
 // ---- kernel launchers (each validates nothing; callers have done so) -------------------
 hipError_t launch_proxy_scores(const lrqk_shape& s, const float* A_K, const float* q_hat,
                                float* scores, hipStream_t st);
+// Filtered variant of the proxy-score pass (fast shapes only): a sampled threshold bin per
+// head, then scores plus a bitmap of the positions at or above that bin.
+inline int filter_words64(int n) { return (n + 63) / 64; }
+bool proxy_filter_supported(const lrqk_shape& s);
+constexpr int kThrMaxSamples = 8192;  // sample scores kept per head
+// samples: [BHq][kThrMaxSamples] floats
+hipError_t launch_proxy_threshold(const lrqk_shape& s, const float* A_K, const float* q_hat,
+                                  float* samples, uint32_t* thr, hipStream_t st);
+hipError_t launch_proxy_scores_filter(const lrqk_shape& s, const float* A_K, const float* q_hat,
+                                      float* scores, const uint32_t* thr,
+                                      unsigned long long* bitmap, hipStream_t st);
 hipError_t launch_select_topk(const lrqk_shape& s, const float* scores, int32_t* sel_idx,
                               const SelectWs& ws, hipStream_t st);
 // One workgroup per head, everything in LDS (select_resolve.hip); usable when the
@@ -68,7 +79,10 @@ hipError_t launch_select_topk(const lrqk_shape& s, const float* scores, int32_t*
 bool select_resolve_fits(const lrqk_shape& s, bool resolve);
 hipError_t launch_select_only(const lrqk_shape& s, const float* scores, int32_t* sel_idx,
                               hipStream_t st);
-hipError_t launch_select_resolve(const lrqk_shape& s, const float* scores, int32_t* sel_idx,
+// ext_bitmap: candidate bitmap written by the filtered proxy-score pass ([BHq][words64]
+// 64-bit words), or nullptr to let the kernel derive its own from the scores.
+hipError_t launch_select_resolve(const lrqk_shape& s, const float* scores,
+                                 const unsigned long long* ext_bitmap, int32_t* sel_idx,
                                  int32_t step, int32_t* slot_of, int32_t* token_of,
                                  int32_t* last_used, int32_t* sel_slot, uint8_t* hit,
                                  int32_t* miss_tok, int32_t* miss_slot, int32_t* n_miss,

@@ -18,6 +18,7 @@
 // load -> LDS -> compute chain of each other; measured on MI355X this beats fewer
 // workgroups that loop over tiles with a register prefetch.
 // The chain order (j ascending from 0.0f) makes the scores bit-reproducible.
+#include "lrqk_device.h"
 #include "lrqk_internal.h"
 
 namespace lrqk {
@@ -31,10 +32,14 @@ __device__ __forceinline__ float4 load_streaming(const float4* p) {
   return make_float4(x.x, x.y, x.z, x.w);
 }
 
-template <int R, int G>
+// FILTER: besides the scores, emit for every head a bitmap of the positions in [0, n)
+// whose order key is >= thr[head]: one 64-bit ballot per wavefront and head, no
+// atomics.  The selection kernel starts from that bitmap.
+template <int R, int G, bool FILTER>
 __global__ __launch_bounds__(kTileRows) void proxy_scores_kernel(
     const float* __restrict__ A_K, const float* __restrict__ q_hat, float* __restrict__ scores,
-    int l, int Hq, int Hkv) {
+    int l, int Hq, int Hkv, int n, const uint32_t* __restrict__ thr,
+    unsigned long long* __restrict__ bitmap, int words64) {
   constexpr int V4 = R / 4;       // 16-byte chunks per row
   constexpr int ROW4 = V4 + 1;    // padded LDS row stride in 16-byte units
   __shared__ float4 tile[kTileRows * ROW4];
@@ -81,6 +86,127 @@ __global__ __launch_bounds__(kTileRows) void proxy_scores_kernel(
 #pragma unroll
     for (int g = 0; g < G; ++g) sc[(size_t)g * l + row] = acc[g];
   }
+  if (FILTER) {
+    const int wrow = row0 + (t & ~63);  // first row of this wavefront
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const size_t bh = (size_t)b * Hq + (size_t)kv * G + g;
+      const bool in = row < n && dev::order_key(acc[g]) >= thr[bh];
+      const unsigned long long mask = __ballot(in);
+      if ((t & 63) == 0 && wrow < n) bitmap[bh * words64 + (wrow >> 6)] = mask;
+    }
+  }
+}
+
+// Sampled estimate of the selection threshold of every head, before the scores exist.
+// Kernel 1: the proxy score of every SS-th row, kThrParts workgroups per (batch, query
+// head): 8 lanes share a row (one 16-byte chunk each, partial sums added across the
+// lanes -- the estimate does not need the exact rounding of the full pass), several rows'
+// loads in flight per lane; the sample scores go to a small buffer.
+// Kernel 2: one workgroup per head histograms the head's sample keys (top 12 bits, then
+// 6 more inside the bin found) and writes the key below which a position is not expected
+// among the k largest, with a margin of six standard deviations of the sample count
+// (SS = 1 for short contexts: every row is sampled).
+// The estimate only decides how many candidates the selection kernel gets; that kernel
+// checks the count and derives everything exactly.  (Two launches rather than one with
+// a "last workgroup" hand-over: the device-wide fences that hand-over needs cost far
+// more on this chip than a launch.)
+constexpr int kThrThreads = 1024;
+constexpr int kThrParts = 8;
+constexpr int kThrRowsPerIter = kThrThreads / 8;
+constexpr int kThrBatch = 4;
+
+__device__ __forceinline__ float sum8(float v) {
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, false));
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xf, 0xf, false));
+  v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xf, 0xf, false));
+  return v;
+}
+
+__global__ __launch_bounds__(kThrThreads) void proxy_sample_kernel(
+    const float* __restrict__ A_K, const float* __restrict__ q_hat, int l, int r, int Hq, int Hkv,
+    int SS, int ns, int parts, float* __restrict__ samples) {
+  const int bh = blockIdx.y, part = blockIdx.x, t = threadIdx.x;
+  const int b = bh / Hq, h = bh - b * Hq, kv = h / (Hq / Hkv);
+  const float* __restrict__ A = A_K + ((size_t)b * Hkv + kv) * (size_t)l * r;
+  const float* __restrict__ qh = q_hat + (size_t)bh * r;
+  float* __restrict__ smp = samples + (size_t)bh * kThrMaxSamples;
+  const int off = SS >> 1;
+  const int V4 = r / 4;
+  const int c = t & 7, rg = t >> 3;
+  // this lane's chunks of q_hat: c, c+8, c+16, c+24 (r <= 128)
+  float4 qv[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    qv[u] = (c + 8 * u < V4) ? reinterpret_cast<const float4*>(qh)[c + 8 * u]
+                             : make_float4(0.f, 0.f, 0.f, 0.f);
+  const int per_part = (ns + parts - 1) / parts;
+  const int j_begin = part * per_part, j_end = min(ns, j_begin + per_part);
+  for (int j0 = j_begin; j0 < j_end; j0 += kThrRowsPerIter * kThrBatch) {
+    float part_sum[kThrBatch];
+#pragma unroll
+    for (int u = 0; u < kThrBatch; ++u) {
+      const int j = j0 + u * kThrRowsPerIter + rg;
+      float acc = 0.0f;
+      if (j < j_end) {
+        const float4* __restrict__ row =
+            reinterpret_cast<const float4*>(A + ((size_t)off + (size_t)j * SS) * r);
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          if (c + 8 * v < V4) {
+            const float4 a = row[c + 8 * v];
+            acc = __builtin_fmaf(a.x, qv[v].x, acc);
+            acc = __builtin_fmaf(a.y, qv[v].y, acc);
+            acc = __builtin_fmaf(a.z, qv[v].z, acc);
+            acc = __builtin_fmaf(a.w, qv[v].w, acc);
+          }
+      }
+      part_sum[u] = acc;
+    }
+#pragma unroll
+    for (int u = 0; u < kThrBatch; ++u) {
+      const float sc = sum8(part_sum[u]);
+      const int j = j0 + u * kThrRowsPerIter + rg;
+      if (c == 0 && j < j_end) smp[j] = sc;
+    }
+  }
+}
+
+__global__ __launch_bounds__(kThrThreads) void proxy_threshold_kernel(
+    const float* __restrict__ samples, int n, int k, int SS, int ns, uint32_t* __restrict__ thr) {
+  __shared__ uint32_t hist[kBins];
+  __shared__ uint32_t wave_tot[16];
+  __shared__ uint32_t res[4];
+  const int bh = blockIdx.x, t = threadIdx.x;
+  const float* __restrict__ smp = samples + (size_t)bh * kThrMaxSamples;
+  for (int i = t; i < kBins; i += kThrThreads) hist[i] = 0u;
+  __syncthreads();
+  for (int j = t; j < ns; j += kThrThreads) {
+    const float sc = smp[j];
+    atomicAdd(&hist[dev::order_key(sc) >> kBinShift], 1u);
+  }
+  __syncthreads();
+  uint32_t want = (uint32_t)k;
+  if (SS > 1) {
+    const uint32_t ks = (uint32_t)(((long long)k * ns + n - 1) / n);  // expected hits in the sample
+    uint32_t sq = 1;
+    while (sq * sq < ks) ++sq;
+    want = ks + 6 * sq + 4;
+  }
+  uint32_t bin, above;
+  dev::find_from_top_4096(hist, want, wave_tot, res, &bin, &above);
+  // refine inside that bin with the next 6 key bits, so that the cut does not overshoot
+  // by a whole 12-bit bin
+  for (int i = t; i < 2048; i += kThrThreads) hist[i] = 0u;
+  __syncthreads();
+  for (int j = t; j < ns; j += kThrThreads) {
+    const uint32_t key = dev::order_key(smp[j]);
+    if ((key >> kBinShift) == bin) atomicAdd(&hist[(key >> 14) & 63u], 1u);
+  }
+  __syncthreads();
+  dev::find_from_top(hist, want > above ? want - above : 1u, wave_tot, res);
+  const uint32_t sub = res[0] == 0xffffffffu ? 0u : res[0];
+  if (t == 0) thr[bh] = (bin << kBinShift) | (sub << 14);
 }
 
 // Any r (multiple of 4, <= 128) and any G <= 8: tiles of 64 rows; the four
@@ -128,37 +254,81 @@ __global__ __launch_bounds__(256) void proxy_scores_generic_kernel(
 
 template <int R, int G>
 hipError_t launch_fast(const lrqk_shape& s, const float* A_K, const float* q_hat, float* scores,
-                       hipStream_t st) {
+                       const uint32_t* thr, unsigned long long* bitmap, hipStream_t st) {
   dim3 grid(ceil_div(s.l, kTileRows), s.B * s.Hkv);
-  hipLaunchKernelGGL((proxy_scores_kernel<R, G>), grid, dim3(kTileRows), 0, st, A_K, q_hat,
-                     scores, s.l, s.Hq, s.Hkv);
+  const int n = s.l - s.w;
+  if (thr)
+    hipLaunchKernelGGL((proxy_scores_kernel<R, G, true>), grid, dim3(kTileRows), 0, st, A_K,
+                       q_hat, scores, s.l, s.Hq, s.Hkv, n, thr, bitmap, filter_words64(n));
+  else
+    hipLaunchKernelGGL((proxy_scores_kernel<R, G, false>), grid, dim3(kTileRows), 0, st, A_K,
+                       q_hat, scores, s.l, s.Hq, s.Hkv, n, nullptr, nullptr, 0);
   return hipGetLastError();
 }
 
 template <int R>
 hipError_t dispatch_G(const lrqk_shape& s, const float* A_K, const float* q_hat, float* scores,
-                      hipStream_t st, bool* handled) {
+                      const uint32_t* thr, unsigned long long* bitmap, hipStream_t st,
+                      bool* handled) {
   *handled = true;
   switch (s.Hq / s.Hkv) {
-    case 1: return launch_fast<R, 1>(s, A_K, q_hat, scores, st);
-    case 2: return launch_fast<R, 2>(s, A_K, q_hat, scores, st);
-    case 4: return launch_fast<R, 4>(s, A_K, q_hat, scores, st);
-    case 7: return launch_fast<R, 7>(s, A_K, q_hat, scores, st);
-    case 8: return launch_fast<R, 8>(s, A_K, q_hat, scores, st);
+    case 1: return launch_fast<R, 1>(s, A_K, q_hat, scores, thr, bitmap, st);
+    case 2: return launch_fast<R, 2>(s, A_K, q_hat, scores, thr, bitmap, st);
+    case 4: return launch_fast<R, 4>(s, A_K, q_hat, scores, thr, bitmap, st);
+    case 7: return launch_fast<R, 7>(s, A_K, q_hat, scores, thr, bitmap, st);
+    case 8: return launch_fast<R, 8>(s, A_K, q_hat, scores, thr, bitmap, st);
     default: *handled = false; return hipSuccess;
   }
 }
 
 }  // namespace
 
+bool proxy_filter_supported(const lrqk_shape& s) {
+  const int G = s.Hq / s.Hkv;
+  return (s.r == 16 || s.r == 32 || s.r == 64) && (G == 1 || G == 2 || G == 4 || G == 7 || G == 8);
+}
+
+hipError_t launch_proxy_threshold(const lrqk_shape& s, const float* A_K, const float* q_hat,
+                                  float* samples, uint32_t* thr, hipStream_t st) {
+  const int n = s.l - s.w;
+  int SS = 1;  // every SS-th row, about 4096 samples per head once the context is long enough
+  while (SS < 256 && n / (SS * 2) >= 2048) SS *= 2;
+  if (n / SS >= kThrMaxSamples) SS *= 2;  // very long contexts: stay inside the sample buffer
+  while (n / SS >= kThrMaxSamples) SS *= 2;
+  const int off = SS >> 1;
+  const int ns = n > off ? (n - off + SS - 1) / SS : 0;
+  int parts = ceil_div(ns, 512);
+  if (parts > kThrParts) parts = kThrParts;
+  if (parts < 1) parts = 1;
+  hipLaunchKernelGGL(proxy_sample_kernel, dim3(parts, s.B * s.Hq), dim3(kThrThreads), 0, st, A_K,
+                     q_hat, s.l, s.r, s.Hq, s.Hkv, SS, ns, parts, samples);
+  hipLaunchKernelGGL(proxy_threshold_kernel, dim3(s.B * s.Hq), dim3(kThrThreads), 0, st, samples,
+                     n, s.k, SS, ns, thr);
+  return hipGetLastError();
+}
+
+hipError_t launch_proxy_scores_filter(const lrqk_shape& s, const float* A_K, const float* q_hat,
+                                      float* scores, const uint32_t* thr,
+                                      unsigned long long* bitmap, hipStream_t st) {
+  bool handled = false;
+  hipError_t e = hipErrorInvalidValue;
+  switch (s.r) {
+    case 16: e = dispatch_G<16>(s, A_K, q_hat, scores, thr, bitmap, st, &handled); break;
+    case 32: e = dispatch_G<32>(s, A_K, q_hat, scores, thr, bitmap, st, &handled); break;
+    case 64: e = dispatch_G<64>(s, A_K, q_hat, scores, thr, bitmap, st, &handled); break;
+    default: break;
+  }
+  return handled ? e : hipErrorInvalidValue;
+}
+
 hipError_t launch_proxy_scores(const lrqk_shape& s, const float* A_K, const float* q_hat,
                                float* scores, hipStream_t st) {
   bool handled = false;
   hipError_t e = hipSuccess;
   switch (s.r) {
-    case 16: e = dispatch_G<16>(s, A_K, q_hat, scores, st, &handled); break;
-    case 32: e = dispatch_G<32>(s, A_K, q_hat, scores, st, &handled); break;
-    case 64: e = dispatch_G<64>(s, A_K, q_hat, scores, st, &handled); break;
+    case 16: e = dispatch_G<16>(s, A_K, q_hat, scores, nullptr, nullptr, st, &handled); break;
+    case 32: e = dispatch_G<32>(s, A_K, q_hat, scores, nullptr, nullptr, st, &handled); break;
+    case 64: e = dispatch_G<64>(s, A_K, q_hat, scores, nullptr, nullptr, st, &handled); break;
     default: break;
   }
   if (handled) return e;

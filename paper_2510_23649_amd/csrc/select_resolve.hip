@@ -31,6 +31,7 @@
 //
 // All decisions are integer comparisons: the result is exact and independent of
 // scheduling.
+#include "lrqk_device.h"
 #include "lrqk_internal.h"
 
 #ifdef LRQK_KPROF
@@ -51,59 +52,14 @@ extern "C" __attribute__((visibility("default"))) int lrqk_kprof_read(unsigned l
 namespace lrqk {
 namespace {
 
+using namespace dev;
+
 constexpr int kT = 1024;  // threads per workgroup
 constexpr int kWaves = kT / 64;
 constexpr int kIter = kT * 4;  // scores per workgroup iteration (one float4 per lane)
 constexpr int kBatch = 8;      // iterations whose loads are issued together
 constexpr int kAgeBins = 2048;
 constexpr int kSampleStride = 8;
-
-__device__ __forceinline__ uint32_t order_key(float s) {
-  uint32_t u = __float_as_uint(s);
-  if (u == 0x80000000u) u = 0u;  // -0.0f ranks with +0.0f
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-
-template <int CTRL>
-__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
-  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, false);
-}
-// OR over aligned groups of 8 lanes; every lane of the group gets the result
-__device__ __forceinline__ uint32_t or_reduce8(uint32_t v) {
-  v |= dpp_u32<0xB1>(v);   // quad_perm [1,0,3,2]
-  v |= dpp_u32<0x4E>(v);   // quad_perm [2,3,0,1]
-  v |= dpp_u32<0x141>(v);  // row_half_mirror: lane i <-> 7-i within 8 lanes
-  return v;
-}
-
-__device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
-  const int lane = threadIdx.x & 63;
-#pragma unroll
-  for (int d = 1; d < 64; d <<= 1) {
-    const uint32_t n = __shfl_up(v, d);
-    if (lane >= d) v += n;
-  }
-  return v;
-}
-
-// Exclusive prefix sum of v over the kT threads (thread order) and the block total.
-__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t* wave_tot,
-                                                         uint32_t* total) {
-  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const uint32_t incl = wave_inclusive_scan(v);
-  __syncthreads();  // wave_tot may still be read from an earlier call
-  if (lane == 63) wave_tot[wv] = incl;
-  __syncthreads();
-  uint32_t before = 0, tot = 0;
-#pragma unroll
-  for (int i = 0; i < kWaves; ++i) {
-    const uint32_t c = wave_tot[i];
-    before += i < wv ? c : 0u;
-    tot += c;
-  }
-  *total = tot;
-  return before + incl - v;
-}
 
 struct Keys4 {
   uint32_t k[4];
@@ -155,33 +111,6 @@ __device__ __forceinline__ void bitonic_sort_lds(T* a, int n) {
   __syncthreads();
 }
 
-// Scan a histogram of nbins = 2 * kT bins from the top: the bin d with
-// (count in bins above d) < want <= (count in bins >= d).  Thread t owns bins 2t, 2t+1.
-// Results through res[0] = d, res[1] = count above d, res[2] = total.  If the total is
-// smaller than `want`, res[0] stays 0xffffffff.
-__device__ __forceinline__ void find_from_top(const uint32_t* hist, uint32_t want,
-                                              uint32_t* wave_tot, uint32_t* res) {
-  const int t = threadIdx.x;
-  const uint32_t c0 = hist[2 * t], c1 = hist[2 * t + 1];
-  uint32_t total;
-  const uint32_t below = block_exclusive_scan(c0 + c1, wave_tot, &total);
-  if (t == 0) {
-    res[0] = 0xffffffffu;
-    res[2] = total;
-  }
-  __syncthreads();
-  const uint32_t above1 = total - below - c0 - c1;  // above bin 2t+1
-  const uint32_t above0 = above1 + c1;              // above bin 2t
-  if (above1 < want && want <= above1 + c1) {
-    res[0] = 2 * t + 1;
-    res[1] = above1;
-  } else if (above0 < want && want <= above0 + c0) {
-    res[0] = 2 * t;
-    res[1] = above0;
-  }
-  __syncthreads();
-}
-
 __host__ __device__ inline int cand_capacity(int k) {
   int c = 2 * k + 2048;
   if (c < 4096) c = 4096;
@@ -213,7 +142,8 @@ __host__ __device__ inline ArenaSizes arena_sizes(int k, int n, int C, bool reso
 
 template <bool RESOLVE>
 __global__ __launch_bounds__(kT) void select_resolve_kernel(
-    const float* __restrict__ scores, int l, int n, int k, int32_t* __restrict__ sel_idx,
+    const float* __restrict__ scores, const uint32_t* __restrict__ ext_bitmap, int ext_words,
+    int l, int n, int k, int32_t* __restrict__ sel_idx,
     // resolution (unused when !RESOLVE)
     int32_t step, int C, int32_t* __restrict__ slot_of, int32_t* __restrict__ token_of,
     int32_t* __restrict__ last_used, int32_t* __restrict__ sel_slot, uint8_t* __restrict__ hit,
@@ -241,14 +171,20 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
   const int words = (n + 31) / 32;
   const int wpt = (words + kT - 1) / kT;  // bitmap words per thread in the prefix counts
 
-  KPROF(0);
-  // ---- 1. sampled histogram -> b_lo ------------------------------------------------------
-  const int stride = (n >= 65536 && k >= 512) ? kSampleStride : 1;
-  for (int i = t; i < kBins; i += kT) hist[i] = 0u;
   if (t == 0) {
     sh_nmiss = 0u;
     sh_bad = 0u;
   }
+  KPROF(0);
+  if (ext_bitmap != nullptr) {
+    // the proxy-score pass already marked the candidates of this head
+    const uint32_t* __restrict__ eb = ext_bitmap + (size_t)bh * ext_words;
+    for (int i = t; i < words; i += kT) bitmap[i] = eb[i];
+    __syncthreads();
+  } else {
+  // ---- 1. sampled histogram -> b_lo ------------------------------------------------------
+  const int stride = (n >= 65536 && k >= 512) ? kSampleStride : 1;
+  for (int i = t; i < kBins; i += kT) hist[i] = 0u;
   __syncthreads();
   if (stride == 1) {
     for (int it0 = 0; it0 < n_iter; it0 += kBatch) {
@@ -284,22 +220,9 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
   {
     const uint32_t ks = (uint32_t)(k + stride - 1) / stride;
     const uint32_t want = stride == 1 ? (uint32_t)k : ks + (ks * 3) / 8 + 16;
-    // 4096 bins = 2 halves of 2048: scan the upper half first, then the lower one
-    find_from_top(hist + 2048, want, wave_tot, res);
-    uint32_t d = res[0];
-    const uint32_t upper_total = res[2];
-    __syncthreads();
-    if (d != 0xffffffffu) {
-      b_lo = 2048 + d;
-    } else {
-      find_from_top(hist, want - upper_total, wave_tot, res);
-      d = res[0];
-      b_lo = d == 0xffffffffu ? 0u : d;
-      __syncthreads();
-    }
+    uint32_t above_unused;
+    find_from_top_4096(hist, want, wave_tot, res, &b_lo, &above_unused);
   }
-
-  KPROF(1);
   // ---- 2. bitmap of the positions with bin >= b_lo ----------------------------------------
   for (int it0 = 0; it0 < n_iter; it0 += kBatch) {
     Raw4 raw[kBatch];
@@ -320,7 +243,8 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
   }
   __syncthreads();
 
-  KPROF(2);
+  }
+  KPROF(1);
   // ---- 3. candidates -> exact selection -----------------------------------------------------
   uint32_t m;
   {
@@ -341,43 +265,53 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
     }
   }
   __syncthreads();
+  KPROF(2);
   if (m >= (uint32_t)k && m <= (uint32_t)cap) {
+    for (int i = t; i < kBins; i += kT) hist[i] = 0u;
     for (uint32_t i = t; i < m; i += kT) ckey[i] = order_key(s[clist[i]]);
+    __syncthreads();
+  KPROF(3);
     // exact key of the k-th largest candidate: digits [31:21], [20:10], [9:0]
     uint32_t prefix = 0, remaining = (uint32_t)k;
+    uint32_t n_eq_total = 0;
 #pragma unroll
     for (int level = 0; level < 3; ++level) {
       const int shift = level == 0 ? 21 : (level == 1 ? 10 : 0);
       const int bits = level == 2 ? 10 : 11;
       const int known = shift + bits;  // key >> known must equal prefix
-      for (int i = t; i < 2048; i += kT) hist[i] = 0u;
-      __syncthreads();
+      uint32_t* const lh = hist + (level & 1) * 2048;  // the other half was cleared meanwhile
       for (uint32_t i = t; i < m; i += kT) {
         const uint32_t key = ckey[i];
         if (level == 0 || (key >> known) == prefix)
-          atomicAdd(&hist[(key >> shift) & ((1u << bits) - 1u)], 1u);
+          atomicAdd(&lh[(key >> shift) & ((1u << bits) - 1u)], 1u);
       }
+      for (int i = t; i < 2048; i += kT) hist[((level + 1) & 1) * 2048 + i] = 0u;
       __syncthreads();
-      find_from_top(hist, remaining, wave_tot, res);
+      find_from_top(lh, remaining, wave_tot, res);
       prefix = (prefix << bits) | res[0];
       remaining -= res[1];
+      n_eq_total = lh[res[0]];
       __syncthreads();
     }
+  KPROF(4);
     const uint32_t tau = prefix, need_eq = remaining;
     // candidates are in ascending position: take key > tau, and the first need_eq with key == tau
     const uint32_t per = (m + kT - 1) / kT;
     const uint32_t i0 = min(m, (uint32_t)t * per), i1 = min(m, i0 + per);
-    uint32_t neq = 0;
-    for (uint32_t i = i0; i < i1; ++i) neq += ckey[i] == tau ? 1u : 0u;
     uint32_t tot;
-    uint32_t eq_rank = block_exclusive_scan(neq, wave_tot, &tot);
+    uint32_t eq_rank = 0;
+    if (need_eq < n_eq_total) {  // ties at the threshold are cut: rank them in position order
+      uint32_t neq = 0;
+      for (uint32_t i = i0; i < i1; ++i) neq += ckey[i] == tau ? 1u : 0u;
+      eq_rank = block_exclusive_scan(neq, wave_tot, &tot);
+    }
     uint32_t nsel = 0;
     uint32_t flags = 0;  // per <= 8
     for (uint32_t i = i0; i < i1; ++i) {
       const uint32_t key = ckey[i];
       bool take = key > tau;
       if (key == tau) {
-        take = eq_rank < need_eq;
+        take = need_eq >= n_eq_total || eq_rank < need_eq;
         ++eq_rank;
       }
       if (take) {
@@ -393,6 +327,9 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
       }
   } else {
     // ---- safe route --------------------------------------------------------------------------
+#ifdef LRQK_KPROF
+    if (t == 0) atomicAdd(&g_kprof[15], 1ull);
+#endif
     uint32_t bin, above;
     // complete histogram
     for (int i = t; i < kBins; i += kT) hist[i] = 0u;
@@ -410,20 +347,7 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
       }
     }
     __syncthreads();
-    find_from_top(hist + 2048, (uint32_t)k, wave_tot, res);
-    {
-      const uint32_t d = res[0], a = res[1], upper_total = res[2];
-      __syncthreads();
-      if (d != 0xffffffffu) {
-        bin = 2048 + d;
-        above = a;
-      } else {
-        find_from_top(hist, (uint32_t)k - upper_total, wave_tot, res);
-        bin = res[0];
-        above = upper_total + res[1];
-        __syncthreads();
-      }
-    }
+    find_from_top_4096(hist, (uint32_t)k, wave_tot, res, &bin, &above);
     // refine the threshold inside the bin: two 10-bit levels over the low 20 key bits
     uint32_t prefix = bin, remaining = (uint32_t)k - above;
     int shift = kBinShift;
@@ -496,7 +420,7 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
     }
   }
   __syncthreads();
-  KPROF(3);
+  KPROF(5);
   for (int i = t; i < k; i += kT) sel_idx[(size_t)bh * k + i] = sel[i];
   if (!RESOLVE) return;
 
@@ -517,39 +441,54 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
   int32_t* const vsorted = reinterpret_cast<int32_t*>(vlist + kpad);  // [k] victims in rank order
 
   __syncthreads();  // the selection buffers are dead from here on
+  KPROF(6);
   for (int i = t; i < C; i += kT) lu_s[i] = lu[i];
   for (int i = t; i < kAgeBins; i += kT) ahist[i] = 0u;
   __syncthreads();
-  for (int j0 = 0; j0 < k; j0 += kT) {
-    const int j = j0 + t;
-    int32_t tok = -1, slot = -1;
-    bool miss = false;
-    if (j < k) {
-      tok = sel[j];
-      slot = so[tok];
-      if (slot >= C) slot = -1;  // corrupt map entry: treat as absent
-      miss = slot < 0;
-      if (!miss) {
-        ss[j] = slot;
-        ht[j] = 1;
-        lu[slot] = step;
-        lu_s[slot] = step;  // used in this step: never a victim
-      } else {
-        ht[j] = 0;
+  KPROF(7);
+  {
+    // thread t owns the selected positions [t*jp, (t+1)*jp) (jp <= 4): one prefix count
+    // ranks all misses in position order
+    const int jp = (k + kT - 1) / kT;
+    const int j0 = min(k, t * jp), j1 = min(k, j0 + jp);
+    int32_t toks[4], slots[4];
+    uint32_t nmine = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = j0 + u;
+      toks[u] = -1;
+      slots[u] = 0;
+      if (j < j1) {
+        toks[u] = sel[j];
+        int32_t slot = so[toks[u]];
+        if (slot >= C) slot = -1;  // corrupt map entry: treat as absent
+        slots[u] = slot;
+        nmine += slot < 0 ? 1u : 0u;
       }
     }
     uint32_t tot;
-    const uint32_t rank = sh_nmiss + block_exclusive_scan(miss ? 1u : 0u, wave_tot, &tot);
-    if (miss) {
-      mt[rank] = tok;
-      sel[j] = -(int32_t)rank - 2;  // remember the rank; the slot is filled in below
+    uint32_t rank = block_exclusive_scan(nmine, wave_tot, &tot);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = j0 + u;
+      if (j >= j1) continue;
+      if (slots[u] >= 0) {
+        ss[j] = slots[u];
+        ht[j] = 1;
+        lu[slots[u]] = step;
+        lu_s[slots[u]] = step;  // used in this step: never a victim
+      } else {
+        ht[j] = 0;
+        mt[rank] = toks[u];
+        sel[j] = -(int32_t)rank - 2;  // remember the rank; the slot is filled in below
+        ++rank;
+      }
     }
-    __syncthreads();
-    if (t == 0) sh_nmiss += tot;
+    if (t == 0) sh_nmiss = tot;
     __syncthreads();
   }
+  KPROF(8);
   const int nm = (int)sh_nmiss;
-  KPROF(4);
   if (nm > 0) {
     // ages of the slots not used in this step; thread t owns slots [t*spt, (t+1)*spt)
     const int spt = (C + kT - 1) / kT;
@@ -559,6 +498,7 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
       if (u != step) atomicAdd(&ahist[min((uint32_t)(step - 1 - u), (uint32_t)(kAgeBins - 1))], 1u);
     }
     __syncthreads();
+  KPROF(9);
     find_from_top(ahist, (uint32_t)nm, wave_tot, res);
     const uint32_t Ta = res[0], c_older = res[1], n_elig = res[2];
     __syncthreads();
@@ -595,6 +535,7 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
         if (flags & (1u << (v - s0)))
           vlist[pos++] = (((uint64_t)(uint32_t)(lu_s[v] + 1)) << 32) | (uint32_t)v;
       __syncthreads();
+  KPROF(10);
       if (nv <= kT) {
         // rank every victim among the victims by direct comparison
         if (t < nv) {
@@ -624,6 +565,7 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
       nv = (int)min((uint32_t)nm, n_elig);
       sorted64 = vlist;
     }
+  KPROF(11);
     for (int j = t; j < nm; j += kT) {
       if (j >= nv) {  // ran out of victims (the caller reused `step`)
         atomicOr(&sh_bad, 1u);
@@ -640,13 +582,14 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
       ms[j] = v;
     }
     __syncthreads();
+  KPROF(12);
     for (int j = t; j < k; j += kT) {
       const int32_t v = sel[j];
       if (v <= -2) ss[j] = ms[-(v + 2)];
     }
   }
   __syncthreads();
-  KPROF(5);
+  KPROF(13);
   if (t == 0) n_miss[bh] = sh_bad ? -1 : nm;
 }
 
@@ -678,12 +621,13 @@ hipError_t launch_select_only(const lrqk_shape& s, const float* scores, int32_t*
   hipError_t e = raise_lds_limit<false>();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((select_resolve_kernel<false>), dim3(s.B * s.Hq), dim3(kT), lds, st, scores,
-                     s.l, n, s.k, sel_idx, 0, s.C, nullptr, nullptr, nullptr, nullptr, nullptr,
+                     nullptr, 0, s.l, n, s.k, sel_idx, 0, s.C, nullptr, nullptr, nullptr, nullptr, nullptr,
                      nullptr, nullptr, nullptr);
   return hipGetLastError();
 }
 
-hipError_t launch_select_resolve(const lrqk_shape& s, const float* scores, int32_t* sel_idx,
+hipError_t launch_select_resolve(const lrqk_shape& s, const float* scores,
+                                 const unsigned long long* ext_bitmap, int32_t* sel_idx,
                                  int32_t step, int32_t* slot_of, int32_t* token_of,
                                  int32_t* last_used, int32_t* sel_slot, uint8_t* hit,
                                  int32_t* miss_tok, int32_t* miss_slot, int32_t* n_miss,
@@ -693,7 +637,8 @@ hipError_t launch_select_resolve(const lrqk_shape& s, const float* scores, int32
   hipError_t e = raise_lds_limit<true>();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((select_resolve_kernel<true>), dim3(s.B * s.Hq), dim3(kT), lds, st, scores,
-                     s.l, n, s.k, sel_idx, step, s.C, slot_of, token_of, last_used, sel_slot, hit,
+                     reinterpret_cast<const uint32_t*>(ext_bitmap), 2 * filter_words64(n), s.l, n,
+                     s.k, sel_idx, step, s.C, slot_of, token_of, last_used, sel_slot, hit,
                      miss_tok, miss_slot, n_miss);
   return hipGetLastError();
 }

@@ -332,6 +332,20 @@ def test_decode_step_very_long_context():
     run_steps_against_oracle(cfg, 3, "direct", check_unfused=False)
 
 
+@pytest.mark.parametrize("factor", [0.0, 50.0])
+def test_decode_step_misleading_threshold_sample(factor):
+    say(f"decode_step where the rows the threshold estimate samples are scaled by {factor}")
+    cfg = small_cfg(B=1, Hq=8, Hkv=2, l=70000, r=32, k=1024, w=64, C=2048, n_heavy=64)
+    data = make_layer(cfg)
+    n = cfg.l - cfg.w
+    ss = 1
+    while ss < 256 and n // (ss * 2) >= 2048:      # the library's sampling stride for this n
+        ss *= 2
+    assert ss == 32
+    data.A_K[:, :, ss // 2:n:ss, :] *= factor      # every row the estimate looks at
+    run_steps_against_oracle(cfg, 2, "direct", data=data, check_unfused=False)
+
+
 def test_config1_all_hits():
     say("config 1: l=4096 r=32 k=256 w=16, identity cache (all hits)")
     cfg = get_config("c1")
