@@ -32,9 +32,10 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM traffic of one proxy-score launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
-# scaled by the same counters on a plain copy kernel; bytes per launch.  See profiles/.
-MEASURED_TRAFFIC = {}
+# HBM traffic of one proxy-score launch measured with rocprofv3 --pmc (FETCH_SIZE, then
+# WRITE_SIZE, each scaled by what the same counter reads for lrqk_calib_copy), bytes per launch:
+# profiles/proxy_scores_c3_r32_hbm_traffic.md.  Only for the workload it was measured on.
+MEASURED_TRAFFIC = {"c3_r32": 130680 * 1024 + 17280 * 1024}
 
 
 def main():
@@ -165,6 +166,14 @@ def main():
     k1_us = 1e3 * e0.elapsed_time(e1) / n_k
     a_k_bytes = cfg.B * cfg.Hkv * cfg.l * cfg.r * 4 + cfg.B * cfg.Hq * cfg.r * 4
     k1_gbs = a_k_bytes / (k1_us * 1e-6) / 1e9
+
+    # a plain copy of known traffic (2 x A_K bytes per launch): calibrates the HBM byte counters
+    # when this script runs under rocprofv3 --pmc; it is outside every timed region
+    calib_dst = torch.empty_like(layers[0].A_K)
+    for i in range(4):
+        L.lrqk_calib_copy(calib_dst, layers[(i + 1) % nl].A_K)
+    torch.cuda.synchronize()
+    del calib_dst
 
     step_bytes = (a_k_bytes + 2 * 2 * cfg.d * (cfg.B * cfg.Hq * cfg.k + cfg.B * cfg.Hkv * cfg.w)
                   + 2 * cfg.B * cfg.Hq * cfg.d * 4 + 2 * cfg.B * cfg.Hq * cfg.k * 4)

@@ -273,6 +273,14 @@ int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
 int lrqk_plan_profile(lrqk_plan* plan, int n_steps);
 int lrqk_plan_profile_read(lrqk_plan* plan, double* ms_sum, int* n_steps_out);
 
+/*
+ * Instrumentation: copy `bytes` (a multiple of 16) from src to dst, both device memory,
+ * 16-byte aligned, with a plain one-load-one-store kernel.  Its HBM traffic is known
+ * (bytes read + bytes written), which calibrates the hardware byte counters that the
+ * measured traffic of the other kernels is scaled by.
+ */
+int lrqk_calib_copy(void* dst, const void* src, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -79,6 +79,7 @@ def load_library():
                                         C.POINTER(C.c_int64), vp]),
         "lrqk_decode_step": (C.c_int, [vp, sp, i32, C.POINTER(Layer), vp, vp, vp, C.c_int,
                                        C.POINTER(_StepDebug), C.POINTER(C.c_int64), vp]),
+        "lrqk_calib_copy": (C.c_int, [vp, vp, sz, vp]),
         "lrqk_plan_profile": (C.c_int, [vp, C.c_int]),
         "lrqk_plan_profile_read": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int)]),
     }
@@ -92,7 +93,7 @@ def load_library():
 EXPORTS = ["lrqk_version", "lrqk_status_string", "lrqk_last_hip_error", "lrqk_validate_shape",
            "lrqk_workspace_bytes", "lrqk_proxy_scores", "lrqk_select_topk", "lrqk_cache_init",
            "lrqk_cache_resolve", "lrqk_sparse_attend", "lrqk_plan_create", "lrqk_plan_destroy",
-           "lrqk_fetch_misses", "lrqk_decode_step", "lrqk_plan_profile", "lrqk_plan_profile_read"]
+           "lrqk_fetch_misses", "lrqk_decode_step", "lrqk_plan_profile", "lrqk_plan_profile_read", "lrqk_calib_copy"]
 
 
 def _check(status: int, where: str):
@@ -180,6 +181,14 @@ def lrqk_sparse_attend(shape, q, cacheK, cacheV, sel_slot, liteK, liteV, out, wo
         _dev(sel_slot, torch.int32), _dev(liteK), _dev(liteV), _dev(out, torch.float32),
         _dev(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
         "lrqk_sparse_attend")
+
+
+def lrqk_calib_copy(dst, src, stream=None):
+    """Plain device copy of known traffic (counter calibration)."""
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() >= nbytes
+    _check(load_library().lrqk_calib_copy(_dev(dst), _dev(src), nbytes, _stream(stream)),
+           "lrqk_calib_copy")
 
 
 class Plan:
