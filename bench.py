@@ -35,7 +35,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM traffic of one proxy-score launch measured with rocprofv3 --pmc (FETCH_SIZE, then
 # WRITE_SIZE, each scaled by what the same counter reads for lrqk_calib_copy), bytes per launch:
 # profiles/proxy_scores_c3_r32_hbm_traffic.md.  Only for the workload it was measured on.
-MEASURED_TRAFFIC = {"c3_r32": 130680 * 1024 + 17280 * 1024}
+MEASURED_TRAFFIC = {"c3_r32": 130618 * 1024 + 2611 * 1024}
 
 
 def main():
@@ -152,18 +152,11 @@ def main():
                  else last_nmiss / (cfg.B * cfg.Hq * cfg.k))
 
     # ---------------------------------------------------------------- dominant kernel alone
-    scores = torch.empty((cfg.B, cfg.Hq, cfg.l), device=dev)
-    for i in range(8):
-        L.lrqk_proxy_scores(shape, layers[i % nl].A_K, queries[i][1], scores)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    # the proxy-score pass exactly as the fused step launches it, n_k launches back to back
+    # over the layers' A_K, bracketed by HIP events on the launch stream inside the library
+    # (a Python loop of single launches would be bound by the interpreter, not by the GPU)
     n_k = max(args.steps, 64)
-    e0.record()
-    for i in range(n_k):
-        L.lrqk_proxy_scores(shape, layers[i % nl].A_K, queries[i % n_pre][1], scores)
-    e1.record()
-    torch.cuda.synchronize()
-    k1_us = 1e3 * e0.elapsed_time(e1) / n_k
+    k1_us = plan.time_proxy_pass(shape, [lb.A_K for lb in layers], queries[0][1], n_k)
     a_k_bytes = cfg.B * cfg.Hkv * cfg.l * cfg.r * 4 + cfg.B * cfg.Hq * cfg.r * 4
     k1_gbs = a_k_bytes / (k1_us * 1e-6) / 1e9
 

@@ -265,13 +265,27 @@ int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
  * (n = 0 switches it off); lrqk_plan_profile_read waits for the recorded steps, adds
  * up the time between consecutive marks into ms_sum[LRQK_PROFILE_MARKS - 1]
  * (milliseconds, summed over steps) and re-arms.  Intervals, in order:
- *   0 proxy scores | 1 selection | 2 hit/miss resolution |
- *   3 fetch kernel (DIRECT) or miss-list copy + host synchronisation (STAGED) |
- *   4 attention partials (STAGED: includes the wait for the side-stream copy) | 5 merge
+ *   0 sampled threshold estimate (0 when the shape does not use it) | 1 proxy-score pass |
+ *   2 selection (with the resolution when both run in one launch) | 3 separate resolution |
+ *   4 fetch kernel (DIRECT) or miss-list copy + host synchronisation (STAGED) |
+ *   5 attention partials (STAGED: includes the wait for the side-stream copy) | 6 merge
  */
-#define LRQK_PROFILE_MARKS 7
+#define LRQK_PROFILE_MARKS 8
 int lrqk_plan_profile(lrqk_plan* plan, int n_steps);
 int lrqk_plan_profile_read(lrqk_plan* plan, double* ms_sum, int* n_steps_out);
+
+/*
+ * Instrumentation: time the dominant kernel alone.  Runs step a1's pass over A_K exactly as
+ * lrqk_decode_step launches it for this shape (the filtered proxy-score kernel with the
+ * thresholds estimated once for q_hat; the plain proxy-score kernel for shapes that do not
+ * use the filter), n_launches times back to back on `stream`, cycling through the n_list
+ * device arrays A_K_list[i] (each [B,Hkv,l,r] fp32, e.g. one per layer, so that no cache
+ * holds them), bracketed by two HIP events.  Synchronises; *avg_us_out = microseconds per
+ * launch.  Results go to the plan's workspace and are discarded.
+ */
+int lrqk_plan_time_proxy_pass(lrqk_plan* plan, const lrqk_shape* shape,
+                              const float* const* A_K_list, int n_list, const float* q_hat,
+                              int n_launches, float* avg_us_out, void* stream);
 
 /*
  * Instrumentation: copy `bytes` (a multiple of 16) from src to dst, both device memory,

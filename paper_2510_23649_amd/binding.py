@@ -80,6 +80,8 @@ def load_library():
         "lrqk_decode_step": (C.c_int, [vp, sp, i32, C.POINTER(Layer), vp, vp, vp, C.c_int,
                                        C.POINTER(_StepDebug), C.POINTER(C.c_int64), vp]),
         "lrqk_calib_copy": (C.c_int, [vp, vp, sz, vp]),
+        "lrqk_plan_time_proxy_pass": (C.c_int, [vp, sp, C.POINTER(vp), C.c_int, vp, C.c_int,
+                                                C.POINTER(C.c_float), vp]),
         "lrqk_plan_profile": (C.c_int, [vp, C.c_int]),
         "lrqk_plan_profile_read": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int)]),
     }
@@ -93,7 +95,8 @@ def load_library():
 EXPORTS = ["lrqk_version", "lrqk_status_string", "lrqk_last_hip_error", "lrqk_validate_shape",
            "lrqk_workspace_bytes", "lrqk_proxy_scores", "lrqk_select_topk", "lrqk_cache_init",
            "lrqk_cache_resolve", "lrqk_sparse_attend", "lrqk_plan_create", "lrqk_plan_destroy",
-           "lrqk_fetch_misses", "lrqk_decode_step", "lrqk_plan_profile", "lrqk_plan_profile_read", "lrqk_calib_copy"]
+           "lrqk_fetch_misses", "lrqk_decode_step", "lrqk_plan_profile", "lrqk_plan_profile_read", "lrqk_calib_copy",
+           "lrqk_plan_time_proxy_pass"]
 
 
 def _check(status: int, where: str):
@@ -199,7 +202,8 @@ class Plan:
         _check(load_library().lrqk_plan_create(C.byref(max_shape), C.byref(h)), "lrqk_plan_create")
         self.handle = h
 
-    PHASES = ("proxy_scores", "select_topk", "cache_resolve", "fetch_or_sync", "attend", "combine")
+    PHASES = ("threshold_estimate", "proxy_scores", "select_and_resolve", "separate_resolve",
+              "fetch_or_sync", "attend", "combine")
 
     def profile(self, n_steps: int):
         """lrqk_plan_profile: time the phases of the next n_steps fused steps (0 = off)."""
@@ -207,11 +211,20 @@ class Plan:
 
     def profile_read(self):
         """lrqk_plan_profile_read -> (dict phase -> summed ms, number of steps)."""
-        ms = (C.c_double * 6)()
+        ms = (C.c_double * 7)()
         n = C.c_int(0)
         _check(load_library().lrqk_plan_profile_read(self.handle, ms, C.byref(n)),
                "lrqk_plan_profile_read")
         return dict(zip(self.PHASES, list(ms))), n.value
+
+    def time_proxy_pass(self, shape, A_K_list, q_hat, n_launches, stream=None) -> float:
+        """lrqk_plan_time_proxy_pass: microseconds per launch of step a1's pass over A_K."""
+        ptrs = (C.c_void_p * len(A_K_list))(*[_dev(a, torch.float32) for a in A_K_list])
+        us = C.c_float(0.0)
+        _check(load_library().lrqk_plan_time_proxy_pass(
+            self.handle, C.byref(shape), ptrs, len(A_K_list), _dev(q_hat, torch.float32),
+            int(n_launches), C.byref(us), _stream(stream)), "lrqk_plan_time_proxy_pass")
+        return us.value
 
     def close(self):
         if getattr(self, "handle", None):

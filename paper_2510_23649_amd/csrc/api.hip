@@ -53,6 +53,7 @@ struct lrqk_plan {
   uint32_t* thr;               // [BHq] sampled threshold bin of each head
   float* samples;              // [BHq][kThrMaxSamples] sample scores behind thr
   unsigned long long* filter;  // [BHq][words64] candidate bitmap from the proxy-score pass
+  float* cand_scores;          // [BHq][words64][kCandPerGroup] the candidates' scores
   void* select_ws;
   size_t select_bytes;
   float* partials;
@@ -197,7 +198,7 @@ int lrqk_plan_destroy(lrqk_plan* p) {
   (void)hipGetDevice(&prev);
   (void)hipSetDevice(p->device);
   if (p->side) (void)hipStreamSynchronize(p->side);
-  void* dev[] = {p->scores, p->thr, p->samples, p->filter, p->select_ws, p->partials, p->sel_idx, p->sel_slot, p->miss_tok,
+  void* dev[] = {p->scores, p->thr, p->samples, p->filter, p->cand_scores, p->select_ws, p->partials, p->sel_idx, p->sel_slot, p->miss_tok,
                  p->miss_slot, p->n_miss, p->hit, p->d_stage, p->d_rowdst};
   for (void* q : dev)
     if (q) (void)hipFree(q);
@@ -240,6 +241,7 @@ int lrqk_plan_create(const lrqk_shape* max_shape, lrqk_plan** plan_out) {
   dmalloc((void**)&p->thr, BHq * 4);
   dmalloc((void**)&p->samples, BHq * (size_t)kThrMaxSamples * 4);
   dmalloc((void**)&p->filter, BHq * (size_t)filter_words64(s.l) * 8);
+  dmalloc((void**)&p->cand_scores, BHq * (size_t)filter_words64(s.l) * kCandPerGroup * 4);
   dmalloc(&p->select_ws, p->select_bytes);
   dmalloc((void**)&p->partials, p->partial_bytes);
   dmalloc((void**)&p->sel_idx, BHq * s.k * 4);
@@ -385,40 +387,43 @@ int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
   const bool one_wg = select_resolve_fits(s, true);
   const bool filtered = one_wg && proxy_filter_supported(s);
   if (filtered) {
-    // sampled threshold, then scores + candidate bitmap in one pass over A_K
+    // sampled threshold, then one pass over A_K that leaves only the candidate bitmap
     LRQK_HIP(launch_proxy_threshold(s, L->A_K, q_hat, plan->samples, plan->thr, st));
+    LRQK_HIP(prof_mark(plan, 1, st));
     LRQK_HIP(launch_proxy_scores_filter(s, L->A_K, q_hat, plan->scores, plan->thr, plan->filter,
-                                        st));
+                                        plan->cand_scores, st));
   } else {
+    LRQK_HIP(prof_mark(plan, 1, st));
     LRQK_HIP(launch_proxy_scores(s, L->A_K, q_hat, plan->scores, st));
   }
-  LRQK_HIP(prof_mark(plan, 1, st));
+  LRQK_HIP(prof_mark(plan, 2, st));
   if (one_wg) {
     // selection and resolution in one launch; the profile books it all under "selection"
-    LRQK_HIP(launch_select_resolve(s, plan->scores, filtered ? plan->filter : nullptr, sel_idx,
-                                   step, L->slot_of, L->token_of, L->last_used, sel_slot, hit,
-                                   miss_tok, miss_slot, n_miss, st));
-    LRQK_HIP(prof_mark(plan, 2, st));
+    LRQK_HIP(launch_select_resolve(s, plan->scores, filtered ? plan->filter : nullptr,
+                                   plan->cand_scores, L->A_K, q_hat, sel_idx, step, L->slot_of,
+                                   L->token_of, L->last_used, sel_slot, hit, miss_tok, miss_slot,
+                                   n_miss, st));
+    LRQK_HIP(prof_mark(plan, 3, st));
   } else {
     LRQK_HIP(launch_select_topk(s, plan->scores, sel_idx, ws, st));
-    LRQK_HIP(prof_mark(plan, 2, st));
+    LRQK_HIP(prof_mark(plan, 3, st));
     LRQK_HIP(launch_cache_resolve(s, sel_idx, step, L->slot_of, L->token_of, L->last_used,
                                   sel_slot, hit, miss_tok, miss_slot, n_miss, st));
   }
-  LRQK_HIP(prof_mark(plan, 3, st));
+  LRQK_HIP(prof_mark(plan, 4, st));
   const AttendGeom g = attend_geometry(BHq, s.k, s.w);
   const int parts_per_head = g.nsplit + ceil_div(s.k, g.rows_per_block);
 
   if (mode == LRQK_FETCH_DIRECT) {
     LRQK_HIP(launch_fetch_direct(s, L->K_host, L->V_host, miss_tok, miss_slot, n_miss, L->cacheK,
                                  L->cacheV, st));
-    LRQK_HIP(prof_mark(plan, 4, st));
+    LRQK_HIP(prof_mark(plan, 5, st));
     LRQK_HIP(launch_attend_partial(s, kAttendAll, q, L->cacheK, L->cacheV, sel_slot, nullptr,
                                    nullptr, nullptr, L->liteK, L->liteV, plan->partials, g.nsplit,
                                    g.rows_per_block, parts_per_head, 0, st));
-    LRQK_HIP(prof_mark(plan, 5, st));
-    LRQK_HIP(launch_attend_combine(s, plan->partials, parts_per_head, g.nsplit, out, st));
     LRQK_HIP(prof_mark(plan, 6, st));
+    LRQK_HIP(launch_attend_combine(s, plan->partials, parts_per_head, g.nsplit, out, st));
+    LRQK_HIP(prof_mark(plan, 7, st));
     if (plan->prof_ev && plan->prof_n < plan->prof_cap) ++plan->prof_n;
     if (total_miss_out) *total_miss_out = -1;
     return LRQK_OK;
@@ -430,7 +435,7 @@ int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
   LRQK_HIP(hipMemcpyAsync(plan->h_miss_tok, miss_tok, nb * s.k * 4, hipMemcpyDeviceToHost, st));
   LRQK_HIP(hipMemcpyAsync(plan->h_miss_slot, miss_slot, nb * s.k * 4, hipMemcpyDeviceToHost, st));
   LRQK_HIP(hipStreamSynchronize(st));
-  LRQK_HIP(prof_mark(plan, 4, st));
+  LRQK_HIP(prof_mark(plan, 5, st));
   // ... attend the rows already resident and the lite rows while the host packs the misses
   LRQK_HIP(launch_attend_partial(s, kAttendHitsAndLite, q, L->cacheK, L->cacheV, sel_slot, hit,
                                  nullptr, nullptr, L->liteK, L->liteV, plan->partials, g.nsplit,
@@ -443,10 +448,49 @@ int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
   LRQK_HIP(launch_attend_partial(s, kAttendMisses, q, L->cacheK, L->cacheV, sel_slot, hit,
                                  miss_slot, n_miss, L->liteK, L->liteV, plan->partials, nblk_miss,
                                  g.rows_per_block, parts_per_head, g.nsplit, st));
-  LRQK_HIP(prof_mark(plan, 5, st));
-  LRQK_HIP(launch_attend_combine(s, plan->partials, parts_per_head, g.nsplit + nblk_miss, out, st));
   LRQK_HIP(prof_mark(plan, 6, st));
+  LRQK_HIP(launch_attend_combine(s, plan->partials, parts_per_head, g.nsplit + nblk_miss, out, st));
+  LRQK_HIP(prof_mark(plan, 7, st));
   if (plan->prof_ev && plan->prof_n < plan->prof_cap) ++plan->prof_n;
+  return LRQK_OK;
+}
+
+int lrqk_plan_time_proxy_pass(lrqk_plan* plan, const lrqk_shape* shape,
+                              const float* const* A_K_list, int n_list, const float* q_hat,
+                              int n_launches, float* avg_us_out, void* stream) {
+  int rc = check_shape(shape);
+  if (rc != LRQK_OK) return rc;
+  if (!A_K_list || n_list < 1 || n_launches < 1 || !avg_us_out || !all_aligned16({q_hat}))
+    return LRQK_EINVAL;
+  for (int i = 0; i < n_list; ++i)
+    if (!all_aligned16({A_K_list[i]})) return LRQK_EINVAL;
+  rc = check_plan_fits(plan, shape);
+  if (rc != LRQK_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const bool filtered = select_resolve_fits(*shape, true) && proxy_filter_supported(*shape);
+  auto pass = [&](const float* A_K) -> hipError_t {
+    if (filtered)
+      return launch_proxy_scores_filter(*shape, A_K, q_hat, plan->scores, plan->thr, plan->filter,
+                                        plan->cand_scores, st);
+    return launch_proxy_scores(*shape, A_K, q_hat, plan->scores, st);
+  };
+  // thresholds for this q_hat, then a few untimed launches
+  if (filtered)
+    LRQK_HIP(launch_proxy_threshold(*shape, A_K_list[0], q_hat, plan->samples, plan->thr, st));
+  for (int i = 0; i < (n_list < 4 ? n_list : 4); ++i) LRQK_HIP(pass(A_K_list[i]));
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  LRQK_HIP(hipEventCreate(&e0));
+  hipError_t e = hipEventCreate(&e1);
+  if (e == hipSuccess) e = hipEventRecord(e0, st);
+  for (int i = 0; i < n_launches && e == hipSuccess; ++i) e = pass(A_K_list[i % n_list]);
+  if (e == hipSuccess) e = hipEventRecord(e1, st);
+  if (e == hipSuccess) e = hipEventSynchronize(e1);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  LRQK_HIP(e);
+  *avg_us_out = 1e3f * ms / (float)n_launches;
   return LRQK_OK;
 }
 

@@ -69,9 +69,12 @@ constexpr int kThrMaxSamples = 8192;  // sample scores kept per head
 // samples: [BHq][kThrMaxSamples] floats
 hipError_t launch_proxy_threshold(const lrqk_shape& s, const float* A_K, const float* q_hat,
                                   float* samples, uint32_t* thr, hipStream_t st);
+constexpr int kCandPerGroup = 8;  // candidate scores kept per head and 64-row group
+// cand_scores: [BHq][words64][kCandPerGroup] floats
 hipError_t launch_proxy_scores_filter(const lrqk_shape& s, const float* A_K, const float* q_hat,
                                       float* scores, const uint32_t* thr,
-                                      unsigned long long* bitmap, hipStream_t st);
+                                      unsigned long long* bitmap, float* cand_scores,
+                                      hipStream_t st);
 hipError_t launch_select_topk(const lrqk_shape& s, const float* scores, int32_t* sel_idx,
                               const SelectWs& ws, hipStream_t st);
 // One workgroup per head, everything in LDS (select_resolve.hip); usable when the
@@ -80,10 +83,13 @@ bool select_resolve_fits(const lrqk_shape& s, bool resolve);
 hipError_t launch_select_only(const lrqk_shape& s, const float* scores, int32_t* sel_idx,
                               hipStream_t st);
 // ext_bitmap: candidate bitmap written by the filtered proxy-score pass ([BHq][words64]
-// 64-bit words), or nullptr to let the kernel derive its own from the scores.
-hipError_t launch_select_resolve(const lrqk_shape& s, const float* scores,
-                                 const unsigned long long* ext_bitmap, int32_t* sel_idx,
-                                 int32_t step, int32_t* slot_of, int32_t* token_of,
+// 64-bit words); the scores are then recomputed from A_K / q_hat where needed and `scores`
+// is only scratch for heads that take the safe route.  With ext_bitmap == nullptr the
+// kernel works from the materialised `scores` and A_K / q_hat are ignored.
+hipError_t launch_select_resolve(const lrqk_shape& s, float* scores,
+                                 const unsigned long long* ext_bitmap, const float* cand_scores,
+                                 const float* A_K,
+                                 const float* q_hat, int32_t* sel_idx, int32_t step, int32_t* slot_of, int32_t* token_of,
                                  int32_t* last_used, int32_t* sel_slot, uint8_t* hit,
                                  int32_t* miss_tok, int32_t* miss_slot, int32_t* n_miss,
                                  hipStream_t st);

@@ -32,14 +32,19 @@ __device__ __forceinline__ float4 load_streaming(const float4* p) {
   return make_float4(x.x, x.y, x.z, x.w);
 }
 
-// FILTER: besides the scores, emit for every head a bitmap of the positions in [0, n)
-// whose order key is >= thr[head]: one 64-bit ballot per wavefront and head, no
-// atomics.  The selection kernel starts from that bitmap.
+// FILTER: emit, INSTEAD of the scores, a bitmap per head of the positions in [0, n) whose
+// order key is >= thr[head] (one 64-bit ballot per wavefront and head, no atomics) and
+// the scores of those candidates, packed in position order into a slot of
+// kCandPerGroup floats per 64-row group (the i-th set bit of the group's ballot goes to
+// entry i; a group with more candidates than the slot holds keeps the first ones and
+// the selection kernel recomputes the others from A_K).  The fused step therefore never
+// writes the l-sized score array: about 5 MB leave this kernel instead of 16.8 MB at
+// l = 131072.
 template <int R, int G, bool FILTER>
 __global__ __launch_bounds__(kTileRows) void proxy_scores_kernel(
     const float* __restrict__ A_K, const float* __restrict__ q_hat, float* __restrict__ scores,
     int l, int Hq, int Hkv, int n, const uint32_t* __restrict__ thr,
-    unsigned long long* __restrict__ bitmap, int words64) {
+    unsigned long long* __restrict__ bitmap, float* __restrict__ cand_scores, int words64) {
   constexpr int V4 = R / 4;       // 16-byte chunks per row
   constexpr int ROW4 = V4 + 1;    // padded LDS row stride in 16-byte units
   __shared__ float4 tile[kTileRows * ROW4];
@@ -82,18 +87,34 @@ __global__ __launch_bounds__(kTileRows) void proxy_scores_kernel(
     }
   }
   const int row = row0 + t;
-  if (row < l) {
+  if (!FILTER) {
+    if (row < l) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) sc[(size_t)g * l + row] = acc[g];
-  }
-  if (FILTER) {
+      for (int g = 0; g < G; ++g) sc[(size_t)g * l + row] = acc[g];
+    }
+  } else {
     const int wrow = row0 + (t & ~63);  // first row of this wavefront
+    const int lane = t & 63;
+    // The 64 rows of the tile that this wavefront owns are read by no other wavefront, so
+    // their LDS space can stage the packed candidate scores without a workgroup barrier.
+    float* stage = reinterpret_cast<float*>(&tile[(t & ~63) * ROW4]);
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       const size_t bh = (size_t)b * Hq + (size_t)kv * G + g;
       const bool in = row < n && dev::order_key(acc[g]) >= thr[bh];
       const unsigned long long mask = __ballot(in);
-      if ((t & 63) == 0 && wrow < n) bitmap[bh * words64 + (wrow >> 6)] = mask;
+      if (lane == 0 && wrow < n) bitmap[bh * words64 + (wrow >> 6)] = mask;
+      if (mask != 0ull) {  // wave-uniform
+        const int rank = __popcll(mask & ((1ull << lane) - 1ull));
+        if (lane < kCandPerGroup) stage[g * kCandPerGroup + lane] = 0.0f;
+        __builtin_amdgcn_wave_barrier();
+        if (in && rank < kCandPerGroup) stage[g * kCandPerGroup + rank] = acc[g];
+        __builtin_amdgcn_wave_barrier();
+        // one full 64-byte store per wavefront and head instead of scattered 4-byte ones
+        if (lane < kCandPerGroup)
+          cand_scores[(bh * words64 + (wrow >> 6)) * kCandPerGroup + lane] =
+              stage[g * kCandPerGroup + lane];
+      }
     }
   }
 }
@@ -254,29 +275,31 @@ __global__ __launch_bounds__(256) void proxy_scores_generic_kernel(
 
 template <int R, int G>
 hipError_t launch_fast(const lrqk_shape& s, const float* A_K, const float* q_hat, float* scores,
-                       const uint32_t* thr, unsigned long long* bitmap, hipStream_t st) {
+                       const uint32_t* thr, unsigned long long* bitmap, float* cand_scores,
+                       hipStream_t st) {
   dim3 grid(ceil_div(s.l, kTileRows), s.B * s.Hkv);
   const int n = s.l - s.w;
   if (thr)
     hipLaunchKernelGGL((proxy_scores_kernel<R, G, true>), grid, dim3(kTileRows), 0, st, A_K,
-                       q_hat, scores, s.l, s.Hq, s.Hkv, n, thr, bitmap, filter_words64(n));
+                       q_hat, scores, s.l, s.Hq, s.Hkv, n, thr, bitmap, cand_scores,
+                       filter_words64(n));
   else
     hipLaunchKernelGGL((proxy_scores_kernel<R, G, false>), grid, dim3(kTileRows), 0, st, A_K,
-                       q_hat, scores, s.l, s.Hq, s.Hkv, n, nullptr, nullptr, 0);
+                       q_hat, scores, s.l, s.Hq, s.Hkv, n, nullptr, nullptr, nullptr, 0);
   return hipGetLastError();
 }
 
 template <int R>
 hipError_t dispatch_G(const lrqk_shape& s, const float* A_K, const float* q_hat, float* scores,
-                      const uint32_t* thr, unsigned long long* bitmap, hipStream_t st,
-                      bool* handled) {
+                      const uint32_t* thr, unsigned long long* bitmap, float* cand_scores,
+                      hipStream_t st, bool* handled) {
   *handled = true;
   switch (s.Hq / s.Hkv) {
-    case 1: return launch_fast<R, 1>(s, A_K, q_hat, scores, thr, bitmap, st);
-    case 2: return launch_fast<R, 2>(s, A_K, q_hat, scores, thr, bitmap, st);
-    case 4: return launch_fast<R, 4>(s, A_K, q_hat, scores, thr, bitmap, st);
-    case 7: return launch_fast<R, 7>(s, A_K, q_hat, scores, thr, bitmap, st);
-    case 8: return launch_fast<R, 8>(s, A_K, q_hat, scores, thr, bitmap, st);
+    case 1: return launch_fast<R, 1>(s, A_K, q_hat, scores, thr, bitmap, cand_scores, st);
+    case 2: return launch_fast<R, 2>(s, A_K, q_hat, scores, thr, bitmap, cand_scores, st);
+    case 4: return launch_fast<R, 4>(s, A_K, q_hat, scores, thr, bitmap, cand_scores, st);
+    case 7: return launch_fast<R, 7>(s, A_K, q_hat, scores, thr, bitmap, cand_scores, st);
+    case 8: return launch_fast<R, 8>(s, A_K, q_hat, scores, thr, bitmap, cand_scores, st);
     default: *handled = false; return hipSuccess;
   }
 }
@@ -309,13 +332,14 @@ hipError_t launch_proxy_threshold(const lrqk_shape& s, const float* A_K, const f
 
 hipError_t launch_proxy_scores_filter(const lrqk_shape& s, const float* A_K, const float* q_hat,
                                       float* scores, const uint32_t* thr,
-                                      unsigned long long* bitmap, hipStream_t st) {
+                                      unsigned long long* bitmap, float* cand_scores,
+                                      hipStream_t st) {
   bool handled = false;
   hipError_t e = hipErrorInvalidValue;
   switch (s.r) {
-    case 16: e = dispatch_G<16>(s, A_K, q_hat, scores, thr, bitmap, st, &handled); break;
-    case 32: e = dispatch_G<32>(s, A_K, q_hat, scores, thr, bitmap, st, &handled); break;
-    case 64: e = dispatch_G<64>(s, A_K, q_hat, scores, thr, bitmap, st, &handled); break;
+    case 16: e = dispatch_G<16>(s, A_K, q_hat, scores, thr, bitmap, cand_scores, st, &handled); break;
+    case 32: e = dispatch_G<32>(s, A_K, q_hat, scores, thr, bitmap, cand_scores, st, &handled); break;
+    case 64: e = dispatch_G<64>(s, A_K, q_hat, scores, thr, bitmap, cand_scores, st, &handled); break;
     default: break;
   }
   return handled ? e : hipErrorInvalidValue;
@@ -326,9 +350,9 @@ hipError_t launch_proxy_scores(const lrqk_shape& s, const float* A_K, const floa
   bool handled = false;
   hipError_t e = hipSuccess;
   switch (s.r) {
-    case 16: e = dispatch_G<16>(s, A_K, q_hat, scores, nullptr, nullptr, st, &handled); break;
-    case 32: e = dispatch_G<32>(s, A_K, q_hat, scores, nullptr, nullptr, st, &handled); break;
-    case 64: e = dispatch_G<64>(s, A_K, q_hat, scores, nullptr, nullptr, st, &handled); break;
+    case 16: e = dispatch_G<16>(s, A_K, q_hat, scores, nullptr, nullptr, nullptr, st, &handled); break;
+    case 32: e = dispatch_G<32>(s, A_K, q_hat, scores, nullptr, nullptr, nullptr, st, &handled); break;
+    case 64: e = dispatch_G<64>(s, A_K, q_hat, scores, nullptr, nullptr, nullptr, st, &handled); break;
     default: break;
   }
   if (handled) return e;

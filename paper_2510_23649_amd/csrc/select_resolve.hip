@@ -142,8 +142,12 @@ __host__ __device__ inline ArenaSizes arena_sizes(int k, int n, int C, bool reso
 
 template <bool RESOLVE>
 __global__ __launch_bounds__(kT) void select_resolve_kernel(
-    const float* __restrict__ scores, const uint32_t* __restrict__ ext_bitmap, int ext_words,
-    int l, int n, int k, int32_t* __restrict__ sel_idx,
+    const float* scores, const uint32_t* __restrict__ ext_bitmap, int ext_words,
+    // with an external bitmap the scores are not materialised: they are recomputed from A_K
+    // (scores_w: this head's slice is filled in only if the safe route needs every score)
+    const float* __restrict__ cand_scores, const float* __restrict__ A_K,
+    const float* __restrict__ q_hat, float* scores_w, int r,
+    int Hq, int Hkv, int l, int n, int k, int32_t* __restrict__ sel_idx,
     // resolution (unused when !RESOLVE)
     int32_t step, int C, int32_t* __restrict__ slot_of, int32_t* __restrict__ token_of,
     int32_t* __restrict__ last_used, int32_t* __restrict__ sel_slot, uint8_t* __restrict__ hit,
@@ -165,8 +169,29 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
   int32_t* const clist = reinterpret_cast<int32_t*>(U + (size_t)kBins * 4 + az.words_b);
   uint32_t* const ckey = reinterpret_cast<uint32_t*>(clist + cap);
 
-  const float* __restrict__ s = scores + (size_t)bh * l;
+  const float* s = scores + (size_t)bh * l;
   const bool vec_ok = (l & 3) == 0;
+  const bool recompute = ext_bitmap != nullptr && A_K != nullptr;
+  const float* __restrict__ Arow = nullptr;  // this head's A_K and q_hat (recompute only)
+  const float* __restrict__ qh = nullptr;
+  if (recompute) {
+    const int b = bh / Hq, h = bh - b * Hq, kvh = h / (Hq / Hkv);
+    Arow = A_K + ((size_t)b * Hkv + kvh) * (size_t)l * r;
+    qh = q_hat + (size_t)bh * r;
+  }
+  // proxy score of one row: the same fused-multiply-add chain as the proxy-score kernels
+  auto score_of_row = [&](int row) -> float {
+    const float4* __restrict__ a4 = reinterpret_cast<const float4*>(Arow + (size_t)row * r);
+    float acc = 0.0f;
+    for (int c = 0; c < r / 4; ++c) {
+      const float4 a = a4[c];
+      acc = __builtin_fmaf(a.x, qh[4 * c + 0], acc);
+      acc = __builtin_fmaf(a.y, qh[4 * c + 1], acc);
+      acc = __builtin_fmaf(a.z, qh[4 * c + 2], acc);
+      acc = __builtin_fmaf(a.w, qh[4 * c + 3], acc);
+    }
+    return acc;
+  };
   const int n_iter = (n + kIter - 1) / kIter;
   const int words = (n + 31) / 32;
   const int wpt = (words + kT - 1) / kT;  // bitmap words per thread in the prefix counts
@@ -255,11 +280,19 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
     if (m >= (uint32_t)k && m <= (uint32_t)cap) {
       for (int j = 0; j < wpt; ++j) {
         if (t * wpt + j >= words) break;
-        uint32_t wbits = bitmap[t * wpt + j];
+        const int wi = t * wpt + j;
+        uint32_t wbits = bitmap[wi];
+        // rank of a bit inside its 64-position group (two words): where the proxy-score
+        // pass left that candidate's score
+        int grank = (wi & 1) ? __popc(bitmap[wi - 1]) : 0;
         while (wbits) {
           const int bpos = __ffs((int)wbits) - 1;
           wbits &= wbits - 1;
-          clist[off++] = (t * wpt + j) * 32 + bpos;
+          clist[off] = wi * 32 + bpos;
+          ckey[off] = grank < kCandPerGroup ? (uint32_t)((wi >> 1) * kCandPerGroup + grank)
+                                            : 0xffffffffu;
+          ++grank;
+          ++off;
         }
       }
     }
@@ -268,7 +301,16 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
   KPROF(2);
   if (m >= (uint32_t)k && m <= (uint32_t)cap) {
     for (int i = t; i < kBins; i += kT) hist[i] = 0u;
-    for (uint32_t i = t; i < m; i += kT) ckey[i] = order_key(s[clist[i]]);
+    if (recompute) {
+      const float* __restrict__ cs =
+          cand_scores + (size_t)bh * (size_t)(ext_words >> 1) * kCandPerGroup;
+      for (uint32_t i = t; i < m; i += kT) {
+        const uint32_t slot = ckey[i];
+        ckey[i] = order_key(slot != 0xffffffffu ? cs[slot] : score_of_row(clist[i]));
+      }
+    } else {
+      for (uint32_t i = t; i < m; i += kT) ckey[i] = order_key(s[clist[i]]);
+    }
     __syncthreads();
   KPROF(3);
     // exact key of the k-th largest candidate: digits [31:21], [20:10], [9:0]
@@ -331,6 +373,13 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
     if (t == 0) atomicAdd(&g_kprof[15], 1ull);
 #endif
     uint32_t bin, above;
+    if (recompute) {
+      // every score of this head is needed now: compute them into the score array
+      float* sw = scores_w + (size_t)bh * l;
+      for (int row = t; row < n; row += kT) sw[row] = score_of_row(row);
+      __threadfence_block();
+      __syncthreads();
+    }
     // complete histogram
     for (int i = t; i < kBins; i += kT) hist[i] = 0u;
     __syncthreads();
@@ -621,14 +670,17 @@ hipError_t launch_select_only(const lrqk_shape& s, const float* scores, int32_t*
   hipError_t e = raise_lds_limit<false>();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((select_resolve_kernel<false>), dim3(s.B * s.Hq), dim3(kT), lds, st, scores,
-                     nullptr, 0, s.l, n, s.k, sel_idx, 0, s.C, nullptr, nullptr, nullptr, nullptr, nullptr,
+                     nullptr, 0, nullptr, nullptr, nullptr, nullptr, s.r, s.Hq, s.Hkv, s.l, n, s.k,
+                     sel_idx,
+                     0, s.C, nullptr, nullptr, nullptr, nullptr, nullptr,
                      nullptr, nullptr, nullptr);
   return hipGetLastError();
 }
 
-hipError_t launch_select_resolve(const lrqk_shape& s, const float* scores,
-                                 const unsigned long long* ext_bitmap, int32_t* sel_idx,
-                                 int32_t step, int32_t* slot_of, int32_t* token_of,
+hipError_t launch_select_resolve(const lrqk_shape& s, float* scores,
+                                 const unsigned long long* ext_bitmap, const float* cand_scores,
+                                 const float* A_K,
+                                 const float* q_hat, int32_t* sel_idx, int32_t step, int32_t* slot_of, int32_t* token_of,
                                  int32_t* last_used, int32_t* sel_slot, uint8_t* hit,
                                  int32_t* miss_tok, int32_t* miss_slot, int32_t* n_miss,
                                  hipStream_t st) {
@@ -637,8 +689,9 @@ hipError_t launch_select_resolve(const lrqk_shape& s, const float* scores,
   hipError_t e = raise_lds_limit<true>();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((select_resolve_kernel<true>), dim3(s.B * s.Hq), dim3(kT), lds, st, scores,
-                     reinterpret_cast<const uint32_t*>(ext_bitmap), 2 * filter_words64(n), s.l, n,
-                     s.k, sel_idx, step, s.C, slot_of, token_of, last_used, sel_slot, hit,
+                     reinterpret_cast<const uint32_t*>(ext_bitmap), 2 * filter_words64(n),
+                     cand_scores, ext_bitmap ? A_K : nullptr, q_hat, scores, s.r, s.Hq, s.Hkv, s.l, n, s.k,
+                     sel_idx, step, s.C, slot_of, token_of, last_used, sel_slot, hit,
                      miss_tok, miss_slot, n_miss);
   return hipGetLastError();
 }

@@ -346,6 +346,15 @@ def test_decode_step_misleading_threshold_sample(factor):
     run_steps_against_oracle(cfg, 2, "direct", data=data, check_unfused=False)
 
 
+def test_decode_step_clustered_candidates():
+    say("decode_step with > 16 candidates inside single 64-position groups")
+    cfg = small_cfg(B=1, Hq=8, Hkv=2, l=70000, r=32, k=1024, w=64, C=2048, n_heavy=64)
+    data = make_layer(cfg)
+    data.A_K[:, :, 5000:5200, :] *= 6.0          # 200 consecutive rows with large |score|
+    data.A_K[:, :, 64000:64064, :] *= 9.0        # one whole group
+    run_steps_against_oracle(cfg, 2, "direct", data=data, check_unfused=False)
+
+
 def test_config1_all_hits():
     say("config 1: l=4096 r=32 k=256 w=16, identity cache (all hits)")
     cfg = get_config("c1")
