@@ -415,12 +415,13 @@ int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
   const int parts_per_head = g.nsplit + ceil_div(s.k, g.rows_per_block);
 
   if (mode == LRQK_FETCH_DIRECT) {
-    LRQK_HIP(launch_fetch_direct(s, L->K_host, L->V_host, miss_tok, miss_slot, n_miss, L->cacheK,
-                                 L->cacheV, st));
+    // fetch and attention in one kernel: a row that missed is read from the pinned host store,
+    // used, and written into its slot, while the other rows stream from HBM
     LRQK_HIP(prof_mark(plan, 5, st));
-    LRQK_HIP(launch_attend_partial(s, kAttendAll, q, L->cacheK, L->cacheV, sel_slot, nullptr,
+    LRQK_HIP(launch_attend_partial(s, kAttendAllFetch, q, L->cacheK, L->cacheV, sel_slot, hit,
                                    nullptr, nullptr, L->liteK, L->liteV, plan->partials, g.nsplit,
-                                   g.rows_per_block, parts_per_head, 0, st));
+                                   g.rows_per_block, parts_per_head, 0, st, L->K_host, L->V_host,
+                                   sel_idx));
     LRQK_HIP(prof_mark(plan, 6, st));
     LRQK_HIP(launch_attend_combine(s, plan->partials, parts_per_head, g.nsplit, out, st));
     LRQK_HIP(prof_mark(plan, 7, st));

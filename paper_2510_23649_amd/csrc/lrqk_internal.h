@@ -100,13 +100,14 @@ hipError_t launch_cache_resolve(const lrqk_shape& s, const int32_t* sel_idx, int
                                 int32_t* sel_slot, uint8_t* hit, int32_t* miss_tok,
                                 int32_t* miss_slot, int32_t* n_miss, hipStream_t st);
 // which rows of Omega an attention launch covers
-enum AttendMode { kAttendAll = 0, kAttendHitsAndLite = 1, kAttendMisses = 2 };
+enum AttendMode { kAttendAll = 0, kAttendHitsAndLite = 1, kAttendMisses = 2, kAttendAllFetch = 3 };
 hipError_t launch_attend_partial(const lrqk_shape& s, int mode, const float* q, const void* cacheK,
                                  const void* cacheV, const int32_t* sel_slot, const uint8_t* hit,
                                  const int32_t* miss_slot, const int32_t* n_miss,
                                  const void* liteK, const void* liteV, float* partials,
                                  int nblocks, int rows_per_block, int parts_per_head,
-                                 int part_offset, hipStream_t st);
+                                 int part_offset, hipStream_t st, const void* K_host = nullptr,
+                                 const void* V_host = nullptr, const int32_t* sel_idx = nullptr);
 hipError_t launch_attend_combine(const lrqk_shape& s, const float* partials, int parts_per_head,
                                  int nparts, float* out, hipStream_t st);
 hipError_t launch_fetch_direct(const lrqk_shape& s, const void* K_host, const void* V_host,

@@ -24,7 +24,13 @@ namespace {
 
 constexpr int kAttThreads = 256;
 constexpr int kRowsPerPass = 16;  // 4 wavefronts x 4 row groups
-constexpr int kUnroll = 4;        // passes whose loads are in flight together
+#ifndef LRQK_ATT_UNROLL
+#define LRQK_ATT_UNROLL 4
+#endif
+#ifndef LRQK_ATT_MIN_RPB
+#define LRQK_ATT_MIN_RPB (kRowsPerPass * kUnroll)
+#endif
+constexpr int kUnroll = LRQK_ATT_UNROLL;  // passes whose loads are in flight together
 constexpr float kLog2e = 1.4426950408889634f;
 
 template <int CTRL>
@@ -67,6 +73,9 @@ struct RowChunk<true> {
   __device__ __forceinline__ void load(const void* row, int c) {
     raw = reinterpret_cast<const uint4*>(row)[c];
   }
+  __device__ __forceinline__ void store(void* row, int c) const {
+    reinterpret_cast<uint4*>(row)[c] = raw;
+  }
   __device__ __forceinline__ Chunk8 get() const { return unpack_bf16x8(raw); }
 };
 template <>
@@ -76,6 +85,10 @@ struct RowChunk<false> {
     a = reinterpret_cast<const float4*>(row)[2 * c];
     b = reinterpret_cast<const float4*>(row)[2 * c + 1];
   }
+  __device__ __forceinline__ void store(void* row, int c) const {
+    reinterpret_cast<float4*>(row)[2 * c] = a;
+    reinterpret_cast<float4*>(row)[2 * c + 1] = b;
+  }
   __device__ __forceinline__ Chunk8 get() const {
     Chunk8 o;
     o.v[0] = a.x; o.v[1] = a.y; o.v[2] = a.z; o.v[3] = a.w;
@@ -84,10 +97,21 @@ struct RowChunk<false> {
   }
 };
 
+// kAttendAllFetch: rows that missed the cache are read straight from the pinned host store
+// (device-visible host memory), used, and written into their cache slot on the way: the
+// fetch leg and the attention become one kernel, so the host-link reads of the few missing
+// rows overlap with the HBM reads of all the others.
+struct FetchSrc {
+  const char* K_host;       // [B,Hkv,l,d] rows
+  const char* V_host;
+  const int32_t* sel_idx;   // [B,Hq,k] position of each selected row
+  int l;
+};
+
 template <bool BF16>
 __global__ __launch_bounds__(kAttThreads) void attend_partial_kernel(
-    int mode, const float* __restrict__ q, const void* __restrict__ cacheK,
-    const void* __restrict__ cacheV, const int32_t* __restrict__ sel_slot,
+    int mode, FetchSrc fs, const float* __restrict__ q, const void* cacheK,
+    const void* cacheV, const int32_t* __restrict__ sel_slot,
     const uint8_t* __restrict__ hit, const int32_t* __restrict__ miss_slot,
     const int32_t* __restrict__ n_miss, const void* __restrict__ liteK,
     const void* __restrict__ liteV, float* __restrict__ partials, int Hq, int Hkv, int C, int k,
@@ -102,8 +126,16 @@ __global__ __launch_bounds__(kAttThreads) void attend_partial_kernel(
   const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
   const int grp = lane >> 4, c = lane & 15;
 
-  const char* __restrict__ Kc = static_cast<const char*>(cacheK) + (size_t)bh * C * ROWB;
-  const char* __restrict__ Vc = static_cast<const char*>(cacheV) + (size_t)bh * C * ROWB;
+  const char* Kc = static_cast<const char*>(cacheK) + (size_t)bh * C * ROWB;
+  const char* Vc = static_cast<const char*>(cacheV) + (size_t)bh * C * ROWB;
+  const char* __restrict__ Kh = nullptr;
+  const char* __restrict__ Vh = nullptr;
+  const int32_t* __restrict__ toks = nullptr;
+  if (mode == kAttendAllFetch) {
+    Kh = fs.K_host + ((size_t)b * Hkv + kvh) * (size_t)fs.l * ROWB;
+    Vh = fs.V_host + ((size_t)b * Hkv + kvh) * (size_t)fs.l * ROWB;
+    toks = fs.sel_idx + (size_t)bh * k;
+  }
   const char* __restrict__ Kl =
       static_cast<const char*>(liteK) + ((size_t)b * Hkv + kvh) * (size_t)w * ROWB;
   const char* __restrict__ Vl =
@@ -137,6 +169,8 @@ __global__ __launch_bounds__(kAttThreads) void attend_partial_kernel(
   for (int base = row_begin; base < row_end; base += kRowsPerPass * kUnroll) {
     const void* kp[kUnroll];
     const void* vp[kUnroll];
+    void* kdst[kUnroll];  // cache slot to fill when the row comes from the host store
+    void* vdst[kUnroll];
     bool ok[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
@@ -144,6 +178,8 @@ __global__ __launch_bounds__(kAttThreads) void attend_partial_kernel(
       ok[u] = j < row_end;
       kp[u] = nullptr;
       vp[u] = nullptr;
+      kdst[u] = nullptr;
+      vdst[u] = nullptr;
       if (ok[u]) {
         if (mode != kAttendMisses && j >= k) {
           kp[u] = Kl + (size_t)(j - k) * ROWB;
@@ -153,6 +189,15 @@ __global__ __launch_bounds__(kAttThreads) void attend_partial_kernel(
           ok[u] = s >= 0 && s < C && !(mode == kAttendHitsAndLite && hits[j] == 0);
           kp[u] = Kc + (size_t)s * ROWB;
           vp[u] = Vc + (size_t)s * ROWB;
+          if (mode == kAttendAllFetch && ok[u] && hits[j] == 0) {
+            const int32_t tok = toks[j];
+            if (tok >= 0 && tok < fs.l) {
+              kdst[u] = const_cast<char*>(Kc) + (size_t)s * ROWB;
+              vdst[u] = const_cast<char*>(Vc) + (size_t)s * ROWB;
+              kp[u] = Kh + (size_t)tok * ROWB;
+              vp[u] = Vh + (size_t)tok * ROWB;
+            }
+          }
         }
       }
     }
@@ -162,6 +207,12 @@ __global__ __launch_bounds__(kAttThreads) void attend_partial_kernel(
       if (ok[u]) {
         kc[u].load(kp[u], c);
         vc[u].load(vp[u], c);
+      }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+      if (kdst[u]) {
+        kc[u].store(kdst[u], c);
+        vc[u].store(vdst[u], c);
       }
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
@@ -293,7 +344,7 @@ __global__ __launch_bounds__(kCombThreads) void attend_combine_kernel(
 AttendGeom attend_geometry(int BHq, int k, int w) {
   const int rows = k + w;
   AttendGeom g;
-  g.rows_per_block = kRowsPerPass * kUnroll;  // 64
+  g.rows_per_block = LRQK_ATT_MIN_RPB;
   // fewer, larger workgroups once there are plenty of them
   while (g.rows_per_block < 512 && (long)ceil_div(rows, g.rows_per_block * 2) * BHq >= 2048)
     g.rows_per_block *= 2;
@@ -312,16 +363,21 @@ hipError_t launch_attend_partial(const lrqk_shape& s, int mode, const float* q, 
                                  const int32_t* miss_slot, const int32_t* n_miss,
                                  const void* liteK, const void* liteV, float* partials,
                                  int nblocks, int rows_per_block, int parts_per_head,
-                                 int part_offset, hipStream_t st) {
+                                 int part_offset, hipStream_t st, const void* K_host,
+                                 const void* V_host, const int32_t* sel_idx) {
   if (nblocks <= 0) return hipSuccess;
+  if (mode == kAttendAllFetch && (!K_host || !V_host || !sel_idx || !hit))
+    return hipErrorInvalidValue;
+  const FetchSrc fs{static_cast<const char*>(K_host), static_cast<const char*>(V_host), sel_idx,
+                    s.l};
   const dim3 grid(nblocks, s.B * s.Hq);
   if (s.kv_dtype == LRQK_KV_BF16)
-    hipLaunchKernelGGL((attend_partial_kernel<true>), grid, dim3(kAttThreads), 0, st, mode, q,
+    hipLaunchKernelGGL((attend_partial_kernel<true>), grid, dim3(kAttThreads), 0, st, mode, fs, q,
                        cacheK, cacheV, sel_slot, hit, miss_slot, n_miss, liteK, liteV, partials,
                        s.Hq, s.Hkv, s.C, s.k, s.w, rows_per_block, parts_per_head, part_offset,
                        s.scale);
   else
-    hipLaunchKernelGGL((attend_partial_kernel<false>), grid, dim3(kAttThreads), 0, st, mode, q,
+    hipLaunchKernelGGL((attend_partial_kernel<false>), grid, dim3(kAttThreads), 0, st, mode, fs, q,
                        cacheK, cacheV, sel_slot, hit, miss_slot, n_miss, liteK, liteV, partials,
                        s.Hq, s.Hkv, s.C, s.k, s.w, rows_per_block, parts_per_head, part_offset,
                        s.scale);
