@@ -1,10 +1,16 @@
 // C ABI of liblrqk: argument validation, the plan object, the fetch leg's host
 // side and the fused decode step.  Every kernel lives in its own source file;
 // this file only checks, carves workspaces and enqueues.
+#include <atomic>
 #include <cmath>
+#include <condition_variable>
 #include <cstdlib>
 #include <cstring>
+#include <functional>
+#include <mutex>
 #include <new>
+#include <thread>
+#include <vector>
 
 #include "lrqk_internal.h"
 
@@ -40,6 +46,65 @@ static bool all_aligned16(std::initializer_list<const void*> ps) {
   return true;
 }
 
+// A few host threads that split the row gather of the staged fetch (random 256..512-byte
+// reads from the pinned K/V store: one thread is bound by memory latency).
+class HostPool {
+ public:
+  explicit HostPool(int n) {
+    for (int i = 0; i < n; ++i) workers_.emplace_back([this, i] { loop(i); });
+  }
+  ~HostPool() {
+    {
+      std::lock_guard<std::mutex> g(mu_);
+      stop_ = true;
+      ++epoch_;
+    }
+    cv_.notify_all();
+    for (auto& w : workers_) w.join();
+  }
+  int size() const { return (int)workers_.size(); }
+  // run fn(worker_index, n_workers) on every worker and wait for all of them
+  void run(const std::function<void(int, int)>& fn) {
+    {
+      std::lock_guard<std::mutex> g(mu_);
+      fn_ = &fn;
+      pending_ = (int)workers_.size();
+      ++epoch_;
+    }
+    cv_.notify_all();
+    std::unique_lock<std::mutex> g(mu_);
+    done_.wait(g, [this] { return pending_ == 0; });
+    fn_ = nullptr;
+  }
+
+ private:
+  void loop(int idx) {
+    unsigned long seen = 0;
+    for (;;) {
+      const std::function<void(int, int)>* fn;
+      {
+        std::unique_lock<std::mutex> g(mu_);
+        cv_.wait(g, [&] { return epoch_ != seen; });
+        seen = epoch_;
+        if (stop_) return;
+        fn = fn_;
+      }
+      (*fn)(idx, (int)workers_.size());
+      {
+        std::lock_guard<std::mutex> g(mu_);
+        if (--pending_ == 0) done_.notify_all();
+      }
+    }
+  }
+  std::vector<std::thread> workers_;
+  std::mutex mu_;
+  std::condition_variable cv_, done_;
+  const std::function<void(int, int)>* fn_ = nullptr;
+  unsigned long epoch_ = 0;
+  int pending_ = 0;
+  bool stop_ = false;
+};
+
 }  // namespace lrqk
 
 using namespace lrqk;
@@ -72,6 +137,8 @@ struct lrqk_plan {
   // optional per-phase timing of lrqk_decode_step (lrqk_plan_profile)
   int prof_cap, prof_n;
   hipEvent_t* prof_ev;  // [prof_cap][LRQK_PROFILE_MARKS]
+  HostPool* pool;       // host threads of the staged fetch (created on first use)
+  int64_t* h_rowbase;   // [BHq + 1] first staging row of each head (host, not pinned)
 };
 
 static void prof_free(lrqk_plan* p) {
@@ -206,6 +273,8 @@ int lrqk_plan_destroy(lrqk_plan* p) {
   for (void* q : host)
     if (q) (void)hipHostFree(q);
   prof_free(p);
+  delete p->pool;
+  std::free(p->h_rowbase);
   if (p->ev_main) (void)hipEventDestroy(p->ev_main);
   if (p->ev_side) (void)hipEventDestroy(p->ev_side);
   if (p->side) (void)hipStreamDestroy(p->side);
@@ -300,25 +369,53 @@ static int staged_fetch(lrqk_plan* p, const lrqk_shape& s, const void* K_host, c
   const char* Kh = static_cast<const char*>(K_host);
   const char* Vh = static_cast<const char*>(V_host);
   char* stage = static_cast<char*>(p->h_stage);
+  // staging rows are laid out head after head: prefix sums of the per-head counts
+  if (!p->h_rowbase) {
+    p->h_rowbase = static_cast<int64_t*>(std::malloc(((size_t)p->BHq + 1) * sizeof(int64_t)));
+    if (!p->h_rowbase) return LRQK_ENOMEM;
+  }
   int64_t total = 0;
   int mx = 0;
   for (size_t bh = 0; bh < BHq; ++bh) {
     const int nm = p->h_nmiss[bh];
-    if (nm <= 0) continue;
-    const int cnt = nm < s.k ? nm : s.k;
+    const int cnt = nm <= 0 ? 0 : (nm < s.k ? nm : s.k);
     if (cnt > mx) mx = cnt;
-    const size_t b = bh / s.Hq, h = bh % s.Hq, kvh = h / G;
-    const char* Ks = Kh + (b * s.Hkv + kvh) * (size_t)s.l * rowB;
-    const char* Vs = Vh + (b * s.Hkv + kvh) * (size_t)s.l * rowB;
-    for (int j = 0; j < cnt; ++j) {
+    p->h_rowbase[bh] = total;
+    total += cnt;
+  }
+  p->h_rowbase[BHq] = total;
+  auto gather = [&](int widx, int nworkers) {
+    // worker widx takes the staging rows [lo, hi)
+    const int64_t lo = total * widx / nworkers, hi = total * (widx + 1) / nworkers;
+    size_t bh = 0;
+    for (int64_t i = lo; i < hi; ++i) {
+      while (p->h_rowbase[bh + 1] <= i) ++bh;
+      const int j = (int)(i - p->h_rowbase[bh]);
+      const size_t b = bh / s.Hq, h = bh % s.Hq, kvh = h / G;
       const int32_t tok = p->h_miss_tok[bh * s.k + j];
       const int32_t slot = p->h_miss_slot[bh * s.k + j];
-      if (tok < 0 || tok >= s.l || slot < 0 || slot >= s.C) continue;
-      std::memcpy(stage + (size_t)total * 2 * rowB, Ks + (size_t)tok * rowB, rowB);
-      std::memcpy(stage + (size_t)total * 2 * rowB + rowB, Vs + (size_t)tok * rowB, rowB);
-      p->h_rowdst[total] = (int64_t)bh * s.C + slot;
-      ++total;
+      if (tok < 0 || tok >= s.l || slot < 0 || slot >= s.C) {
+        p->h_rowdst[i] = -1;  // skipped by the scatter kernel
+        continue;
+      }
+      const char* Ks = Kh + ((b * s.Hkv + kvh) * (size_t)s.l + (size_t)tok) * rowB;
+      const char* Vs = Vh + ((b * s.Hkv + kvh) * (size_t)s.l + (size_t)tok) * rowB;
+      std::memcpy(stage + (size_t)i * 2 * rowB, Ks, rowB);
+      std::memcpy(stage + (size_t)i * 2 * rowB + rowB, Vs, rowB);
+      p->h_rowdst[i] = (int64_t)bh * s.C + slot;
     }
+  };
+  if (total >= 256) {
+    if (!p->pool) {
+      unsigned hw = std::thread::hardware_concurrency();
+      int nthreads = hw == 0 ? 4 : (hw > 16 ? 8 : (int)(hw / 2));
+      if (nthreads < 1) nthreads = 1;
+      p->pool = new (std::nothrow) HostPool(nthreads);
+      if (!p->pool) return LRQK_ENOMEM;
+    }
+    p->pool->run(gather);
+  } else if (total > 0) {
+    gather(0, 1);
   }
   if (max_nmiss) *max_nmiss = mx;
   if (total_out) *total_out = total;
