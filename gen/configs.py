@@ -68,11 +68,11 @@ CONFIGS = {
                          layers=32, n_heavy=256, drift=0.1, rho=0.97),
     # 4: Qwen2.5-7B-shaped single layer, batch 8, 1 % heavy tokens, ~85 % hits.
     "c4": WorkloadConfig(name="c4", B=8, Hq=28, Hkv=4, l=65536, r=32, k=1024, w=64, C=2048,
-                         n_heavy=655, pool_mult=4, drift=0.1, rho=0.95),
+                         n_heavy=655, pool_mult=4, drift=0.1, rho=0.96),
     # 5: miss-heavy stress, batch 16 at 128K, heavy set re-drawn every 4 steps.
     #    The cache size is not stated for this workload; 4096 slots as in config 3.
     "c5": WorkloadConfig(name="c5", B=16, Hq=32, Hkv=8, l=131072, r=32, k=2048, w=64, C=4096,
-                         n_heavy=256, drift=0.1, redraw_every=4, rho=0.6),
+                         n_heavy=256, drift=0.1, redraw_every=4, rho=0.8),
 }
 
 

@@ -163,8 +163,9 @@ class QueryStream:
         window = 2.0 * math.pi * c.n_heavy / max(c.pool, 1)
         if c.redraw_every > 0:
             epoch, within = divmod(self.t, c.redraw_every)
-            # a fresh, far-away window for every epoch: golden-angle hops
-            base = self._theta0 + epoch * 2.0 * math.pi * 0.381966011250105
+            # a fresh heavy window for every epoch: hop by one and a half windows, so the new
+            # window shares no pool token with the old one
+            base = self._theta0 + epoch * 1.5 * window
             return base + within * c.drift * window
         return self._theta0 + self.t * c.drift * window
 

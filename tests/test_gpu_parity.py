@@ -379,6 +379,25 @@ def test_config4_qwen_shape_reduced_batch():
     run_steps_against_oracle(get_config("c4", B=2), 3, "direct", check_unfused=False)
 
 
+@pytest.mark.timeout(600)
+def test_config4_full_batch():
+    say("config 4 at full size: batch 8, 28 q / 4 kv heads, l = 65536, k = 1024, C = 2048")
+    cfg = get_config("c4")
+    rates = run_steps_against_oracle(cfg, 4, "direct", data=make_layer(cfg, 0, device=DEV),
+                                     check_unfused=False)
+    assert 0.10 < rates[-1] < 0.25            # the workload asks for about 85 % hits
+
+
+@pytest.mark.timeout(900)
+def test_config5_miss_heavy_full_batch():
+    say("config 5 at full size: batch 16, l = 131072, k = 2048, heavy set re-drawn every 4 steps")
+    cfg = get_config("c5")
+    rates = run_steps_against_oracle(cfg, 6, "direct", data=make_layer(cfg, 0, device=DEV),
+                                     check_unfused=False)
+    assert all(0.2 < r < 0.8 for r in rates[1:])    # 30-60 % misses on average, more at a re-draw
+    assert 0.30 <= sum(rates[1:]) / len(rates[1:]) <= 0.60
+
+
 def test_rerun_is_deterministic():
     say("two runs of the same steps give identical bits")
     cfg = small_cfg()
