@@ -45,8 +45,14 @@ __global__ __launch_bounds__(kTileRows) void proxy_scores_kernel(
     const float* __restrict__ A_K, const float* __restrict__ q_hat, float* __restrict__ scores,
     int l, int Hq, int Hkv, int n, const uint32_t* __restrict__ thr,
     unsigned long long* __restrict__ bitmap, float* __restrict__ cand_scores, int words64) {
-  constexpr int V4 = R / 4;       // 16-byte chunks per row
-  constexpr int ROW4 = V4 + 1;    // padded LDS row stride in 16-byte units
+  // The tile goes through LDS in column phases of at most 32 floats, so that the LDS
+  // footprint (and with it the number of resident workgroups) does not grow with r; the
+  // fma chain simply continues from one phase to the next, in the same order.
+  constexpr int CH = R < 32 ? R : 32;  // columns per phase
+  constexpr int NPH = R / CH;          // phases
+  constexpr int V4 = CH / 4;           // 16-byte chunks per row and phase
+  constexpr int ROW4 = V4 + 1;         // padded LDS row stride in 16-byte units
+  static_assert(R % CH == 0, "rank must be a multiple of the phase width");
   __shared__ float4 tile[kTileRows * ROW4];
 
   const int bkv = blockIdx.y;
@@ -57,33 +63,44 @@ __global__ __launch_bounds__(kTileRows) void proxy_scores_kernel(
   const int t = threadIdx.x;
   const int row0 = blockIdx.x * kTileRows;
   const float4* __restrict__ src = reinterpret_cast<const float4*>(A + (size_t)row0 * R);
-  const int nvalid = min(kTileRows, l - row0) * V4;
+  const int rows_valid = min(kTileRows, l - row0);
 
-  float4 pre[V4];
+  // all phases' loads are issued up front: chunk idx of phase p is row idx / V4,
+  // 16-byte column p * V4 + idx % V4 (8 lanes read 128 contiguous bytes of a row)
+  float4 pre[NPH][V4];
 #pragma unroll
-  for (int i = 0; i < V4; ++i) {
-    const int idx = i * kTileRows + t;
-    pre[i] = idx < nvalid ? load_streaming(src + idx) : make_float4(0.f, 0.f, 0.f, 0.f);
-  }
+  for (int p = 0; p < NPH; ++p)
 #pragma unroll
-  for (int i = 0; i < V4; ++i) {
-    const int idx = i * kTileRows + t;
-    tile[(idx / V4) * ROW4 + (idx % V4)] = pre[i];
-  }
-  __syncthreads();
+    for (int i = 0; i < V4; ++i) {
+      const int idx = i * kTileRows + t;
+      const int rr = idx / V4, cc = idx % V4;
+      pre[p][i] = rr < rows_valid ? load_streaming(src + (size_t)rr * (R / 4) + p * V4 + cc)
+                                  : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
 
   float acc[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) acc[g] = 0.0f;
 #pragma unroll
-  for (int c = 0; c < V4; ++c) {
-    const float4 a = tile[t * ROW4 + c];
+  for (int p = 0; p < NPH; ++p) {
+    if (p > 0) __syncthreads();  // the previous phase has been consumed
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-      acc[g] = __builtin_fmaf(a.x, qh[g * R + 4 * c + 0], acc[g]);
-      acc[g] = __builtin_fmaf(a.y, qh[g * R + 4 * c + 1], acc[g]);
-      acc[g] = __builtin_fmaf(a.z, qh[g * R + 4 * c + 2], acc[g]);
-      acc[g] = __builtin_fmaf(a.w, qh[g * R + 4 * c + 3], acc[g]);
+    for (int i = 0; i < V4; ++i) {
+      const int idx = i * kTileRows + t;
+      tile[(idx / V4) * ROW4 + (idx % V4)] = pre[p][i];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < V4; ++c) {
+      const float4 a = tile[t * ROW4 + c];
+      const int j = p * CH + 4 * c;
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        acc[g] = __builtin_fmaf(a.x, qh[g * R + j + 0], acc[g]);
+        acc[g] = __builtin_fmaf(a.y, qh[g * R + j + 1], acc[g]);
+        acc[g] = __builtin_fmaf(a.z, qh[g * R + j + 2], acc[g]);
+        acc[g] = __builtin_fmaf(a.w, qh[g * R + j + 3], acc[g]);
+      }
     }
   }
   const int row = row0 + t;
