@@ -89,7 +89,7 @@ typedef struct lrqk_shape {
 } lrqk_shape;
 
 /* Which call a workspace is sized for (lrqk_workspace_bytes). */
-enum { LRQK_WS_SELECT = 1, LRQK_WS_ATTEND = 2 };
+enum { LRQK_WS_SELECT = 1, LRQK_WS_ATTEND = 2, LRQK_WS_UPDATE = 3 };
 
 int lrqk_version(void);
 const char* lrqk_status_string(int status);
@@ -179,7 +179,9 @@ int lrqk_cache_resolve(const lrqk_shape* shape, const int32_t* sel_idx, int32_t 
  *   q                device fp32 [B,Hq,d]
  *   cacheK, cacheV   device kv_dtype [B,Hq,C,d]
  *   sel_slot         device int32 [B,Hq,k]
- *   liteK, liteV     device kv_dtype [B,Hkv,w,d] (rows l-w .. l-1; may be NULL when w == 0)
+ *   liteK, liteV     device kv_dtype [B,Hkv,w,d]: the rows of positions l-w .. l-1, kept as a
+ *                    ring: row j holds the position p of [l-w, l) with p mod w == j (the
+ *                    attention does not depend on their order; may be NULL when w == 0)
  *   out              device fp32 [B,Hq,d]   written
  *   workspace        device, >= lrqk_workspace_bytes(shape, LRQK_WS_ATTEND), 256-byte aligned
  */
@@ -257,6 +259,46 @@ int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
                      const lrqk_layer* layer, const float* q_hat, const float* q, float* out,
                      int mode, const lrqk_step_debug* dbg, int64_t* total_miss_out,
                      void* stream);
+
+/*
+ * u1 — decode-time update of the factors (Alg. 2, from the initial guess of k_hat to the two
+ * gradient steps on B_Q and B_K; Sec. 4.2 decode objective and update rules; App. A.2 step
+ * lengths).  Runs BEFORE the step's proxy scores: it produces the q_hat that lrqk_proxy_scores
+ * / lrqk_decode_step take, and the k_hat that lrqk_append_token adds to A_K.
+ * For the new projections q_t (per query head) and k_t (per KV head):
+ *   k_hat <- k B_K^T (B_K B_K^T)^-1                                   (lambda_d1 = 0 guess)
+ *   n_iter times:
+ *     q_hat <- m_lq M_rq^-1 for every query head, with
+ *        m_lq = q B_Q^T + lambda_d1 (q.k) k_hat + lambda_d2 (q K_Om^T) A_Om
+ *        M_rq = B_Q B_Q^T + lambda_d1 k_hat^T k_hat + lambda_d2 A_Om^T A_Om
+ *     k_hat <- (k B_K^T + lambda_d1 sum_g (q_g.k) q_hat_g)
+ *              (B_K B_K^T + lambda_d1 sum_g q_hat_g^T q_hat_g)^-1     (sums over the G query
+ *              heads that share the KV head; G = 1 gives the paper's rule)
+ *   B_Q <- B_Q - eta_Q q_hat^T (q_hat B_Q - q),  B_K <- B_K - eta_K k_hat^T (k_hat B_K - k),
+ *   each eta the exact minimiser along its gradient; a zero gradient leaves B unchanged.
+ * Omega = the rows attended at the previous step: the previous selection (A_K rows at
+ * sel_idx_prev, K rows in the cache slots sel_slot_prev) and the lite window [l-w, l) (A_K
+ * rows l-w .. l-1, K rows in layer->liteK); q K_Om^T is the raw dot product.  Entries of the
+ * previous selection with a position outside [0, l) or a slot outside [0, C) are left out.
+ * The loop runs exactly n_iter rounds (the paper uses at most 2); there is no tolerance test.
+ * All arithmetic is fp32 (App. B.1).  Supported ranks: r in {8, 16, 32, 64}.
+ *   layer          A_K, cacheK and liteK are read (device)
+ *   sel_idx_prev, sel_slot_prev  device int32 [B,Hq,k], as written by the previous step
+ *   q              device fp32 [B,Hq,d]
+ *   k_new          device kv_dtype [B,Hkv,d]
+ *   B_Q            device fp32 [B,Hq,r,d]   updated in place
+ *   B_K            device fp32 [B,Hkv,r,d]  updated in place
+ *   lambda_d1, lambda_d2  >= 0, finite;  1 <= n_iter <= 64
+ *   q_hat          device fp32 [B,Hq,r]   written
+ *   k_hat          device fp32 [B,Hkv,r]  written
+ *   workspace      device, >= lrqk_workspace_bytes(shape, LRQK_WS_UPDATE), 256-byte aligned
+ * LRQK_ESHAPE for an unsupported rank, LRQK_ENOMEM if ws_bytes is too small.
+ */
+int lrqk_factor_update(const lrqk_shape* shape, const lrqk_layer* layer,
+                       const int32_t* sel_idx_prev, const int32_t* sel_slot_prev, const float* q,
+                       const void* k_new, float* B_Q, float* B_K, float lambda_d1,
+                       float lambda_d2, int32_t n_iter, float* q_hat, float* k_hat,
+                       void* workspace, size_t ws_bytes, void* stream);
 
 /*
  * Instrumentation (not part of the method): per-phase GPU time of lrqk_decode_step,

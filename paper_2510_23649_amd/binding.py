@@ -13,7 +13,7 @@ _lib = None
 
 LRQK_KV_BF16, LRQK_KV_F32 = 0, 1
 LRQK_FETCH_STAGED, LRQK_FETCH_DIRECT = 0, 1
-LRQK_WS_SELECT, LRQK_WS_ATTEND = 1, 2
+LRQK_WS_SELECT, LRQK_WS_ATTEND, LRQK_WS_UPDATE = 1, 2, 3
 
 
 class LrqkError(RuntimeError):
@@ -73,6 +73,8 @@ def load_library():
         "lrqk_cache_init": (C.c_int, [sp, vp, vp, vp, vp]),
         "lrqk_cache_resolve": (C.c_int, [sp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "lrqk_sparse_attend": (C.c_int, [sp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
+        "lrqk_factor_update": (C.c_int, [sp, C.POINTER(Layer), vp, vp, vp, vp, vp, vp, C.c_float,
+                                         C.c_float, i32, vp, vp, vp, sz, vp]),
         "lrqk_plan_create": (C.c_int, [sp, C.POINTER(vp)]),
         "lrqk_plan_destroy": (C.c_int, [vp]),
         "lrqk_fetch_misses": (C.c_int, [vp, sp, vp, vp, vp, vp, vp, vp, vp, C.c_int,
@@ -96,7 +98,7 @@ EXPORTS = ["lrqk_version", "lrqk_status_string", "lrqk_last_hip_error", "lrqk_va
            "lrqk_workspace_bytes", "lrqk_proxy_scores", "lrqk_select_topk", "lrqk_cache_init",
            "lrqk_cache_resolve", "lrqk_sparse_attend", "lrqk_plan_create", "lrqk_plan_destroy",
            "lrqk_fetch_misses", "lrqk_decode_step", "lrqk_plan_profile", "lrqk_plan_profile_read", "lrqk_calib_copy",
-           "lrqk_plan_time_proxy_pass"]
+           "lrqk_plan_time_proxy_pass", "lrqk_factor_update"]
 
 
 def _check(status: int, where: str):
@@ -115,7 +117,9 @@ def _dev(t: Optional[torch.Tensor], dtype=None):
     return t.data_ptr()
 
 
-def _pinned(t: torch.Tensor):
+def _pinned(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
     if t.is_cuda or not t.is_pinned() or not t.is_contiguous():
         raise ValueError("expected a contiguous pinned host tensor")
     return t.data_ptr()
@@ -184,6 +188,16 @@ def lrqk_sparse_attend(shape, q, cacheK, cacheV, sel_slot, liteK, liteV, out, wo
         _dev(sel_slot, torch.int32), _dev(liteK), _dev(liteV), _dev(out, torch.float32),
         _dev(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
         "lrqk_sparse_attend")
+
+
+def lrqk_factor_update(shape, layer, sel_idx_prev, sel_slot_prev, q, k_new, B_Q, B_K, lambda_d1,
+                       lambda_d2, n_iter, q_hat, k_hat, workspace, stream=None):
+    _check(load_library().lrqk_factor_update(
+        C.byref(shape), C.byref(layer), _dev(sel_idx_prev, torch.int32),
+        _dev(sel_slot_prev, torch.int32), _dev(q, torch.float32), _dev(k_new),
+        _dev(B_Q, torch.float32), _dev(B_K, torch.float32), float(lambda_d1), float(lambda_d2),
+        int(n_iter), _dev(q_hat, torch.float32), _dev(k_hat, torch.float32), _dev(workspace),
+        workspace.numel() * workspace.element_size(), _stream(stream)), "lrqk_factor_update")
 
 
 def lrqk_calib_copy(dst, src, stream=None):

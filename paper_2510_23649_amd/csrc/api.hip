@@ -183,6 +183,7 @@ size_t lrqk_workspace_bytes(const lrqk_shape* shape, int which) {
   const int BHq = shape->B * shape->Hq;
   if (which == LRQK_WS_SELECT) return carve_select_ws(nullptr, BHq, shape->k).bytes;
   if (which == LRQK_WS_ATTEND) return attend_ws_bytes(BHq, shape->k, shape->w, 1);
+  if (which == LRQK_WS_UPDATE) return factor_update_supported(*shape) ? update_ws_bytes(*shape) : 0;
   return 0;
 }
 
@@ -254,6 +255,31 @@ int lrqk_sparse_attend(const lrqk_shape* shape, const float* q, const void* cach
                                  nullptr, liteK, liteV, partials, g.nsplit, g.rows_per_block,
                                  g.nsplit, 0, st));
   LRQK_HIP(launch_attend_combine(*shape, partials, g.nsplit, g.nsplit, out, st));
+  return LRQK_OK;
+}
+
+int lrqk_factor_update(const lrqk_shape* shape, const lrqk_layer* layer,
+                       const int32_t* sel_idx_prev, const int32_t* sel_slot_prev, const float* q,
+                       const void* k_new, float* B_Q, float* B_K, float lambda_d1,
+                       float lambda_d2, int32_t n_iter, float* q_hat, float* k_hat,
+                       void* workspace, size_t ws_bytes, void* stream) {
+  const int rc = check_shape(shape);
+  if (rc != LRQK_OK) return rc;
+  if (!factor_update_supported(*shape)) return LRQK_ESHAPE;
+  if (!layer || n_iter < 1 || n_iter > 64) return LRQK_EINVAL;
+  if (!(lambda_d1 >= 0.0f) || !(lambda_d2 >= 0.0f) || std::isinf(lambda_d1) ||
+      std::isinf(lambda_d2))
+    return LRQK_EINVAL;
+  if (!all_aligned16({layer->A_K, layer->cacheK, sel_idx_prev, sel_slot_prev, q, k_new, B_Q, B_K,
+                      q_hat, k_hat}) ||
+      !workspace || !aligned256(workspace))
+    return LRQK_EINVAL;
+  if (shape->w > 0 && !all_aligned16({layer->liteK})) return LRQK_EINVAL;
+  if (ws_bytes < update_ws_bytes(*shape)) return LRQK_ENOMEM;
+  LRQK_HIP(launch_factor_update(*shape, layer->A_K, layer->cacheK, layer->liteK, sel_idx_prev,
+                                sel_slot_prev, q, k_new, B_Q, B_K, lambda_d1, lambda_d2, n_iter,
+                                q_hat, k_hat, static_cast<float*>(workspace),
+                                static_cast<hipStream_t>(stream)));
   return LRQK_OK;
 }
 

@@ -1,0 +1,503 @@
+// u1 — decode-time update of the factors (Alg. 2 from the initial guess of k_hat to the
+// two gradient steps; Sec. 4.2 update rules for q_hat_t, k_hat_t, B_Q, B_K; App. A.2 optimal
+// step lengths).
+//
+// Two launches.
+//
+//  1. factor_gram_kernel: everything that is a sum over many rows.  For a list of rows a_i
+//     (r floats each) with weights u_i it produces  S = sum_i a_i^T a_i  (r x r)  and
+//     g = sum_i u_i a_i  (r).  Three kinds of jobs share the code:
+//       * Omega of a query head (the k rows selected at the previous step, read from their
+//         cache slots, and the w lite rows): a_i = row of A_K, u_i = q . K_i.  This gives
+//         A_Om^T A_Om and q K_Om^T A_Om.  The row list of a head is cut into chunks of 256
+//         rows, one workgroup each, so that batch-1 steps still use hundreds of CUs; K rows
+//         are read by 16 lanes each exactly as the attention kernel reads them;
+//       * B_Q of a query head, read column-wise: a_i = column i of B_Q, u_i = q_i, which
+//         gives B_Q B_Q^T and q B_Q^T;
+//       * B_K of a KV head with u = k_t: B_K B_K^T and k B_K^T.
+//     A batch of 64 rows is staged in LDS, then every thread owns r*r/256 entries of S and
+//     adds the batch's 64 outer products to them; partial sums per chunk go to the
+//     workspace and are added up, in chunk order, by the second kernel: no atomics, the
+//     result does not depend on scheduling.
+//
+//  2. factor_solve_kernel: one workgroup per (batch, KV head), one wavefront per query
+//     head of the group.  The r x r systems (r <= 64) are solved inside a wavefront: lane i
+//     holds row i of the matrix in registers, a right-looking Cholesky factorisation takes
+//     column j from lane registers with v_readlane (all register indices are compile-time
+//     constants), the two triangular solves follow the same pattern, with one transpose of
+//     the factor through LDS in between.  The alternating updates of q_hat (per query
+//     head) and k_hat (per KV head, summed over the group's heads) exchange q_hat through
+//     LDS; every wavefront solves the small k_hat system redundantly, which is cheaper than
+//     a second exchange.  The same kernel then applies the two rank-one gradient steps to
+//     B_Q and B_K in place.
+//
+// All arithmetic is fp32 (App. B.1 runs these updates in fp32).
+#include "lrqk_device.h"
+#include "lrqk_internal.h"
+
+namespace lrqk {
+namespace {
+
+constexpr int kGramThreads = 256;
+constexpr int kGramBatch = 64;   // rows staged in LDS at a time
+
+template <int CTRL>
+__device__ __forceinline__ float fu_dpp(float v) {
+  return __int_as_float(
+      __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float row16_sum(float v) {
+  v += fu_dpp<0x128>(v);  // row_ror:8
+  v += fu_dpp<0x124>(v);  // row_ror:4
+  v += fu_dpp<0x122>(v);  // row_ror:2
+  v += fu_dpp<0x121>(v);  // row_ror:1
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+  v = row16_sum(v);
+  // the four 16-lane rows of the wavefront
+  const float a = __shfl(v, 0), b = __shfl(v, 16), c = __shfl(v, 32), e = __shfl(v, 48);
+  return (a + b) + (c + e);
+}
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) {
+  return __uint_as_float((uint32_t)h << 16);
+}
+template <bool BF16>
+__device__ __forceinline__ float kv_load(const void* row, int j) {
+  if (BF16) return bf16_to_f32(static_cast<const uint16_t*>(row)[j]);
+  return static_cast<const float*>(row)[j];
+}
+
+// q . K_row for the 16 lanes that share a row; lane c of the 16 takes elements 8c .. 8c+7.
+template <bool BF16>
+__device__ __forceinline__ float dot_chunk(const void* row, int c, const float (&qv)[8]) {
+  float x[8];
+  if (BF16) {
+    const uint4 u = static_cast<const uint4*>(row)[c];
+    x[0] = __uint_as_float(u.x << 16); x[1] = __uint_as_float(u.x & 0xffff0000u);
+    x[2] = __uint_as_float(u.y << 16); x[3] = __uint_as_float(u.y & 0xffff0000u);
+    x[4] = __uint_as_float(u.z << 16); x[5] = __uint_as_float(u.z & 0xffff0000u);
+    x[6] = __uint_as_float(u.w << 16); x[7] = __uint_as_float(u.w & 0xffff0000u);
+  } else {
+    const float4 a = static_cast<const float4*>(row)[2 * c];
+    const float4 b = static_cast<const float4*>(row)[2 * c + 1];
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+    x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+  }
+  float acc = 0.0f;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) acc = __builtin_fmaf(x[j], qv[j], acc);
+  return acc;
+}
+
+struct GramArgs {
+  const float* A_K;              // [B,Hkv,l_rows,r]
+  const void* cacheK;            // [B,Hq,C,d]
+  const void* liteK;             // [B,Hkv,w,d], row j holds the position p of [l-w,l), p % w == j
+  const int32_t* sel_idx_prev;   // [B,Hq,k]
+  const int32_t* sel_slot_prev;  // [B,Hq,k]
+  const float* q;                // [B,Hq,d]
+  const void* k_new;             // [B,Hkv,d]
+  const float* B_Q;              // [B,Hq,r,d]
+  const float* B_K;              // [B,Hkv,r,d]
+  float* gram_om;                // [B*Hq][nchunk][r*r + r]
+  float* gram_q;                 // [B*Hq][r*r + r]
+  float* gram_k;                 // [B*Hkv][r*r + r]
+  int Hq, Hkv, l, l_rows, k, w, C, nchunk, chunk_rows;
+};
+
+template <int R, bool BF16>
+__global__ __launch_bounds__(kGramThreads) void factor_gram_kernel(GramArgs a) {
+  constexpr int kEntries = R * R;
+  constexpr int EPT = kEntries >= kGramThreads ? kEntries / kGramThreads : 1;
+  constexpr int kActive = kEntries >= kGramThreads ? kGramThreads : kEntries;
+  constexpr int LDA = R + 4;  // padded LDS row, keeps 16-byte alignment
+  constexpr size_t ROWB = kD * (BF16 ? 2 : 4);
+  static_assert(EPT <= R && R % EPT == 0, "a thread's entries stay inside one row of S");
+  __shared__ __align__(16) float a_s[kGramBatch * LDA];
+  __shared__ float u_s[kGramBatch];
+  __shared__ int pos_s[kGramBatch];
+  __shared__ const char* krow_s[kGramBatch];
+
+  const int bh = blockIdx.y, job = blockIdx.x, t = threadIdx.x;
+  const int b = bh / a.Hq, h = bh - b * a.Hq;
+  const int G = a.Hq / a.Hkv;
+  const int kvh = h / G;
+  const int bkv = b * a.Hkv + kvh;
+  if (job == a.nchunk + 1 && h != kvh * G) return;  // the B_K job runs once per KV head
+
+  const int e0 = t * EPT;
+  const int p = e0 / R, q0 = e0 % R;
+  float acc[EPT];
+#pragma unroll
+  for (int e = 0; e < EPT; ++e) acc[e] = 0.0f;
+  float gacc = 0.0f;
+
+  float* out;
+  if (job < a.nchunk) {
+    // ---- a chunk of the rows of Omega --------------------------------------------------
+    out = a.gram_om + ((size_t)bh * a.nchunk + job) * (kEntries + R);
+    const int n_om = a.k + a.w;
+    const int i_begin = job * a.chunk_rows;
+    const int i_end = min(n_om, i_begin + a.chunk_rows);
+    const float* __restrict__ Ahead = a.A_K + (size_t)bkv * (size_t)a.l_rows * R;
+    const char* Kc = static_cast<const char*>(a.cacheK) + (size_t)bh * a.C * ROWB;
+    const char* Kl = static_cast<const char*>(a.liteK) + (size_t)bkv * a.w * ROWB;
+    const int c16 = t & 15, rsub = t >> 4;
+    float qv[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) qv[j] = a.q[(size_t)bh * kD + c16 * 8 + j];
+    const int lite0 = a.l - a.w;  // first position of the lite window
+    for (int i0 = i_begin; i0 < i_end; i0 += kGramBatch) {
+      __syncthreads();  // the previous batch has been consumed
+      if (t < kGramBatch) {
+        const int i = i0 + t;
+        int pos = -1;
+        const char* krow = nullptr;
+        if (i < i_end) {
+          if (i < a.k) {
+            const int tok = a.sel_idx_prev[(size_t)bh * a.k + i];
+            const int slot = a.sel_slot_prev[(size_t)bh * a.k + i];
+            if (tok >= 0 && tok < a.l && slot >= 0 && slot < a.C) {
+              pos = tok;
+              krow = Kc + (size_t)slot * ROWB;
+            }
+          } else {
+            const int j = i - a.k;  // row of the lite ring
+            // the position in [l-w, l) that is congruent to j modulo w
+            int off = (j - lite0) % a.w;
+            if (off < 0) off += a.w;
+            pos = lite0 + off;
+            krow = Kl + (size_t)j * ROWB;
+          }
+        }
+        pos_s[t] = pos;
+        krow_s[t] = krow;
+      }
+      __syncthreads();
+      // u_i = q . K_i: 16 lanes per row, 16 rows per pass
+#pragma unroll
+      for (int pass = 0; pass < kGramBatch / 16; ++pass) {
+        const int rr = pass * 16 + rsub;
+        const char* krow = krow_s[rr];
+        float dot = 0.0f;
+        if (krow) dot = dot_chunk<BF16>(krow, c16, qv);
+        dot = row16_sum(dot);
+        if (c16 == 0) u_s[rr] = dot;
+      }
+      // a_i = A_K[pos_i, :]
+      for (int idx = t; idx < kGramBatch * (R / 4); idx += kGramThreads) {
+        const int rr = idx / (R / 4), c4 = idx % (R / 4);
+        const int pos = pos_s[rr];
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (pos >= 0) v = reinterpret_cast<const float4*>(Ahead + (size_t)pos * R)[c4];
+        *reinterpret_cast<float4*>(&a_s[rr * LDA + 4 * c4]) = v;
+      }
+      __syncthreads();
+      if (t < kActive) {
+        for (int i = 0; i < kGramBatch; ++i) {
+          const float ap = a_s[i * LDA + p];
+#pragma unroll
+          for (int e = 0; e < EPT; ++e) acc[e] = __builtin_fmaf(ap, a_s[i * LDA + q0 + e], acc[e]);
+        }
+      }
+      if (t < R) {
+        for (int i = 0; i < kGramBatch; ++i) gacc = __builtin_fmaf(u_s[i], a_s[i * LDA + t], gacc);
+      }
+    }
+  } else {
+    // ---- B_Q of this query head, or B_K of this KV head, read column by column ------------
+    const bool isq = job == a.nchunk;
+    out = isq ? a.gram_q + (size_t)bh * (kEntries + R) : a.gram_k + (size_t)bkv * (kEntries + R);
+    const float* __restrict__ Bm =
+        isq ? a.B_Q + (size_t)bh * R * kD : a.B_K + (size_t)bkv * R * kD;
+    for (int i0 = 0; i0 < kD; i0 += kGramBatch) {
+      __syncthreads();
+      if (t < kGramBatch) {
+        const int i = i0 + t;
+        u_s[t] = isq ? a.q[(size_t)bh * kD + i]
+                     : kv_load<BF16>(static_cast<const char*>(a.k_new) + (size_t)bkv * ROWB, i);
+      }
+      for (int idx = t; idx < kGramBatch * R; idx += kGramThreads) {
+        const int c = idx / kGramBatch, ii = idx % kGramBatch;
+        a_s[ii * LDA + c] = Bm[(size_t)c * kD + i0 + ii];
+      }
+      __syncthreads();
+      if (t < kActive) {
+        for (int i = 0; i < kGramBatch; ++i) {
+          const float ap = a_s[i * LDA + p];
+#pragma unroll
+          for (int e = 0; e < EPT; ++e) acc[e] = __builtin_fmaf(ap, a_s[i * LDA + q0 + e], acc[e]);
+        }
+      }
+      if (t < R) {
+        for (int i = 0; i < kGramBatch; ++i) gacc = __builtin_fmaf(u_s[i], a_s[i * LDA + t], gacc);
+      }
+    }
+  }
+  if (t < kActive) {
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) out[e0 + e] = acc[e];
+  }
+  if (t < R) out[kEntries + t] = gacc;
+}
+
+// ------------------------------------------------------------------------------------------
+// r x r symmetric positive definite solve inside one wavefront.
+
+__device__ __forceinline__ float lane_value(float v, int lane) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+
+// Solves x M = b for symmetric positive definite M.  Lane i (< R) holds row i of M in m[]
+// and b_i in b; returns x_i in lane i.  m[] is destroyed.  lt: R * (R + 1) floats of LDS owned
+// by this wavefront.
+template <int R>
+__device__ __forceinline__ float chol_solve(float (&m)[R], float b, float* lt, int lane) {
+  float dinv = 0.0f;  // lane j keeps 1 / L[j][j]
+  // right-looking Cholesky: after step j, m[j] of lane i >= j holds L[i][j]
+#pragma unroll
+  for (int j = 0; j < R; ++j) {
+    const float djj = lane_value(m[j], j);
+    const float inv = 1.0f / sqrtf(djj);
+    const float lij = m[j] * inv;
+    m[j] = lij;
+    if (lane == j) dinv = inv;
+#pragma unroll
+    for (int c = j + 1; c < R; ++c) m[c] = __builtin_fmaf(-lij, lane_value(lij, c), m[c]);
+  }
+  // forward: L y = b
+  float y = 0.0f;
+#pragma unroll
+  for (int j = 0; j < R; ++j) {
+    const float yj = lane_value(b * dinv, j);
+    if (lane == j) y = yj;
+    b = __builtin_fmaf(-m[j], yj, b);
+  }
+  // transpose the factor through LDS: afterwards m[c] of lane i holds L[c][i]
+  if (lane < R) {
+#pragma unroll
+    for (int c = 0; c < R; ++c) lt[lane * (R + 1) + c] = m[c];
+  }
+  __builtin_amdgcn_wave_barrier();
+  if (lane < R) {
+#pragma unroll
+    for (int c = 0; c < R; ++c) m[c] = lt[c * (R + 1) + lane];
+  }
+  __builtin_amdgcn_wave_barrier();
+  // backward: L^T x = y
+  float x = 0.0f;
+#pragma unroll
+  for (int j = R - 1; j >= 0; --j) {
+    const float xj = lane_value(y * dinv, j);
+    if (lane == j) x = xj;
+    y = __builtin_fmaf(-m[j], xj, y);
+  }
+  return x;
+}
+
+struct SolveArgs {
+  const float* gram_om;  // [B*Hq][nchunk][r*r + r]
+  const float* gram_q;   // [B*Hq][r*r + r]
+  const float* gram_k;   // [B*Hkv][r*r + r]
+  const float* q;        // [B,Hq,d]
+  const void* k_new;     // [B,Hkv,d]
+  float* B_Q;            // [B,Hq,r,d]   updated in place
+  float* B_K;            // [B,Hkv,r,d]  updated in place
+  float* q_hat;          // [B,Hq,r]
+  float* k_hat;          // [B,Hkv,r]
+  int Hq, Hkv, nchunk, n_iter;
+  float lam1, lam2;
+};
+
+// One exact line-search gradient step on 1/2 |x_hat B - x|^2 (App. A.2), by one wavefront:
+//   resid = x_hat B - x,  grad = x_hat^T resid,  eta = <resid, x_hat grad> / |x_hat grad|^2,
+//   B <- B - eta grad.  Lane i (< R) holds x_hat_i; x(j) returns element j of the target.
+template <int R, typename XF>
+__device__ __forceinline__ void line_search_step(float xh, float* __restrict__ Bm, XF x, int lane) {
+  const float xhz = lane < R ? xh : 0.0f;
+  const float nrm2 = wave_sum(xhz * xhz);
+  // this lane's two columns of the residual
+  float e0 = -x(lane), e1 = -x(lane + 64);
+#pragma unroll
+  for (int i = 0; i < R; ++i) {
+    const float xi = lane_value(xh, i);
+    e0 = __builtin_fmaf(xi, Bm[(size_t)i * kD + lane], e0);
+    e1 = __builtin_fmaf(xi, Bm[(size_t)i * kD + lane + 64], e1);
+  }
+  // x_hat grad = |x_hat|^2 resid
+  const float v0 = nrm2 * e0, v1 = nrm2 * e1;
+  const float num = wave_sum(e0 * v0 + e1 * v1);
+  const float den = wave_sum(v0 * v0 + v1 * v1);
+  const float eta = den > 0.0f ? num / den : 0.0f;
+#pragma unroll
+  for (int i = 0; i < R; ++i) {
+    const float s = eta * lane_value(xh, i);
+    Bm[(size_t)i * kD + lane] = __builtin_fmaf(-s, e0, Bm[(size_t)i * kD + lane]);
+    Bm[(size_t)i * kD + lane + 64] = __builtin_fmaf(-s, e1, Bm[(size_t)i * kD + lane + 64]);
+  }
+}
+
+template <int R, bool BF16>
+__global__ __launch_bounds__(kMaxG * 64) void factor_solve_kernel(SolveArgs a) {
+  constexpr int kEntries = R * R;
+  constexpr size_t ROWB = kD * (BF16 ? 2 : 4);
+  extern __shared__ __align__(16) float lds[];
+  const int G = a.Hq / a.Hkv;
+  // [G][R*(R+1)] transpose space | [G][R] q_hat exchange | [G] q.k
+  float* const lt = lds + (size_t)(threadIdx.x >> 6) * R * (R + 1);
+  float* const qhat_s = lds + (size_t)G * R * (R + 1);
+  float* const qk_s = qhat_s + G * R;
+
+  const int bkv = blockIdx.x;
+  const int b = bkv / a.Hkv, kvh = bkv - b * a.Hkv;
+  const int g = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int bh = b * a.Hq + kvh * G + g;
+  const bool row = lane < R;
+  const int li = row ? lane : 0;  // keeps the loads of idle lanes in bounds
+
+  // P = B_Q B_Q^T + lambda_d2 A_Om^T A_Om (row li),  cvec = q B_Q^T + lambda_d2 q K_Om^T A_Om;
+  // N = B_K B_K^T (row li),  nb = k B_K^T.  The chunk partials are added in chunk order.
+  float P[R], N[R], m[R];
+  float cvec, nb;
+  {
+    const float* gq = a.gram_q + (size_t)bh * (kEntries + R);
+    const float* gk = a.gram_k + (size_t)bkv * (kEntries + R);
+#pragma unroll
+    for (int c = 0; c < R; ++c) m[c] = 0.0f;
+    float gsum = 0.0f;
+    for (int s = 0; s < a.nchunk; ++s) {
+      const float* go = a.gram_om + ((size_t)bh * a.nchunk + s) * (kEntries + R);
+#pragma unroll
+      for (int c4 = 0; c4 < R / 4; ++c4) {
+        const float4 v = reinterpret_cast<const float4*>(go + (size_t)li * R)[c4];
+        m[4 * c4 + 0] += v.x; m[4 * c4 + 1] += v.y; m[4 * c4 + 2] += v.z; m[4 * c4 + 3] += v.w;
+      }
+      gsum += go[kEntries + li];
+    }
+#pragma unroll
+    for (int c = 0; c < R; ++c) {
+      P[c] = __builtin_fmaf(a.lam2, m[c], gq[(size_t)li * R + c]);
+      N[c] = gk[(size_t)li * R + c];
+    }
+    cvec = __builtin_fmaf(a.lam2, gsum, gq[kEntries + li]);
+    nb = gk[kEntries + li];
+  }
+
+  // q . k of this query head
+  const float* qp = a.q + (size_t)bh * kD;
+  const char* kp = static_cast<const char*>(a.k_new) + (size_t)bkv * ROWB;
+  const float qk = wave_sum(qp[lane] * kv_load<BF16>(kp, lane) +
+                            qp[lane + 64] * kv_load<BF16>(kp, lane + 64));
+  if (lane == 0) qk_s[g] = qk;
+
+  // initial guess (lambda_d1 = 0): k_hat = k B_K^T (B_K B_K^T)^-1
+#pragma unroll
+  for (int c = 0; c < R; ++c) m[c] = N[c];
+  float k_hat = chol_solve<R>(m, nb, lt, lane);
+  float q_hat = 0.0f;
+  for (int it = 0; it < a.n_iter; ++it) {
+    // q_hat = m_lq M_rq^-1
+#pragma unroll
+    for (int c = 0; c < R; ++c)
+      m[c] = __builtin_fmaf(a.lam1 * k_hat, lane_value(k_hat, c), P[c]);
+    q_hat = chol_solve<R>(m, __builtin_fmaf(a.lam1 * qk, k_hat, cvec), lt, lane);
+    __syncthreads();  // the previous round's q_hat has been read by every wavefront
+    if (row) qhat_s[g * R + lane] = q_hat;
+    __syncthreads();
+    // k_hat = (k B_K^T + lambda_d1 sum_g (q_g.k) q_hat_g)(B_K B_K^T + lambda_d1 sum_g q_hat_g^T q_hat_g)^-1
+    float rhs = nb;
+#pragma unroll
+    for (int c = 0; c < R; ++c) m[c] = N[c];
+    for (int gg = 0; gg < G; ++gg) {
+      const float qi = qhat_s[gg * R + li];
+      rhs = __builtin_fmaf(a.lam1 * qk_s[gg], qi, rhs);
+#pragma unroll
+      for (int c = 0; c < R; ++c) m[c] = __builtin_fmaf(a.lam1 * qi, qhat_s[gg * R + c], m[c]);
+    }
+    k_hat = chol_solve<R>(m, rhs, lt, lane);
+  }
+  if (row) a.q_hat[(size_t)bh * R + lane] = q_hat;
+  if (row && g == 0) a.k_hat[(size_t)bkv * R + lane] = k_hat;
+
+  // gradient steps on B_Q (every wavefront its head) and B_K (the first wavefront)
+  line_search_step<R>(q_hat, a.B_Q + (size_t)bh * R * kD, [&](int j) { return qp[j]; }, lane);
+  if (g == 0)
+    line_search_step<R>(k_hat, a.B_K + (size_t)bkv * R * kD,
+                        [&](int j) { return kv_load<BF16>(kp, j); }, lane);
+}
+
+template <int R, bool BF16>
+hipError_t launch_update_r(const lrqk_shape& s, const GramArgs& ga, const SolveArgs& sa,
+                           hipStream_t st) {
+  const int G = s.Hq / s.Hkv;
+  hipLaunchKernelGGL((factor_gram_kernel<R, BF16>), dim3(ga.nchunk + 2, s.B * s.Hq),
+                     dim3(kGramThreads), 0, st, ga);
+  const size_t lds = ((size_t)G * R * (R + 1) + (size_t)G * R + G) * sizeof(float);
+  if (lds > 64 * 1024) {  // above the default limit the kernel has to opt in, once
+    static bool raised = false;
+    if (!raised) {
+      const hipError_t e = hipFuncSetAttribute(
+          reinterpret_cast<const void*>(factor_solve_kernel<R, BF16>),
+          hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      if (e != hipSuccess) return e;
+      raised = true;
+    }
+  }
+  hipLaunchKernelGGL((factor_solve_kernel<R, BF16>), dim3(s.B * s.Hkv), dim3(G * 64), lds, st,
+                     sa);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool factor_update_supported(const lrqk_shape& s) {
+  return s.r == 8 || s.r == 16 || s.r == 32 || s.r == 64;
+}
+
+UpdateGeom update_geometry(const lrqk_shape& s) {
+  UpdateGeom g;
+  g.chunk_rows = 256;
+  g.nchunk = ceil_div(s.k + s.w, g.chunk_rows);
+  g.per_gram = (size_t)s.r * s.r + s.r;
+  return g;
+}
+
+size_t update_ws_bytes(const lrqk_shape& s) {
+  const UpdateGeom g = update_geometry(s);
+  const size_t BHq = (size_t)s.B * s.Hq, BHkv = (size_t)s.B * s.Hkv;
+  return round_up((BHq * g.nchunk + BHq + BHkv) * g.per_gram * sizeof(float), 256);
+}
+
+hipError_t launch_factor_update(const lrqk_shape& s, const float* A_K, const void* cacheK,
+                                const void* liteK, const int32_t* sel_idx_prev,
+                                const int32_t* sel_slot_prev, const float* q, const void* k_new,
+                                float* B_Q, float* B_K, float lam1, float lam2, int n_iter,
+                                float* q_hat, float* k_hat, float* ws, hipStream_t st) {
+  const UpdateGeom g = update_geometry(s);
+  const size_t BHq = (size_t)s.B * s.Hq;
+  GramArgs ga;
+  ga.A_K = A_K; ga.cacheK = cacheK; ga.liteK = liteK;
+  ga.sel_idx_prev = sel_idx_prev; ga.sel_slot_prev = sel_slot_prev;
+  ga.q = q; ga.k_new = k_new; ga.B_Q = B_Q; ga.B_K = B_K;
+  ga.gram_om = ws;
+  ga.gram_q = ws + BHq * g.nchunk * g.per_gram;
+  ga.gram_k = ga.gram_q + BHq * g.per_gram;
+  ga.Hq = s.Hq; ga.Hkv = s.Hkv; ga.l = s.l; ga.l_rows = s.l; ga.k = s.k; ga.w = s.w; ga.C = s.C;
+  ga.nchunk = g.nchunk; ga.chunk_rows = g.chunk_rows;
+  SolveArgs sa;
+  sa.gram_om = ga.gram_om; sa.gram_q = ga.gram_q; sa.gram_k = ga.gram_k;
+  sa.q = q; sa.k_new = k_new; sa.B_Q = B_Q; sa.B_K = B_K; sa.q_hat = q_hat; sa.k_hat = k_hat;
+  sa.Hq = s.Hq; sa.Hkv = s.Hkv; sa.nchunk = g.nchunk; sa.n_iter = n_iter;
+  sa.lam1 = lam1; sa.lam2 = lam2;
+  const bool bf16 = s.kv_dtype == LRQK_KV_BF16;
+  switch (s.r) {
+    case 8: return bf16 ? launch_update_r<8, true>(s, ga, sa, st) : launch_update_r<8, false>(s, ga, sa, st);
+    case 16: return bf16 ? launch_update_r<16, true>(s, ga, sa, st) : launch_update_r<16, false>(s, ga, sa, st);
+    case 32: return bf16 ? launch_update_r<32, true>(s, ga, sa, st) : launch_update_r<32, false>(s, ga, sa, st);
+    case 64: return bf16 ? launch_update_r<64, true>(s, ga, sa, st) : launch_update_r<64, false>(s, ga, sa, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace lrqk

@@ -117,4 +117,19 @@ hipError_t launch_fetch_direct(const lrqk_shape& s, const void* K_host, const vo
 hipError_t launch_scatter_staged(const lrqk_shape& s, const void* staging, const int64_t* row_dst,
                                  int64_t n_rows, void* cacheK, void* cacheV, hipStream_t st);
 
+// Decode-time factor update (factor_update.hip): r in {8, 16, 32, 64}.
+struct UpdateGeom {
+  int chunk_rows;   // rows of Omega summed by one workgroup
+  int nchunk;       // workgroups per query head
+  size_t per_gram;  // floats of one partial result: r*r + r
+};
+bool factor_update_supported(const lrqk_shape& s);
+UpdateGeom update_geometry(const lrqk_shape& s);
+size_t update_ws_bytes(const lrqk_shape& s);
+hipError_t launch_factor_update(const lrqk_shape& s, const float* A_K, const void* cacheK,
+                                const void* liteK, const int32_t* sel_idx_prev,
+                                const int32_t* sel_slot_prev, const float* q, const void* k_new,
+                                float* B_Q, float* B_K, float lam1, float lam2, int n_iter,
+                                float* q_hat, float* k_hat, float* ws, hipStream_t st);
+
 }  // namespace lrqk

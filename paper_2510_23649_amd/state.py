@@ -9,12 +9,19 @@ import torch
 from . import binding as L
 
 
+def lite_ring(X: torch.Tensor, l: int, w: int) -> torch.Tensor:
+    """The rows of positions [l-w, l) of X [B,Hkv,>=l,d] in ring order: row j of the result is
+    the position p with p mod w == j (a copy of rows, no arithmetic)."""
+    lite = X[:, :, l - w:l, :]
+    return torch.roll(lite, shifts=(l - w) % w, dims=2) if w > 0 else lite
+
+
 class LayerBuffers:
     """Device + pinned-host buffers of one layer, as lrqk_decode_step expects them.
 
     A_K [B,Hkv,l,r] fp32 and K, V [B,Hkv,l,d] (bf16 or fp32) may live on any device;
     A_K is moved to the GPU, K and V into pinned host memory, the last w rows of K
-    and V (the lite tokens) are also kept on the GPU.  The cache starts empty.
+    and V (the lite tokens) are also kept on the GPU, as a ring (lite_ring).  The cache starts empty.
     """
 
     def __init__(self, shape: L.Shape, A_K: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
@@ -27,8 +34,8 @@ class LayerBuffers:
         self.V_host = torch.empty(V.shape, dtype=V.dtype, pin_memory=True)
         self.K_host.copy_(K)
         self.V_host.copy_(V)
-        self.liteK = K[:, :, l - w:, :].to(device).contiguous()
-        self.liteV = V[:, :, l - w:, :].to(device).contiguous()
+        self.liteK = lite_ring(K, l, w).to(device).contiguous()
+        self.liteV = lite_ring(V, l, w).to(device).contiguous()
         i32 = dict(dtype=torch.int32, device=device)
         self.slot_of = torch.empty((B, Hq, l), **i32)
         self.token_of = torch.empty((B, Hq, C), **i32)

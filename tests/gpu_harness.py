@@ -7,6 +7,7 @@ import numpy as np
 import torch
 
 import paper_2510_23649_amd as L
+from paper_2510_23649_amd.state import lite_ring
 from gen import as_numpy
 from oracle import lrqk_oracle as orc
 
@@ -34,8 +35,8 @@ class DeviceLayer:
         self.A_K = data.A_K.to(DEV).contiguous()
         self.K_host = data.K.cpu().contiguous().pin_memory()
         self.V_host = data.V.cpu().contiguous().pin_memory()
-        self.liteK = data.liteK.to(DEV).contiguous()
-        self.liteV = data.liteV.to(DEV).contiguous()
+        self.liteK = lite_ring(data.K, l, cfg.w).to(DEV).contiguous()
+        self.liteV = lite_ring(data.V, l, cfg.w).to(DEV).contiguous()
         self.slot_of = torch.empty((B, Hq, l), dtype=torch.int32, device=DEV)
         self.token_of = torch.empty((B, Hq, C), dtype=torch.int32, device=DEV)
         self.last_used = torch.empty((B, Hq, C), dtype=torch.int32, device=DEV)

@@ -1,0 +1,147 @@
+"""GPU parity of the decode-time factor update (lrqk_factor_update) against the CPU oracle
+(oracle/lrqk_update_oracle.py), through the C ABI.
+
+The update is fp32 linear algebra (Gram sums over the k + w rows of Omega, r x r Cholesky
+solves); the oracle is float64.  Tolerance: the forward error of a backward-stable fp32
+solve is about r * 2^-24 * cond(M) relative to the solution's norm; the synthetic workloads
+have cond(M) of a few tens (A_Om^T A_Om dominates M, and its spectrum is that of k + w
+Gaussian rows plus the planted plane), so with r <= 64 the bound is 64 * 6e-8 * ~10 = 4e-5.
+The tests allow REL_TOL = 5e-5 of the largest entry of each output array and print what
+they see (1e-6 .. 4e-6 on MI355X).
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2510_23649_amd as L
+from gen import get_config, make_layer, QueryStream, as_numpy
+from oracle import lrqk_update_oracle as upd
+from gpu_harness import DEV, DeviceLayer, StepBuffers, workspace
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL = 5e-5
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def upd_cfg(**kw):
+    base = dict(B=2, Hq=8, Hkv=2, l=3000, r=32, k=300, w=40, C=600, n_heavy=32, pool_mult=4)
+    base.update(kw)
+    return get_config("c2").with_(**base)
+
+
+def factors_for(cfg, data, seed, perturb=0.05):
+    """B_K near the generator's basis, B_Q near its dual basis (what a prefill would hand over),
+    both perturbed so that no term of the objective vanishes; a fresh key row k_t."""
+    g = torch.Generator().manual_seed(seed)
+    Bm = data.Bmat.cpu().double()                                     # [B,Hkv,r,d]
+    dual = torch.linalg.solve(Bm @ Bm.transpose(-1, -2), Bm)          # (B B^T)^-1 B
+    B_K = (Bm + perturb * torch.randn(Bm.shape, generator=g, dtype=torch.float64)).float()
+    B_Q = dual.repeat_interleave(cfg.G, dim=1)
+    B_Q = (B_Q + perturb * torch.randn(B_Q.shape, generator=g, dtype=torch.float64)).float()
+    kvdt = torch.bfloat16 if cfg.kv_dtype == "bf16" else torch.float32
+    k_hat_true = torch.randn(cfg.B, cfg.Hkv, cfg.r, generator=g, dtype=torch.float64)
+    k_new = (torch.einsum("bhr,bhrd->bhd", k_hat_true, Bm) +
+             0.05 * torch.randn(cfg.B, cfg.Hkv, cfg.d, generator=g, dtype=torch.float64)).to(kvdt)
+    return B_Q.contiguous(), B_K.contiguous(), k_new.contiguous()
+
+
+def run_update_case(cfg, lam1=1.0, lam2=1.0, n_iter=2, warm_steps=2, seed=7):
+    data = make_layer(cfg)
+    dl = DeviceLayer(cfg, data)
+    plan = L.Plan(dl.shape)
+    qs = QueryStream(data)
+    sb = StepBuffers(cfg)
+    out = torch.empty((cfg.B, cfg.Hq, cfg.d), device=DEV)
+    for step in range(1, warm_steps + 1):          # fills the cache; leaves the previous selection
+        q, q_hat = qs.next()
+        L.lrqk_decode_step(plan, dl.shape, step, dl.struct(), q_hat.to(DEV), q.to(DEV), out,
+                           L.LRQK_FETCH_DIRECT, sb.debug())
+    prev = sb.to_np()
+    assert (prev["sel_slot"] >= 0).all()
+    q, _ = qs.next()
+    B_Q, B_K, k_new = factors_for(cfg, data, seed)
+    ref = upd.factor_update(as_numpy(q), as_numpy(k_new), as_numpy(B_Q), as_numpy(B_K),
+                            dl.np["A_K"], dl.np["K"],
+                            upd.omega_positions(prev["sel_idx"], cfg.l, cfg.w), lam1, lam2, n_iter)
+    dBQ, dBK = B_Q.to(DEV), B_K.to(DEV)
+    q_hat_d = torch.full((cfg.B, cfg.Hq, cfg.r), float("nan"), device=DEV)
+    k_hat_d = torch.full((cfg.B, cfg.Hkv, cfg.r), float("nan"), device=DEV)
+    ws = workspace(L.lrqk_workspace_bytes(dl.shape, L.LRQK_WS_UPDATE))
+    L.lrqk_factor_update(dl.shape, dl.struct(), sb.sel_idx, sb.sel_slot, q.to(DEV), k_new.to(DEV),
+                         dBQ, dBK, lam1, lam2, n_iter, q_hat_d, k_hat_d, ws)
+    torch.cuda.synchronize()
+    got = dict(q_hat=q_hat_d.cpu().numpy(), k_hat=k_hat_d.cpu().numpy(),
+               B_Q=dBQ.cpu().numpy(), B_K=dBK.cpu().numpy())
+    worst = 0.0
+    for name, arr in got.items():
+        assert np.all(np.isfinite(arr)), name
+        rel = np.abs(arr - ref[name]).max() / np.abs(ref[name]).max()
+        say(f"   {name}: max rel err {rel:.2e}")
+        worst = max(worst, rel)
+        assert rel <= REL_TOL, f"{name}: {rel}"
+    # the step must really have moved B (the comparison above is not vacuous)
+    assert np.abs(got["B_Q"] - as_numpy(B_Q)).max() > 1e-3
+    assert np.abs(got["B_K"] - as_numpy(B_K)).max() > 1e-3
+    plan.close()
+    return worst
+
+
+@pytest.mark.parametrize("r", [8, 16, 32, 64])
+def test_factor_update_ranks(r):
+    say(f"factor update r={r}")
+    run_update_case(upd_cfg(r=r))
+
+
+@pytest.mark.parametrize("G,Hkv", [(1, 3), (2, 2), (7, 1), (8, 1)])
+def test_factor_update_group_sizes(G, Hkv):
+    say(f"factor update G={G}")
+    run_update_case(upd_cfg(B=1, Hq=G * Hkv, Hkv=Hkv, r=16))
+
+
+def test_factor_update_fp32_rows_and_ragged_sizes():
+    say("factor update, fp32 K rows, sizes that leave ragged chunks")
+    run_update_case(upd_cfg(B=1, Hq=4, Hkv=2, l=2777, k=263, w=37, C=263, kv_dtype="f32"))
+
+
+@pytest.mark.parametrize("lam1,lam2,n_iter", [(0.0, 0.0, 1), (1.0, 0.0, 2), (0.0, 1.0, 1),
+                                              (0.5, 2.0, 4)])
+def test_factor_update_lambdas_and_rounds(lam1, lam2, n_iter):
+    say(f"factor update lambda_d1={lam1} lambda_d2={lam2} rounds={n_iter}")
+    run_update_case(upd_cfg(B=1, Hq=4, Hkv=2, r=16), lam1, lam2, n_iter)
+
+
+def test_factor_update_no_lite_window():
+    say("factor update with w = 0")
+    run_update_case(upd_cfg(B=1, Hq=2, Hkv=1, r=16, w=0))
+
+
+def test_factor_update_at_the_headline_shape():
+    say("factor update at l = 131072, k = 2048, w = 64, r = 32, 32 / 8 heads")
+    run_update_case(get_config("c3").with_(layers=1))
+
+
+def test_factor_update_rejects_bad_arguments():
+    cfg = upd_cfg(B=1, Hq=2, Hkv=1, r=12)
+    shp = L.Shape.make(B=1, Hq=2, Hkv=1, l=cfg.l, r=12, k=cfg.k, w=cfg.w, C_slots=cfg.C)
+    assert L.lrqk_workspace_bytes(shp, L.LRQK_WS_UPDATE) == 0
+    t = torch.zeros(4096, device=DEV)
+    ti = torch.zeros(4096, dtype=torch.int32, device=DEV)
+    lay = L.make_layer(A_K=t, K_host=None, V_host=None, liteK=t, liteV=t, slot_of=ti,
+                       token_of=ti, last_used=ti, cacheK=t, cacheV=t)
+    with pytest.raises(L.LrqkError) as e:
+        L.lrqk_factor_update(shp, lay, ti, ti, t, t, t, t, 1.0, 1.0, 2, t, t, workspace(1 << 20))
+    assert e.value.status == -2
+    shp16 = L.Shape.make(B=1, Hq=2, Hkv=1, l=cfg.l, r=16, k=cfg.k, w=cfg.w, C_slots=cfg.C)
+    for bad in (dict(n_iter=0), dict(lam1=-1.0), dict(lam2=float("inf"))):
+        with pytest.raises(L.LrqkError) as e:
+            L.lrqk_factor_update(shp16, lay, ti, ti, t, t, t, t, bad.get("lam1", 1.0),
+                                 bad.get("lam2", 1.0), bad.get("n_iter", 2), t, t,
+                                 workspace(1 << 24))
+        assert e.value.status == -1
+    with pytest.raises(L.LrqkError) as e:
+        L.lrqk_factor_update(shp16, lay, ti, ti, t, t, t, t, 1.0, 1.0, 2, t, t, workspace(256))
+    assert e.value.status == -4
