@@ -80,12 +80,17 @@ enum {
  *   C        cache slots per (batch, query head), k <= C <= 8192.
  *   kv_dtype element type of K/V rows (host store, cache, lite rows).
  *   scale    softmax scale applied to q.k (the usual 1/sqrt(d)).
+ *   l_cap    rows allocated per head in the arrays that grow with the context (A_K, K_host,
+ *            V_host, slot_of): their row stride.  0 means l (no room to grow); otherwise
+ *            l <= l_cap < 2^24.  Where this header writes [.., l, ..] for one of those four
+ *            arrays, read [.., l_cap, ..] with the first l rows in use.
  * Requirements: B >= 1, Hkv >= 1, Hq a multiple of Hkv, Hq/Hkv <= 8, l >= 1, l < 2^24.
  */
 typedef struct lrqk_shape {
   int32_t B, Hq, Hkv, d, l, r, k, w, C;
   int32_t kv_dtype;
   float scale;
+  int32_t l_cap;
 } lrqk_shape;
 
 /* Which call a workspace is sized for (lrqk_workspace_bytes). */
@@ -219,11 +224,11 @@ int lrqk_fetch_misses(lrqk_plan* plan, const lrqk_shape* shape, const void* K_ho
 
 /* Buffers of one layer for the fused step. Device unless marked pinned. */
 typedef struct lrqk_layer {
-  const float* A_K;    /* fp32 [B,Hkv,l,r] */
-  const void* K_host;  /* pinned, kv_dtype [B,Hkv,l,d] */
-  const void* V_host;  /* pinned, kv_dtype [B,Hkv,l,d] */
-  const void* liteK;   /* kv_dtype [B,Hkv,w,d] */
-  const void* liteV;   /* kv_dtype [B,Hkv,w,d] */
+  float* A_K;          /* fp32 [B,Hkv,l,r]                       (written only by lrqk_append_token) */
+  void* K_host;        /* pinned, kv_dtype [B,Hkv,l,d]           (likewise) */
+  void* V_host;        /* pinned, kv_dtype [B,Hkv,l,d]           (likewise) */
+  void* liteK;         /* kv_dtype [B,Hkv,w,d], ring of the last w rows (likewise) */
+  void* liteV;         /* kv_dtype [B,Hkv,w,d]                   (likewise) */
   int32_t* slot_of;    /* int32 [B,Hq,l]  in/out */
   int32_t* token_of;   /* int32 [B,Hq,C]  in/out */
   int32_t* last_used;  /* int32 [B,Hq,C]  in/out */
@@ -299,6 +304,23 @@ int lrqk_factor_update(const lrqk_shape* shape, const lrqk_layer* layer,
                        const void* k_new, float* B_Q, float* B_K, float lambda_d1,
                        float lambda_d2, int32_t n_iter, float* q_hat, float* k_hat,
                        void* workspace, size_t ws_bytes, void* stream);
+
+/*
+ * u2 — the new token joins the context (Alg. 2: A_K <- [A_K; k_hat_t], K_Omega <- [K'; k_t],
+ * V_Omega <- [V'; v_t], "Async k_t, v_t to CPU").  With l = shape->l the current length:
+ *   A_K[b,kv,l,:] = k_hat[b,kv,:];  K_host[b,kv,l,:] = k_new[b,kv,:];  V_host likewise (bit
+ *   copies, written by the GPU into the pinned store: asynchronous to the host, complete
+ *   when the work enqueued on `stream` has finished);  the lite ring row l mod w (which held
+ *   position l - w) receives k_new / v_new;  slot_of[b,h,l] = -1.
+ * Afterwards the context has l + 1 rows: the caller passes shape->l + 1 to the following
+ * calls (the new token is then inside the lite window [l+1-w, l+1), always attended).
+ * Needs room for the row: shape->l_cap > shape->l, else LRQK_ESHAPE.
+ *   layer   A_K, K_host, V_host, liteK, liteV, slot_of are written as described
+ *   k_hat   device fp32 [B,Hkv,r]      (from lrqk_factor_update)
+ *   k_new, v_new  device kv_dtype [B,Hkv,d]
+ */
+int lrqk_append_token(const lrqk_shape* shape, const lrqk_layer* layer, const float* k_hat,
+                      const void* k_new, const void* v_new, void* stream);
 
 /*
  * Instrumentation (not part of the method): per-phase GPU time of lrqk_decode_step,

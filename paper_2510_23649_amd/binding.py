@@ -28,11 +28,23 @@ class Shape(C.Structure):
     """lrqk_shape."""
     _fields_ = [(n, C.c_int32) for n in ("B", "Hq", "Hkv", "d", "l", "r", "k", "w", "C", "kv_dtype")]
     _fields_.append(("scale", C.c_float))
+    _fields_.append(("l_cap", C.c_int32))
 
     @classmethod
-    def make(cls, *, B, Hq, Hkv, l, r, k, w, C_slots, d=128, kv_dtype=LRQK_KV_BF16, scale=None):
+    def make(cls, *, B, Hq, Hkv, l, r, k, w, C_slots, d=128, kv_dtype=LRQK_KV_BF16, scale=None,
+             l_cap=0):
         return cls(B, Hq, Hkv, d, l, r, k, w, C_slots, kv_dtype,
-                   float(scale if scale is not None else d ** -0.5))
+                   float(scale if scale is not None else d ** -0.5), l_cap)
+
+    def with_l(self, l: int) -> "Shape":
+        """The same shape at another context length (same l_cap)."""
+        return Shape(self.B, self.Hq, self.Hkv, self.d, l, self.r, self.k, self.w, self.C,
+                     self.kv_dtype, self.scale, self.l_cap)
+
+    @property
+    def rows(self) -> int:
+        """Rows allocated per head in A_K, the K/V store and slot_of."""
+        return self.l_cap if self.l_cap > 0 else self.l
 
 
 class Layer(C.Structure):
@@ -75,6 +87,7 @@ def load_library():
         "lrqk_sparse_attend": (C.c_int, [sp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
         "lrqk_factor_update": (C.c_int, [sp, C.POINTER(Layer), vp, vp, vp, vp, vp, vp, C.c_float,
                                          C.c_float, i32, vp, vp, vp, sz, vp]),
+        "lrqk_append_token": (C.c_int, [sp, C.POINTER(Layer), vp, vp, vp, vp]),
         "lrqk_plan_create": (C.c_int, [sp, C.POINTER(vp)]),
         "lrqk_plan_destroy": (C.c_int, [vp]),
         "lrqk_fetch_misses": (C.c_int, [vp, sp, vp, vp, vp, vp, vp, vp, vp, C.c_int,
@@ -98,7 +111,7 @@ EXPORTS = ["lrqk_version", "lrqk_status_string", "lrqk_last_hip_error", "lrqk_va
            "lrqk_workspace_bytes", "lrqk_proxy_scores", "lrqk_select_topk", "lrqk_cache_init",
            "lrqk_cache_resolve", "lrqk_sparse_attend", "lrqk_plan_create", "lrqk_plan_destroy",
            "lrqk_fetch_misses", "lrqk_decode_step", "lrqk_plan_profile", "lrqk_plan_profile_read", "lrqk_calib_copy",
-           "lrqk_plan_time_proxy_pass", "lrqk_factor_update"]
+           "lrqk_plan_time_proxy_pass", "lrqk_factor_update", "lrqk_append_token"]
 
 
 def _check(status: int, where: str):
@@ -198,6 +211,12 @@ def lrqk_factor_update(shape, layer, sel_idx_prev, sel_slot_prev, q, k_new, B_Q,
         _dev(B_Q, torch.float32), _dev(B_K, torch.float32), float(lambda_d1), float(lambda_d2),
         int(n_iter), _dev(q_hat, torch.float32), _dev(k_hat, torch.float32), _dev(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream)), "lrqk_factor_update")
+
+
+def lrqk_append_token(shape, layer, k_hat, k_new, v_new, stream=None):
+    _check(load_library().lrqk_append_token(C.byref(shape), C.byref(layer),
+                                            _dev(k_hat, torch.float32), _dev(k_new), _dev(v_new),
+                                            _stream(stream)), "lrqk_append_token")
 
 
 def lrqk_calib_copy(dst, src, stream=None):

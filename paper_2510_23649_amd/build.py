@@ -19,7 +19,8 @@ OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "liblrqk.so")
 
 SOURCES = ["api.hip", "proxy_scores.hip", "select_topk.hip", "cache_resolve.hip", "select_resolve.hip",
-           "sparse_attend.hip", "fetch.hip", "factor_update.hip", "instrument.hip"]
+           "sparse_attend.hip", "fetch.hip", "factor_update.hip", "append_token.hip",
+           "instrument.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

@@ -37,6 +37,7 @@ static int check_shape(const lrqk_shape* s) {
   if (s->C < s->k || s->C > kMaxC) return LRQK_ESHAPE;
   if ((long)s->B * s->Hq > 65535) return LRQK_ESHAPE;
   if (!std::isfinite(s->scale)) return LRQK_ESHAPE;
+  if (s->l_cap != 0 && (s->l_cap < s->l || s->l_cap >= (1 << 24))) return LRQK_ESHAPE;
   return LRQK_OK;
 }
 
@@ -283,6 +284,22 @@ int lrqk_factor_update(const lrqk_shape* shape, const lrqk_layer* layer,
   return LRQK_OK;
 }
 
+int lrqk_append_token(const lrqk_shape* shape, const lrqk_layer* layer, const float* k_hat,
+                      const void* k_new, const void* v_new, void* stream) {
+  const int rc = check_shape(shape);
+  if (rc != LRQK_OK) return rc;
+  if (row_cap(*shape) <= shape->l) return LRQK_ESHAPE;  // no room for row l
+  if (!layer) return LRQK_EINVAL;
+  if (!all_aligned16({layer->A_K, layer->K_host, layer->V_host, layer->slot_of, k_hat, k_new,
+                      v_new}))
+    return LRQK_EINVAL;
+  if (shape->w > 0 && !all_aligned16({layer->liteK, layer->liteV})) return LRQK_EINVAL;
+  LRQK_HIP(launch_append_token(*shape, layer->A_K, layer->K_host, layer->V_host, layer->liteK,
+                               layer->liteV, layer->slot_of, k_hat, k_new, v_new,
+                               static_cast<hipStream_t>(stream)));
+  return LRQK_OK;
+}
+
 // ---------------------------------------------------------------------------- plan
 
 int lrqk_plan_destroy(lrqk_plan* p) {
@@ -424,8 +441,8 @@ static int staged_fetch(lrqk_plan* p, const lrqk_shape& s, const void* K_host, c
         p->h_rowdst[i] = -1;  // skipped by the scatter kernel
         continue;
       }
-      const char* Ks = Kh + ((b * s.Hkv + kvh) * (size_t)s.l + (size_t)tok) * rowB;
-      const char* Vs = Vh + ((b * s.Hkv + kvh) * (size_t)s.l + (size_t)tok) * rowB;
+      const char* Ks = Kh + ((b * s.Hkv + kvh) * (size_t)row_cap(s) + (size_t)tok) * rowB;
+      const char* Vs = Vh + ((b * s.Hkv + kvh) * (size_t)row_cap(s) + (size_t)tok) * rowB;
       std::memcpy(stage + (size_t)i * 2 * rowB, Ks, rowB);
       std::memcpy(stage + (size_t)i * 2 * rowB + rowB, Vs, rowB);
       p->h_rowdst[i] = (int64_t)bh * s.C + slot;

@@ -46,7 +46,7 @@ __device__ __forceinline__ void bitonic_sort_lds(T* a, int n) {
 
 // dynamic LDS: uint64 keys[Cpad]
 __global__ __launch_bounds__(kResThreads) void cache_resolve_kernel(
-    const int32_t* __restrict__ sel_idx, int32_t step, int l, int C, int Cpad, int k,
+    const int32_t* __restrict__ sel_idx, int32_t step, int l, int lrows, int C, int Cpad, int k,
     int32_t* __restrict__ slot_of, int32_t* __restrict__ token_of,
     int32_t* __restrict__ last_used, int32_t* __restrict__ sel_slot, uint8_t* __restrict__ hit,
     int32_t* __restrict__ miss_tok, int32_t* __restrict__ miss_slot,
@@ -57,7 +57,7 @@ __global__ __launch_bounds__(kResThreads) void cache_resolve_kernel(
   const int bh = blockIdx.x, t = threadIdx.x;
   const int lane = t & 63, wv = t >> 6;
   const int32_t* __restrict__ sel = sel_idx + (size_t)bh * k;
-  int32_t* __restrict__ so = slot_of + (size_t)bh * l;
+  int32_t* __restrict__ so = slot_of + (size_t)bh * lrows;
   int32_t* __restrict__ to = token_of + (size_t)bh * C;
   int32_t* __restrict__ lu = last_used + (size_t)bh * C;
   int32_t* __restrict__ ss = sel_slot + (size_t)bh * k;
@@ -155,7 +155,7 @@ __global__ __launch_bounds__(kResThreads) void cache_resolve_kernel(
 hipError_t launch_cache_init(const lrqk_shape& s, int32_t* slot_of, int32_t* token_of,
                              int32_t* last_used, hipStream_t st) {
   const size_t BHq = (size_t)s.B * s.Hq;
-  const size_t n1 = BHq * s.l, n2 = BHq * s.C;
+  const size_t n1 = BHq * row_cap(s), n2 = BHq * s.C;
   hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n1 + 255) / 256)), dim3(256), 0, st,
                      slot_of, n1, -1);
   hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n2 + 255) / 256)), dim3(256), 0, st,
@@ -182,7 +182,7 @@ hipError_t launch_cache_resolve(const lrqk_shape& s, const int32_t* sel_idx, int
     }
   }
   hipLaunchKernelGGL(cache_resolve_kernel, dim3(s.B * s.Hq), dim3(kResThreads), lds, st, sel_idx,
-                     step, s.l, s.C, Cpad, s.k, slot_of, token_of, last_used, sel_slot, hit,
+                     step, s.l, row_cap(s), s.C, Cpad, s.k, slot_of, token_of, last_used, sel_slot, hit,
                      miss_tok, miss_slot, n_miss);
   return hipGetLastError();
 }

@@ -483,7 +483,7 @@ hipError_t launch_factor_update(const lrqk_shape& s, const float* A_K, const voi
   ga.gram_om = ws;
   ga.gram_q = ws + BHq * g.nchunk * g.per_gram;
   ga.gram_k = ga.gram_q + BHq * g.per_gram;
-  ga.Hq = s.Hq; ga.Hkv = s.Hkv; ga.l = s.l; ga.l_rows = s.l; ga.k = s.k; ga.w = s.w; ga.C = s.C;
+  ga.Hq = s.Hq; ga.Hkv = s.Hkv; ga.l = s.l; ga.l_rows = row_cap(s); ga.k = s.k; ga.w = s.w; ga.C = s.C;
   ga.nchunk = g.nchunk; ga.chunk_rows = g.chunk_rows;
   SolveArgs sa;
   sa.gram_om = ga.gram_om; sa.gram_q = ga.gram_q; sa.gram_k = ga.gram_k;

@@ -21,7 +21,7 @@ __global__ __launch_bounds__(kFetchThreads) void fetch_direct_kernel(
     const uint4* __restrict__ K_host, const uint4* __restrict__ V_host,
     const int32_t* __restrict__ miss_tok, const int32_t* __restrict__ miss_slot,
     const int32_t* __restrict__ n_miss, uint4* __restrict__ cacheK, uint4* __restrict__ cacheV,
-    int Hq, int Hkv, int l, int C, int k, int rows_per_block) {
+    int Hq, int Hkv, int l, int lrows, int C, int k, int rows_per_block) {
   const int bh = blockIdx.y;
   const int b = bh / Hq, h = bh - b * Hq;
   const int kvh = h / (Hq / Hkv);
@@ -29,8 +29,8 @@ __global__ __launch_bounds__(kFetchThreads) void fetch_direct_kernel(
   const int row_begin = blockIdx.x * rows_per_block;
   const int row_end = min(nm, row_begin + rows_per_block);
   const int t = threadIdx.x, sub = t & 15, rgrp = t >> 4;  // 16 row groups per workgroup
-  const uint4* __restrict__ Ks = K_host + ((size_t)b * Hkv + kvh) * (size_t)l * ROW16;
-  const uint4* __restrict__ Vs = V_host + ((size_t)b * Hkv + kvh) * (size_t)l * ROW16;
+  const uint4* __restrict__ Ks = K_host + ((size_t)b * Hkv + kvh) * (size_t)lrows * ROW16;
+  const uint4* __restrict__ Vs = V_host + ((size_t)b * Hkv + kvh) * (size_t)lrows * ROW16;
   uint4* __restrict__ Kc = cacheK + (size_t)bh * C * ROW16;
   uint4* __restrict__ Vc = cacheV + (size_t)bh * C * ROW16;
   for (int j = row_begin + rgrp; j < row_end; j += 16) {
@@ -74,11 +74,11 @@ hipError_t launch_fetch_direct(const lrqk_shape& s, const void* K_host, const vo
   if (s.kv_dtype == LRQK_KV_BF16)
     hipLaunchKernelGGL((fetch_direct_kernel<16>), grid, dim3(kFetchThreads), 0, st,
                        (const uint4*)K_host, (const uint4*)V_host, miss_tok, miss_slot, n_miss,
-                       (uint4*)cacheK, (uint4*)cacheV, s.Hq, s.Hkv, s.l, s.C, s.k, rows_per_block);
+                       (uint4*)cacheK, (uint4*)cacheV, s.Hq, s.Hkv, s.l, row_cap(s), s.C, s.k, rows_per_block);
   else
     hipLaunchKernelGGL((fetch_direct_kernel<32>), grid, dim3(kFetchThreads), 0, st,
                        (const uint4*)K_host, (const uint4*)V_host, miss_tok, miss_slot, n_miss,
-                       (uint4*)cacheK, (uint4*)cacheV, s.Hq, s.Hkv, s.l, s.C, s.k, rows_per_block);
+                       (uint4*)cacheK, (uint4*)cacheV, s.Hq, s.Hkv, s.l, row_cap(s), s.C, s.k, rows_per_block);
   return hipGetLastError();
 }
 

@@ -36,6 +36,8 @@ inline int next_pow2(int x) {
   while (p < x) p <<= 1;
   return p;
 }
+// Rows allocated per head in A_K, the K/V store and slot_of (their row stride).
+inline int row_cap(const lrqk_shape& s) { return s.l_cap > 0 ? s.l_cap : s.l; }
 inline size_t kv_elem_bytes(int kv_dtype) { return kv_dtype == LRQK_KV_BF16 ? 2 : 4; }
 
 // Layout of the selection workspace (all offsets multiples of 256 bytes).
@@ -131,5 +133,10 @@ hipError_t launch_factor_update(const lrqk_shape& s, const float* A_K, const voi
                                 const int32_t* sel_slot_prev, const float* q, const void* k_new,
                                 float* B_Q, float* B_K, float lam1, float lam2, int n_iter,
                                 float* q_hat, float* k_hat, float* ws, hipStream_t st);
+
+// The new token's rows: A_K[., l, :], K/V store row l, lite ring row l % w, slot_of[., l] = -1.
+hipError_t launch_append_token(const lrqk_shape& s, float* A_K, void* K_host, void* V_host,
+                               void* liteK, void* liteV, int32_t* slot_of, const float* k_hat,
+                               const void* k_new, const void* v_new, hipStream_t st);
 
 }  // namespace lrqk

@@ -43,7 +43,7 @@ __device__ __forceinline__ float4 load_streaming(const float4* p) {
 template <int R, int G, bool FILTER>
 __global__ __launch_bounds__(kTileRows) void proxy_scores_kernel(
     const float* __restrict__ A_K, const float* __restrict__ q_hat, float* __restrict__ scores,
-    int l, int Hq, int Hkv, int n, const uint32_t* __restrict__ thr,
+    int l, int lrows, int Hq, int Hkv, int n, const uint32_t* __restrict__ thr,
     unsigned long long* __restrict__ bitmap, float* __restrict__ cand_scores, int words64) {
   // The tile goes through LDS in column phases of at most 32 floats, so that the LDS
   // footprint (and with it the number of resident workgroups) does not grow with r; the
@@ -57,7 +57,7 @@ __global__ __launch_bounds__(kTileRows) void proxy_scores_kernel(
 
   const int bkv = blockIdx.y;
   const int b = bkv / Hkv, kv = bkv - b * Hkv;
-  const float* __restrict__ A = A_K + (size_t)bkv * (size_t)l * R;
+  const float* __restrict__ A = A_K + (size_t)bkv * (size_t)lrows * R;
   const float* __restrict__ qh = q_hat + ((size_t)b * Hq + (size_t)kv * G) * R;
   float* __restrict__ sc = scores + ((size_t)b * Hq + (size_t)kv * G) * (size_t)l;
   const int t = threadIdx.x;
@@ -162,11 +162,11 @@ __device__ __forceinline__ float sum8(float v) {
 }
 
 __global__ __launch_bounds__(kThrThreads) void proxy_sample_kernel(
-    const float* __restrict__ A_K, const float* __restrict__ q_hat, int l, int r, int Hq, int Hkv,
-    int SS, int ns, int parts, float* __restrict__ samples) {
+    const float* __restrict__ A_K, const float* __restrict__ q_hat, int lrows, int r, int Hq,
+    int Hkv, int SS, int ns, int parts, float* __restrict__ samples) {
   const int bh = blockIdx.y, part = blockIdx.x, t = threadIdx.x;
   const int b = bh / Hq, h = bh - b * Hq, kv = h / (Hq / Hkv);
-  const float* __restrict__ A = A_K + ((size_t)b * Hkv + kv) * (size_t)l * r;
+  const float* __restrict__ A = A_K + ((size_t)b * Hkv + kv) * (size_t)lrows * r;
   const float* __restrict__ qh = q_hat + (size_t)bh * r;
   float* __restrict__ smp = samples + (size_t)bh * kThrMaxSamples;
   const int off = SS >> 1;
@@ -252,12 +252,12 @@ __global__ __launch_bounds__(kThrThreads) void proxy_threshold_kernel(
 constexpr int kGenRows = 64;
 __global__ __launch_bounds__(256) void proxy_scores_generic_kernel(
     const float* __restrict__ A_K, const float* __restrict__ q_hat, float* __restrict__ scores,
-    int l, int r, int Hq, int Hkv, int G, int tiles_per_block) {
+    int l, int lrows, int r, int Hq, int Hkv, int G, int tiles_per_block) {
   extern __shared__ float4 gtile[];  // kGenRows * (r/4 + 1)
   const int V4 = r / 4, ROW4 = V4 + 1;
   const int bkv = blockIdx.y;
   const int b = bkv / Hkv, kv = bkv - b * Hkv;
-  const float* __restrict__ A = A_K + (size_t)bkv * (size_t)l * r;
+  const float* __restrict__ A = A_K + (size_t)bkv * (size_t)lrows * r;
   const float* __restrict__ qh = q_hat + ((size_t)b * Hq + (size_t)kv * G) * r;
   float* __restrict__ sc = scores + ((size_t)b * Hq + (size_t)kv * G) * (size_t)l;
   const int t = threadIdx.x;
@@ -298,11 +298,11 @@ hipError_t launch_fast(const lrqk_shape& s, const float* A_K, const float* q_hat
   const int n = s.l - s.w;
   if (thr)
     hipLaunchKernelGGL((proxy_scores_kernel<R, G, true>), grid, dim3(kTileRows), 0, st, A_K,
-                       q_hat, scores, s.l, s.Hq, s.Hkv, n, thr, bitmap, cand_scores,
+                       q_hat, scores, s.l, row_cap(s), s.Hq, s.Hkv, n, thr, bitmap, cand_scores,
                        filter_words64(n));
   else
     hipLaunchKernelGGL((proxy_scores_kernel<R, G, false>), grid, dim3(kTileRows), 0, st, A_K,
-                       q_hat, scores, s.l, s.Hq, s.Hkv, n, nullptr, nullptr, nullptr, 0);
+                       q_hat, scores, s.l, row_cap(s), s.Hq, s.Hkv, n, nullptr, nullptr, nullptr, 0);
   return hipGetLastError();
 }
 
@@ -341,7 +341,7 @@ hipError_t launch_proxy_threshold(const lrqk_shape& s, const float* A_K, const f
   if (parts > kThrParts) parts = kThrParts;
   if (parts < 1) parts = 1;
   hipLaunchKernelGGL(proxy_sample_kernel, dim3(parts, s.B * s.Hq), dim3(kThrThreads), 0, st, A_K,
-                     q_hat, s.l, s.r, s.Hq, s.Hkv, SS, ns, parts, samples);
+                     q_hat, row_cap(s), s.r, s.Hq, s.Hkv, SS, ns, parts, samples);
   hipLaunchKernelGGL(proxy_threshold_kernel, dim3(s.B * s.Hq), dim3(kThrThreads), 0, st, samples,
                      n, s.k, SS, ns, thr);
   return hipGetLastError();
@@ -381,7 +381,7 @@ hipError_t launch_proxy_scores(const lrqk_shape& s, const float* A_K, const floa
   dim3 grid(ceil_div(n_tiles, tiles_per_block), bkv);
   const size_t lds = (size_t)kGenRows * (s.r / 4 + 1) * sizeof(float4);
   hipLaunchKernelGGL(proxy_scores_generic_kernel, grid, dim3(256), lds, st, A_K, q_hat, scores,
-                     s.l, s.r, s.Hq, s.Hkv, s.Hq / s.Hkv, tiles_per_block);
+                     s.l, row_cap(s), s.r, s.Hq, s.Hkv, s.Hq / s.Hkv, tiles_per_block);
   return hipGetLastError();
 }
 

@@ -147,7 +147,7 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
     // (scores_w: this head's slice is filled in only if the safe route needs every score)
     const float* __restrict__ cand_scores, const float* __restrict__ A_K,
     const float* __restrict__ q_hat, float* scores_w, int r,
-    int Hq, int Hkv, int l, int n, int k, int32_t* __restrict__ sel_idx,
+    int Hq, int Hkv, int l, int lrows, int n, int k, int32_t* __restrict__ sel_idx,
     // resolution (unused when !RESOLVE)
     int32_t step, int C, int32_t* __restrict__ slot_of, int32_t* __restrict__ token_of,
     int32_t* __restrict__ last_used, int32_t* __restrict__ sel_slot, uint8_t* __restrict__ hit,
@@ -176,7 +176,7 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
   const float* __restrict__ qh = nullptr;
   if (recompute) {
     const int b = bh / Hq, h = bh - b * Hq, kvh = h / (Hq / Hkv);
-    Arow = A_K + ((size_t)b * Hkv + kvh) * (size_t)l * r;
+    Arow = A_K + ((size_t)b * Hkv + kvh) * (size_t)lrows * r;
     qh = q_hat + (size_t)bh * r;
   }
   // proxy score of one row: the same fused-multiply-add chain as the proxy-score kernels
@@ -474,7 +474,7 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
   if (!RESOLVE) return;
 
   // ---- resolution ------------------------------------------------------------------------------
-  int32_t* __restrict__ so = slot_of + (size_t)bh * l;
+  int32_t* __restrict__ so = slot_of + (size_t)bh * lrows;
   int32_t* __restrict__ to = token_of + (size_t)bh * C;
   int32_t* __restrict__ lu = last_used + (size_t)bh * C;
   int32_t* __restrict__ ss = sel_slot + (size_t)bh * k;
@@ -670,7 +670,7 @@ hipError_t launch_select_only(const lrqk_shape& s, const float* scores, int32_t*
   hipError_t e = raise_lds_limit<false>();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((select_resolve_kernel<false>), dim3(s.B * s.Hq), dim3(kT), lds, st, scores,
-                     nullptr, 0, nullptr, nullptr, nullptr, nullptr, s.r, s.Hq, s.Hkv, s.l, n, s.k,
+                     nullptr, 0, nullptr, nullptr, nullptr, nullptr, s.r, s.Hq, s.Hkv, s.l, row_cap(s), n, s.k,
                      sel_idx,
                      0, s.C, nullptr, nullptr, nullptr, nullptr, nullptr,
                      nullptr, nullptr, nullptr);
@@ -690,7 +690,7 @@ hipError_t launch_select_resolve(const lrqk_shape& s, float* scores,
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((select_resolve_kernel<true>), dim3(s.B * s.Hq), dim3(kT), lds, st, scores,
                      reinterpret_cast<const uint32_t*>(ext_bitmap), 2 * filter_words64(n),
-                     cand_scores, ext_bitmap ? A_K : nullptr, q_hat, scores, s.r, s.Hq, s.Hkv, s.l, n, s.k,
+                     cand_scores, ext_bitmap ? A_K : nullptr, q_hat, scores, s.r, s.Hq, s.Hkv, s.l, row_cap(s), n, s.k,
                      sel_idx, step, s.C, slot_of, token_of, last_used, sel_slot, hit,
                      miss_tok, miss_slot, n_miss);
   return hipGetLastError();

@@ -102,10 +102,11 @@ struct RowChunk<false> {
 // fetch leg and the attention become one kernel, so the host-link reads of the few missing
 // rows overlap with the HBM reads of all the others.
 struct FetchSrc {
-  const char* K_host;       // [B,Hkv,l,d] rows
+  const char* K_host;       // [B,Hkv,lrows,d] rows
   const char* V_host;
   const int32_t* sel_idx;   // [B,Hq,k] position of each selected row
-  int l;
+  int l;                    // context length
+  int lrows;                // rows allocated per (batch, KV head)
 };
 
 template <bool BF16>
@@ -132,8 +133,8 @@ __global__ __launch_bounds__(kAttThreads) void attend_partial_kernel(
   const char* __restrict__ Vh = nullptr;
   const int32_t* __restrict__ toks = nullptr;
   if (mode == kAttendAllFetch) {
-    Kh = fs.K_host + ((size_t)b * Hkv + kvh) * (size_t)fs.l * ROWB;
-    Vh = fs.V_host + ((size_t)b * Hkv + kvh) * (size_t)fs.l * ROWB;
+    Kh = fs.K_host + ((size_t)b * Hkv + kvh) * (size_t)fs.lrows * ROWB;
+    Vh = fs.V_host + ((size_t)b * Hkv + kvh) * (size_t)fs.lrows * ROWB;
     toks = fs.sel_idx + (size_t)bh * k;
   }
   const char* __restrict__ Kl =
@@ -369,7 +370,7 @@ hipError_t launch_attend_partial(const lrqk_shape& s, int mode, const float* q, 
   if (mode == kAttendAllFetch && (!K_host || !V_host || !sel_idx || !hit))
     return hipErrorInvalidValue;
   const FetchSrc fs{static_cast<const char*>(K_host), static_cast<const char*>(V_host), sel_idx,
-                    s.l};
+                    s.l, row_cap(s)};
   const dim3 grid(nblocks, s.B * s.Hq);
   if (s.kv_dtype == LRQK_KV_BF16)
     hipLaunchKernelGGL((attend_partial_kernel<true>), grid, dim3(kAttThreads), 0, st, mode, fs, q,

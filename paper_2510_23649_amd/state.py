@@ -28,16 +28,23 @@ class LayerBuffers:
                  device="cuda"):
         self.shape = shape
         B, Hq, Hkv, l, C, d, w = shape.B, shape.Hq, shape.Hkv, shape.l, shape.C, shape.d, shape.w
+        rows = shape.rows   # room for the context to grow when shape.l_cap > l
         assert tuple(K.shape) == (B, Hkv, l, d) == tuple(V.shape)
-        self.A_K = A_K.to(device).contiguous()
-        self.K_host = torch.empty(K.shape, dtype=K.dtype, pin_memory=True)
-        self.V_host = torch.empty(V.shape, dtype=V.dtype, pin_memory=True)
-        self.K_host.copy_(K)
-        self.V_host.copy_(V)
+        if rows == l:
+            self.A_K = A_K.to(device).contiguous()
+        else:
+            self.A_K = torch.zeros((B, Hkv, rows, shape.r), dtype=torch.float32, device=device)
+            self.A_K[:, :, :l].copy_(A_K)
+        self.K_host = torch.empty((B, Hkv, rows, d), dtype=K.dtype, pin_memory=True)
+        self.V_host = torch.empty((B, Hkv, rows, d), dtype=V.dtype, pin_memory=True)
+        self.K_host[:, :, :l].copy_(K)
+        self.V_host[:, :, :l].copy_(V)
+        self.K_host[:, :, l:].zero_()
+        self.V_host[:, :, l:].zero_()
         self.liteK = lite_ring(K, l, w).to(device).contiguous()
         self.liteV = lite_ring(V, l, w).to(device).contiguous()
         i32 = dict(dtype=torch.int32, device=device)
-        self.slot_of = torch.empty((B, Hq, l), **i32)
+        self.slot_of = torch.empty((B, Hq, rows), **i32)
         self.token_of = torch.empty((B, Hq, C), **i32)
         self.last_used = torch.empty((B, Hq, C), **i32)
         self.cacheK = torch.zeros((B, Hq, C, d), dtype=K.dtype, device=device)

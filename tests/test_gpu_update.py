@@ -145,3 +145,131 @@ def test_factor_update_rejects_bad_arguments():
     with pytest.raises(L.LrqkError) as e:
         L.lrqk_factor_update(shp16, lay, ti, ti, t, t, t, t, 1.0, 1.0, 2, t, t, workspace(256))
     assert e.value.status == -4
+
+
+# ------------------------------------------------------------------ the whole of Alg. 2, l growing
+
+def grow(ost, n_new_cols=1):
+    """Oracle-side cache state for a context that is one token longer (new token: not cached)."""
+    B, Hq, _ = ost.slot_of.shape
+    ost.slot_of = np.concatenate(
+        [ost.slot_of, np.full((B, Hq, n_new_cols), -1, np.int32)], axis=2)
+
+
+@pytest.mark.parametrize("mode", ["direct", "staged"])
+def test_alg2_steps_with_a_growing_context(mode):
+    """update -> append -> proxy scores / top-k / hit-miss / fetch / attention, for 40 new
+    tokens.  Each step is compared with the oracle on its own: the oracle's update starts from
+    the factors the GPU holds, and its integer decisions use the GPU's q_hat and k_hat (the
+    paper's fp32), so rounding differences of the fp32 algebra are measured, never amplified
+    into a different selection."""
+    from oracle import lrqk_oracle as orc
+    from paper_2510_23649_amd.state import lite_ring
+    from gpu_harness import compare_resolution
+    say(f"Alg. 2 with appended tokens ({mode})")
+    cfg = upd_cfg(B=1, Hq=4, Hkv=2, l=1500, r=16, k=128, w=24, C=256, n_heavy=16)
+    n_new, lam1, lam2 = 40, 1.0, 1.0
+    l_cap = cfg.l + n_new
+    data = make_layer(cfg)
+    kvd = L.LRQK_KV_BF16
+    shape0 = L.Shape.make(B=cfg.B, Hq=cfg.Hq, Hkv=cfg.Hkv, l=cfg.l, r=cfg.r, k=cfg.k, w=cfg.w,
+                          C_slots=cfg.C, kv_dtype=kvd, scale=cfg.scale, l_cap=l_cap)
+    lb = L.LayerBuffers(shape0, data.A_K, data.K, data.V)
+    plan = L.Plan(shape0.with_l(l_cap))
+    fmode = L.LRQK_FETCH_STAGED if mode == "staged" else L.LRQK_FETCH_DIRECT
+    B, Hq, Hkv, G, r, d, w, k = cfg.B, cfg.Hq, cfg.Hkv, cfg.G, cfg.r, cfg.d, cfg.w, cfg.k
+    # oracle side: arrays with room for the new rows
+    A_np = np.zeros((B, Hkv, l_cap, r), np.float32)
+    K_np = np.zeros((B, Hkv, l_cap, d), np.uint16)
+    V_np = np.zeros_like(K_np)
+    A_np[:, :, :cfg.l], K_np[:, :, :cfg.l], V_np[:, :, :cfg.l] = (as_numpy(data.A_K),
+                                                                 as_numpy(data.K), as_numpy(data.V))
+    ost = orc.CacheState(B, Hq, cfg.l, cfg.C)
+    ocK = np.zeros((B, Hq, cfg.C, d), np.uint16)
+    ocV = np.zeros_like(ocK)
+    qs = QueryStream(data)
+    sb = StepBuffers(cfg)
+    out = torch.empty((B, Hq, d), device=DEV)
+    B_Q, B_K, _ = factors_for(cfg, data, seed=11, perturb=0.02)
+    dBQ, dBK = B_Q.to(DEV), B_K.to(DEV)
+    q_hat_d = torch.zeros((B, Hq, r), device=DEV)
+    k_hat_d = torch.zeros((B, Hkv, r), device=DEV)
+    ws = workspace(L.lrqk_workspace_bytes(shape0.with_l(l_cap), L.LRQK_WS_UPDATE))
+    gen = torch.Generator().manual_seed(99)
+    Bm = data.Bmat.cpu().double()
+
+    def step_and_compare(l, step, q, q_hat_t):
+        shp = shape0.with_l(l)
+        L.lrqk_decode_step(plan, shp, step, lb.struct, q_hat_t, q.to(DEV), out, fmode, sb.debug())
+        got = sb.to_np()
+        ref = orc.decode_step(np.ascontiguousarray(A_np[:, :, :l]), as_numpy(q_hat_t),
+                              as_numpy(q), np.ascontiguousarray(K_np[:, :, :l]),
+                              np.ascontiguousarray(V_np[:, :, :l]), ost, ocK, ocV, step, k, w,
+                              cfg.scale)
+        assert ref["ok"]
+        assert np.array_equal(got["sel_idx"], ref["sel_idx"]), f"l={l}: selection differs"
+        compare_resolution(got, ref, f"l={l}")
+        assert np.array_equal(lb.slot_of.cpu().numpy()[:, :, :l], ost.slot_of), f"l={l}: slot_of"
+        assert np.array_equal(lb.token_of.cpu().numpy(), ost.token_of), f"l={l}: token_of"
+        assert np.array_equal(lb.last_used.cpu().numpy(), ost.last_used), f"l={l}: last_used"
+        used = ost.token_of >= 0
+        assert np.array_equal(as_numpy(lb.cacheK)[used], ocK[used]), f"l={l}: cached K rows"
+        assert np.array_equal(as_numpy(lb.cacheV)[used], ocV[used]), f"l={l}: cached V rows"
+        err = np.abs(out.cpu().numpy() - ref["out"]).max()
+        assert err <= 2e-3, f"l={l}: attention error {err}"
+        return got, ref
+
+    step = 0
+    for _ in range(2):                              # warm the cache with the generator's q_hat
+        step += 1
+        q, q_hat = qs.next()
+        prev, _ = step_and_compare(cfg.l, step, q, q_hat.to(DEV))
+    prev_q_hat = as_numpy(q_hat)
+    new_selected = new_fetched = 0
+    worst = 0.0
+    for t in range(n_new):
+        l = cfg.l + t
+        shp = shape0.with_l(l)
+        q, _ = qs.next()
+        # the new key: near the span of B, its factor aligned with the group's first query head
+        # (so that it is selected once it has left the lite window)
+        dirs = torch.from_numpy(prev_q_hat[:, ::G, :].astype(np.float64))
+        k_fac = 3.0 * dirs / dirs.norm(dim=-1, keepdim=True) + 0.3 * torch.randn(
+            B, Hkv, r, generator=gen, dtype=torch.float64)
+        k_new = (torch.einsum("bhr,bhrd->bhd", k_fac, Bm) +
+                 0.05 * torch.randn(B, Hkv, d, generator=gen, dtype=torch.float64)).bfloat16()
+        v_new = torch.randn(B, Hkv, d, generator=gen).bfloat16()
+        BQ_before, BK_before = dBQ.cpu().numpy(), dBK.cpu().numpy()
+        # u1
+        L.lrqk_factor_update(shp, lb.struct, sb.sel_idx, sb.sel_slot, q.to(DEV), k_new.to(DEV),
+                             dBQ, dBK, lam1, lam2, 2, q_hat_d, k_hat_d, ws)
+        ref = upd.factor_update(as_numpy(q), as_numpy(k_new), BQ_before, BK_before, A_np, K_np,
+                                upd.omega_positions(prev["sel_idx"], l, w), lam1, lam2, 2)
+        got = dict(q_hat=q_hat_d.cpu().numpy(), k_hat=k_hat_d.cpu().numpy(),
+                   B_Q=dBQ.cpu().numpy(), B_K=dBK.cpu().numpy())
+        for name, arr in got.items():
+            rel = np.abs(arr - ref[name]).max() / np.abs(ref[name]).max()
+            worst = max(worst, rel)
+            assert rel <= REL_TOL, f"l={l} {name}: {rel}"
+        # u2
+        L.lrqk_append_token(shp, lb.struct, k_hat_d, k_new.to(DEV), v_new.to(DEV))
+        upd.append_token(A_np, K_np, V_np, l, got["k_hat"], as_numpy(k_new), as_numpy(v_new))
+        torch.cuda.synchronize()
+        assert np.array_equal(lb.A_K.cpu().numpy(), A_np), f"l={l}: A_K after append"
+        assert np.array_equal(as_numpy(lb.K_host), K_np), f"l={l}: K store after append"
+        assert np.array_equal(as_numpy(lb.V_host), V_np), f"l={l}: V store after append"
+        ring = lite_ring(torch.from_numpy(K_np.view(np.int16)), l + 1, w).numpy().view(np.uint16)
+        assert np.array_equal(as_numpy(lb.liteK), ring), f"l={l}: lite ring after append"
+        grow(ost)
+        # a1..a5 at length l + 1 with the GPU's q_hat
+        step += 1
+        prev, r2 = step_and_compare(l + 1, step, q, q_hat_d)
+        prev_q_hat = got["q_hat"]
+        new_selected += int((r2["sel_idx"] >= cfg.l).sum())
+        for bh in range(B * Hq):
+            nm = int(r2["n_miss"].reshape(-1)[bh])
+            new_fetched += int((r2["miss_tok"].reshape(B * Hq, k)[bh, :nm] >= cfg.l).sum())
+    say(f"   worst update error {worst:.2e}; appended tokens selected {new_selected} times, "
+        f"fetched from the host store {new_fetched} times")
+    assert new_selected > 0 and new_fetched > 0
+    plan.close()
