@@ -9,14 +9,14 @@
 //     g = sum_i u_i a_i  (r).  Three kinds of jobs share the code:
 //       * Omega of a query head (the k rows selected at the previous step, read from their
 //         cache slots, and the w lite rows): a_i = row of A_K, u_i = q . K_i.  This gives
-//         A_Om^T A_Om and q K_Om^T A_Om.  The row list of a head is cut into chunks of 256
+//         A_Om^T A_Om and q K_Om^T A_Om.  The row list of a head is cut into chunks of 128
 //         rows, one workgroup each, so that batch-1 steps still use hundreds of CUs; K rows
 //         are read by 16 lanes each exactly as the attention kernel reads them;
 //       * B_Q of a query head, read column-wise: a_i = column i of B_Q, u_i = q_i, which
 //         gives B_Q B_Q^T and q B_Q^T;
 //       * B_K of a KV head with u = k_t: B_K B_K^T and k B_K^T.
-//     A batch of 64 rows is staged in LDS, then every thread owns r*r/256 entries of S and
-//     adds the batch's 64 outer products to them; partial sums per chunk go to the
+//     A batch of 128 rows is staged in LDS, then every thread owns r*r/256 entries of S and
+//     adds the batch's 128 outer products to them; partial sums per chunk go to the
 //     workspace and are added up, in chunk order, by the second kernel: no atomics, the
 //     result does not depend on scheduling.
 //
@@ -25,21 +25,40 @@
 //     holds row i of the matrix in registers, a right-looking Cholesky factorisation takes
 //     column j from lane registers with v_readlane (all register indices are compile-time
 //     constants), the two triangular solves follow the same pattern, with one transpose of
-//     the factor through LDS in between.  The alternating updates of q_hat (per query
-//     head) and k_hat (per KV head, summed over the group's heads) exchange q_hat through
-//     LDS; every wavefront solves the small k_hat system redundantly, which is cheaper than
-//     a second exchange.  The same kernel then applies the two rank-one gradient steps to
-//     B_Q and B_K in place.
+//     the factor through LDS in between.  Only what changes between rounds is factorised
+//     again: M_rq = P + lambda_d1 k_hat^T k_hat differs from the fixed
+//     P = B_Q B_Q^T + lambda_d2 A_Om^T A_Om by a rank-one term, so P is factorised once and
+//     each q_hat costs one pair of triangular solves (Sherman-Morrison); the k_hat system
+//     changes by a rank-G term and is factorised anew each round.  The alternating updates
+//     of q_hat (per query head) and k_hat (per KV head, summed over the group's heads)
+//     exchange q_hat through LDS; every wavefront solves the k_hat system redundantly, which
+//     is cheaper than a second exchange.  The same kernel then applies the two rank-one
+//     gradient steps to B_Q and B_K in place.
 //
 // All arithmetic is fp32 (App. B.1 runs these updates in fp32).
 #include "lrqk_device.h"
 #include "lrqk_internal.h"
 
+#ifdef LRQK_KPROF
+__device__ unsigned long long g_kprof_fu[16];
+#define FKPROF(i)                                                            \
+  do {                                                                       \
+    if (blockIdx.x == 0 && threadIdx.x == 0) g_kprof_fu[i] = wall_clock64(); \
+  } while (0)
+extern "C" __attribute__((visibility("default"))) int lrqk_kprof_fu_read(unsigned long long* out) {
+  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_kprof_fu), sizeof(g_kprof_fu));
+}
+#else
+#define FKPROF(i) \
+  do {            \
+  } while (0)
+#endif
+
 namespace lrqk {
 namespace {
 
 constexpr int kGramThreads = 256;
-constexpr int kGramBatch = 64;   // rows staged in LDS at a time
+constexpr int kGramBatch = 128;  // rows staged in LDS at a time
 
 template <int CTRL>
 __device__ __forceinline__ float fu_dpp(float v) {
@@ -249,51 +268,88 @@ __device__ __forceinline__ float lane_value(float v, int lane) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
 }
 
-// Solves x M = b for symmetric positive definite M.  Lane i (< R) holds row i of M in m[]
-// and b_i in b; returns x_i in lane i.  m[] is destroyed.  lt: R * (R + 1) floats of LDS owned
-// by this wavefront.
+// Building blocks; lane i (< R) holds row i of the matrix in m[], element i of a vector in a
+// scalar.  All loops are fully unrolled, so every register index is a constant.
+//
+// Right-looking Cholesky factorisation M = L L^T, in place: afterwards m[j] of lane i >= j
+// holds L[i][j].  Returns, in lane j, 1 / L[j][j].  Two independent matrices are factorised
+// together so that their dependency chains interleave.
 template <int R>
-__device__ __forceinline__ float chol_solve(float (&m)[R], float b, float* lt, int lane) {
-  float dinv = 0.0f;  // lane j keeps 1 / L[j][j]
-  // right-looking Cholesky: after step j, m[j] of lane i >= j holds L[i][j]
+__device__ __forceinline__ void chol_factor2(float (&m0)[R], float (&m1)[R], float& dinv0,
+                                             float& dinv1, int lane) {
+  dinv0 = dinv1 = 0.0f;
 #pragma unroll
   for (int j = 0; j < R; ++j) {
-    const float djj = lane_value(m[j], j);
-    const float inv = 1.0f / sqrtf(djj);
+    const float inv0 = __builtin_amdgcn_rsqf(lane_value(m0[j], j));
+    const float inv1 = __builtin_amdgcn_rsqf(lane_value(m1[j], j));
+    const float l0 = m0[j] * inv0, l1 = m1[j] * inv1;
+    m0[j] = l0;
+    m1[j] = l1;
+    if (lane == j) {
+      dinv0 = inv0;
+      dinv1 = inv1;
+    }
+#pragma unroll
+    for (int c = j + 1; c < R; ++c) {
+      m0[c] = __builtin_fmaf(-l0, lane_value(l0, c), m0[c]);
+      m1[c] = __builtin_fmaf(-l1, lane_value(l1, c), m1[c]);
+    }
+  }
+}
+template <int R>
+__device__ __forceinline__ float chol_factor(float (&m)[R], int lane) {
+  float dinv = 0.0f;
+#pragma unroll
+  for (int j = 0; j < R; ++j) {
+    const float inv = __builtin_amdgcn_rsqf(lane_value(m[j], j));
     const float lij = m[j] * inv;
     m[j] = lij;
     if (lane == j) dinv = inv;
 #pragma unroll
     for (int c = j + 1; c < R; ++c) m[c] = __builtin_fmaf(-lij, lane_value(lij, c), m[c]);
   }
-  // forward: L y = b
+  return dinv;
+}
+// L y = b with L[i][j] = L[j] of lane i
+template <int R>
+__device__ __forceinline__ float tri_forward(const float (&L)[R], float dinv, float b, int lane) {
   float y = 0.0f;
 #pragma unroll
   for (int j = 0; j < R; ++j) {
     const float yj = lane_value(b * dinv, j);
     if (lane == j) y = yj;
-    b = __builtin_fmaf(-m[j], yj, b);
+    b = __builtin_fmaf(-L[j], yj, b);
   }
-  // transpose the factor through LDS: afterwards m[c] of lane i holds L[c][i]
-  if (lane < R) {
-#pragma unroll
-    for (int c = 0; c < R; ++c) lt[lane * (R + 1) + c] = m[c];
-  }
-  __builtin_amdgcn_wave_barrier();
-  if (lane < R) {
-#pragma unroll
-    for (int c = 0; c < R; ++c) m[c] = lt[c * (R + 1) + lane];
-  }
-  __builtin_amdgcn_wave_barrier();
-  // backward: L^T x = y
+  return y;
+}
+// L^T x = y with the transposed factor: Lt[j] of lane i = L[j][i]
+template <int R>
+__device__ __forceinline__ float tri_backward(const float (&Lt)[R], float dinv, float y, int lane) {
   float x = 0.0f;
 #pragma unroll
   for (int j = R - 1; j >= 0; --j) {
     const float xj = lane_value(y * dinv, j);
     if (lane == j) x = xj;
-    y = __builtin_fmaf(-m[j], xj, y);
+    y = __builtin_fmaf(-Lt[j], xj, y);
   }
   return x;
+}
+// out[c] of lane i = in[i] of lane c, through R * (R + 1) floats of LDS owned by the wavefront
+// (in and out may be the same array)
+template <int R>
+__device__ __forceinline__ void transpose_rows(const float (&in)[R], float (&out)[R], float* lt,
+                                               int lane) {
+  __builtin_amdgcn_wave_barrier();
+  if (lane < R) {
+#pragma unroll
+    for (int c = 0; c < R; ++c) lt[lane * (R + 1) + c] = in[c];
+  }
+  __builtin_amdgcn_wave_barrier();
+  if (lane < R) {
+#pragma unroll
+    for (int c = 0; c < R; ++c) out[c] = lt[c * (R + 1) + lane];
+  }
+  __builtin_amdgcn_wave_barrier();
 }
 
 struct SolveArgs {
@@ -344,9 +400,11 @@ __global__ __launch_bounds__(kMaxG * 64) void factor_solve_kernel(SolveArgs a) {
   constexpr size_t ROWB = kD * (BF16 ? 2 : 4);
   extern __shared__ __align__(16) float lds[];
   const int G = a.Hq / a.Hkv;
-  // [G][R*(R+1)] transpose space | [G][R] q_hat exchange | [G] q.k
+  constexpr int NLD = R + 4;  // padded row of the LDS copy of N
+  // [G][R*(R+1)] transpose space | [R][NLD] N = B_K B_K^T | [G][R] q_hat exchange | [G] q.k
   float* const lt = lds + (size_t)(threadIdx.x >> 6) * R * (R + 1);
-  float* const qhat_s = lds + (size_t)G * R * (R + 1);
+  float* const n_s = lds + ((size_t)G * R * (R + 1) + 3) / 4 * 4;
+  float* const qhat_s = n_s + R * NLD;
   float* const qk_s = qhat_s + G * R;
 
   const int bkv = blockIdx.x;
@@ -356,67 +414,138 @@ __global__ __launch_bounds__(kMaxG * 64) void factor_solve_kernel(SolveArgs a) {
   const bool row = lane < R;
   const int li = row ? lane : 0;  // keeps the loads of idle lanes in bounds
 
-  // P = B_Q B_Q^T + lambda_d2 A_Om^T A_Om (row li),  cvec = q B_Q^T + lambda_d2 q K_Om^T A_Om;
-  // N = B_K B_K^T (row li),  nb = k B_K^T.  The chunk partials are added in chunk order.
-  float P[R], N[R], m[R];
+  FKPROF(0);
+  const float* qp = a.q + (size_t)bh * kD;
+  const char* kp = static_cast<const char*>(a.k_new) + (size_t)bkv * ROWB;
+  const float qk_part = qp[lane] * kv_load<BF16>(kp, lane) +
+                        qp[lane + 64] * kv_load<BF16>(kp, lane + 64);
+  // P = B_Q B_Q^T + lambda_d2 A_Om^T A_Om,  cvec = q B_Q^T + lambda_d2 q K_Om^T A_Om;
+  // N = B_K B_K^T,  nb = k B_K^T.  The chunk partials are added in chunk order.  They are
+  // read with consecutive lanes on consecutive 16-byte pieces and turned into "lane = row"
+  // through LDS.
+  float p[R], pt[R], m[R];
   float cvec, nb;
   {
+    constexpr int U = (kEntries / 4 + 63) / 64;  // 16-byte pieces of an r x r matrix per lane
     const float* gq = a.gram_q + (size_t)bh * (kEntries + R);
     const float* gk = a.gram_k + (size_t)bkv * (kEntries + R);
+    float4 acc[U], vq[U], vk[U];
 #pragma unroll
-    for (int c = 0; c < R; ++c) m[c] = 0.0f;
-    float gsum = 0.0f;
-    for (int s = 0; s < a.nchunk; ++s) {
-      const float* go = a.gram_om + ((size_t)bh * a.nchunk + s) * (kEntries + R);
-#pragma unroll
-      for (int c4 = 0; c4 < R / 4; ++c4) {
-        const float4 v = reinterpret_cast<const float4*>(go + (size_t)li * R)[c4];
-        m[4 * c4 + 0] += v.x; m[4 * c4 + 1] += v.y; m[4 * c4 + 2] += v.z; m[4 * c4 + 3] += v.w;
-      }
-      gsum += go[kEntries + li];
+    for (int u = 0; u < U; ++u) {
+      acc[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      const int e4 = lane + 64 * u;  // issued first: these loads overlap the first round below
+      const bool on = e4 < kEntries / 4;
+      vq[u] = on ? reinterpret_cast<const float4*>(gq)[e4] : acc[u];
+      vk[u] = (on && g == 0) ? reinterpret_cast<const float4*>(gk)[e4] : acc[u];
     }
-#pragma unroll
-    for (int c = 0; c < R; ++c) {
-      P[c] = __builtin_fmaf(a.lam2, m[c], gq[(size_t)li * R + c]);
-      N[c] = gk[(size_t)li * R + c];
-    }
-    cvec = __builtin_fmaf(a.lam2, gsum, gq[kEntries + li]);
+    const float cq = gq[kEntries + li];
     nb = gk[kEntries + li];
+    float gsum = 0.0f;
+    // chunks whose loads are in flight together (the partials were written by the previous
+    // kernel and come from memory, so each round of loads costs a full memory latency)
+    constexpr int SB = U >= 16 ? 2 : (U >= 4 ? 9 : 16);
+    const float* go0 = a.gram_om + (size_t)bh * a.nchunk * (kEntries + R);
+    for (int s0 = 0; s0 < a.nchunk; s0 += SB) {
+      float4 v[SB][U];
+      float gv[SB];
+#pragma unroll
+      for (int j = 0; j < SB; ++j) {
+        const bool on = s0 + j < a.nchunk;
+        const float* go = go0 + (size_t)(on ? s0 + j : s0) * (kEntries + R);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int e4 = lane + 64 * u;
+          v[j][u] = (on && e4 < kEntries / 4) ? reinterpret_cast<const float4*>(go)[e4]
+                                              : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        gv[j] = on ? go[kEntries + li] : 0.0f;
+      }
+#pragma unroll
+      for (int j = 0; j < SB; ++j) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          acc[u].x += v[j][u].x; acc[u].y += v[j][u].y;
+          acc[u].z += v[j][u].z; acc[u].w += v[j][u].w;
+        }
+        gsum += gv[j];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int e4 = lane + 64 * u;
+      if (e4 < kEntries / 4) {
+        const int e = 4 * e4, rr = e / R, cc = e % R;
+        lt[rr * (R + 1) + cc + 0] = __builtin_fmaf(a.lam2, acc[u].x, vq[u].x);
+        lt[rr * (R + 1) + cc + 1] = __builtin_fmaf(a.lam2, acc[u].y, vq[u].y);
+        lt[rr * (R + 1) + cc + 2] = __builtin_fmaf(a.lam2, acc[u].z, vq[u].z);
+        lt[rr * (R + 1) + cc + 3] = __builtin_fmaf(a.lam2, acc[u].w, vq[u].w);
+        if (g == 0) *reinterpret_cast<float4*>(&n_s[rr * NLD + cc]) = vk[u];
+      }
+    }
+    cvec = __builtin_fmaf(a.lam2, gsum, cq);
+    __syncthreads();  // n_s (and, within the wavefront, lt) is complete
+#pragma unroll
+    for (int c = 0; c < R; ++c) p[c] = lt[li * (R + 1) + c];
+#pragma unroll
+    for (int c4 = 0; c4 < R / 4; ++c4) {
+      const float4 vk = *reinterpret_cast<const float4*>(&n_s[li * NLD + 4 * c4]);
+      m[4 * c4 + 0] = vk.x; m[4 * c4 + 1] = vk.y; m[4 * c4 + 2] = vk.z; m[4 * c4 + 3] = vk.w;
+    }
   }
 
   // q . k of this query head
-  const float* qp = a.q + (size_t)bh * kD;
-  const char* kp = static_cast<const char*>(a.k_new) + (size_t)bkv * ROWB;
-  const float qk = wave_sum(qp[lane] * kv_load<BF16>(kp, lane) +
-                            qp[lane + 64] * kv_load<BF16>(kp, lane + 64));
+  const float qk = wave_sum(qk_part);
   if (lane == 0) qk_s[g] = qk;
 
+  FKPROF(1);
+  // Factorise N (for the initial guess) and P (kept for every round) together.
+  float dN, dP;
+  chol_factor2<R>(m, p, dN, dP, lane);
+  FKPROF(2);
   // initial guess (lambda_d1 = 0): k_hat = k B_K^T (B_K B_K^T)^-1
-#pragma unroll
-  for (int c = 0; c < R; ++c) m[c] = N[c];
-  float k_hat = chol_solve<R>(m, nb, lt, lane);
+  float k_hat = tri_forward<R>(m, dN, nb, lane);
+  transpose_rows<R>(m, m, lt, lane);
+  k_hat = tri_backward<R>(m, dN, k_hat, lane);
+  // y0 = cvec P^-1
+  transpose_rows<R>(p, pt, lt, lane);
+  const float y0 = tri_backward<R>(pt, dP, tri_forward<R>(p, dP, cvec, lane), lane);
+
+  FKPROF(3);
   float q_hat = 0.0f;
   for (int it = 0; it < a.n_iter; ++it) {
-    // q_hat = m_lq M_rq^-1
-#pragma unroll
-    for (int c = 0; c < R; ++c)
-      m[c] = __builtin_fmaf(a.lam1 * k_hat, lane_value(k_hat, c), P[c]);
-    q_hat = chol_solve<R>(m, __builtin_fmaf(a.lam1 * qk, k_hat, cvec), lt, lane);
+    // q_hat = m_lq M_rq^-1 with M_rq = P + lambda_d1 k_hat^T k_hat a rank-one change of P:
+    //   z = k_hat P^-1,  v = m_lq P^-1 = y0 + lambda_d1 (q.k) z,
+    //   q_hat = v - z * lambda_d1 (k_hat . v) / (1 + lambda_d1 (k_hat . z))
+    const float z = tri_backward<R>(pt, dP, tri_forward<R>(p, dP, k_hat, lane), lane);
+    const float v = __builtin_fmaf(a.lam1 * qk, z, y0);
+    const float kv_ = wave_sum(row ? k_hat * v : 0.0f);
+    const float kz = wave_sum(row ? k_hat * z : 0.0f);
+    q_hat = __builtin_fmaf(-z, a.lam1 * kv_ / __builtin_fmaf(a.lam1, kz, 1.0f), v);
+    if (it == 0) FKPROF(4);
     __syncthreads();  // the previous round's q_hat has been read by every wavefront
     if (row) qhat_s[g * R + lane] = q_hat;
     __syncthreads();
     // k_hat = (k B_K^T + lambda_d1 sum_g (q_g.k) q_hat_g)(B_K B_K^T + lambda_d1 sum_g q_hat_g^T q_hat_g)^-1
     float rhs = nb;
 #pragma unroll
-    for (int c = 0; c < R; ++c) m[c] = N[c];
+    for (int c4 = 0; c4 < R / 4; ++c4) {
+      const float4 vk = *reinterpret_cast<const float4*>(&n_s[li * NLD + 4 * c4]);
+      m[4 * c4 + 0] = vk.x; m[4 * c4 + 1] = vk.y; m[4 * c4 + 2] = vk.z; m[4 * c4 + 3] = vk.w;
+    }
     for (int gg = 0; gg < G; ++gg) {
       const float qi = qhat_s[gg * R + li];
       rhs = __builtin_fmaf(a.lam1 * qk_s[gg], qi, rhs);
 #pragma unroll
       for (int c = 0; c < R; ++c) m[c] = __builtin_fmaf(a.lam1 * qi, qhat_s[gg * R + c], m[c]);
     }
-    k_hat = chol_solve<R>(m, rhs, lt, lane);
+    if (it == 0) FKPROF(5);
+    const float dM = chol_factor<R>(m, lane);
+    k_hat = tri_forward<R>(m, dM, rhs, lane);
+    transpose_rows<R>(m, m, lt, lane);
+    k_hat = tri_backward<R>(m, dM, k_hat, lane);
+    if (it == 0) FKPROF(6);
   }
+  FKPROF(7);
   if (row) a.q_hat[(size_t)bh * R + lane] = q_hat;
   if (row && g == 0) a.k_hat[(size_t)bkv * R + lane] = k_hat;
 
@@ -425,6 +554,7 @@ __global__ __launch_bounds__(kMaxG * 64) void factor_solve_kernel(SolveArgs a) {
   if (g == 0)
     line_search_step<R>(k_hat, a.B_K + (size_t)bkv * R * kD,
                         [&](int j) { return kv_load<BF16>(kp, j); }, lane);
+  FKPROF(8);
 }
 
 template <int R, bool BF16>
@@ -433,7 +563,9 @@ hipError_t launch_update_r(const lrqk_shape& s, const GramArgs& ga, const SolveA
   const int G = s.Hq / s.Hkv;
   hipLaunchKernelGGL((factor_gram_kernel<R, BF16>), dim3(ga.nchunk + 2, s.B * s.Hq),
                      dim3(kGramThreads), 0, st, ga);
-  const size_t lds = ((size_t)G * R * (R + 1) + (size_t)G * R + G) * sizeof(float);
+  const size_t lds =
+      (((size_t)G * R * (R + 1) + 3) / 4 * 4 + (size_t)R * (R + 4) + (size_t)G * R + G) *
+      sizeof(float);
   if (lds > 64 * 1024) {  // above the default limit the kernel has to opt in, once
     static bool raised = false;
     if (!raised) {
@@ -457,7 +589,7 @@ bool factor_update_supported(const lrqk_shape& s) {
 
 UpdateGeom update_geometry(const lrqk_shape& s) {
   UpdateGeom g;
-  g.chunk_rows = 256;
+  g.chunk_rows = 128;
   g.nchunk = ceil_div(s.k + s.w, g.chunk_rows);
   g.per_gram = (size_t)s.r * s.r + s.r;
   return g;
