@@ -9,14 +9,14 @@
 //     g = sum_i u_i a_i  (r).  Three kinds of jobs share the code:
 //       * Omega of a query head (the k rows selected at the previous step, read from their
 //         cache slots, and the w lite rows): a_i = row of A_K, u_i = q . K_i.  This gives
-//         A_Om^T A_Om and q K_Om^T A_Om.  The row list of a head is cut into chunks of 128
-//         rows, one workgroup each, so that batch-1 steps still use hundreds of CUs; K rows
+//         A_Om^T A_Om and q K_Om^T A_Om.  The row list of a head is cut into chunks of at most
+//         144 rows, one workgroup each, so that batch-1 steps still use hundreds of CUs; K rows
 //         are read by 16 lanes each exactly as the attention kernel reads them;
 //       * B_Q of a query head, read column-wise: a_i = column i of B_Q, u_i = q_i, which
 //         gives B_Q B_Q^T and q B_Q^T;
 //       * B_K of a KV head with u = k_t: B_K B_K^T and k B_K^T.
-//     A batch of 128 rows is staged in LDS, then every thread owns r*r/256 entries of S and
-//     adds the batch's 128 outer products to them; partial sums per chunk go to the
+//     The chunk's rows are staged in LDS, then every thread owns r*r/256 entries of S and
+//     adds the rows' outer products to them; partial sums per chunk go to the
 //     workspace and are added up, in chunk order, by the second kernel: no atomics, the
 //     result does not depend on scheduling.
 //
@@ -58,7 +58,7 @@ namespace lrqk {
 namespace {
 
 constexpr int kGramThreads = 256;
-constexpr int kGramBatch = 128;  // rows staged in LDS at a time
+constexpr int kGramBatch = 144;  // rows staged in LDS at a time (a multiple of 16)
 
 template <int CTRL>
 __device__ __forceinline__ float fu_dpp(float v) {
@@ -234,12 +234,15 @@ __global__ __launch_bounds__(kGramThreads) void factor_gram_kernel(GramArgs a) {
       __syncthreads();
       if (t < kGramBatch) {
         const int i = i0 + t;
-        u_s[t] = isq ? a.q[(size_t)bh * kD + i]
-                     : kv_load<BF16>(static_cast<const char*>(a.k_new) + (size_t)bkv * ROWB, i);
+        float u = 0.0f;
+        if (i < kD)
+          u = isq ? a.q[(size_t)bh * kD + i]
+                  : kv_load<BF16>(static_cast<const char*>(a.k_new) + (size_t)bkv * ROWB, i);
+        u_s[t] = u;
       }
       for (int idx = t; idx < kGramBatch * R; idx += kGramThreads) {
         const int c = idx / kGramBatch, ii = idx % kGramBatch;
-        a_s[ii * LDA + c] = Bm[(size_t)c * kD + i0 + ii];
+        a_s[ii * LDA + c] = i0 + ii < kD ? Bm[(size_t)c * kD + i0 + ii] : 0.0f;
       }
       __syncthreads();
       if (t < kActive) {
@@ -429,12 +432,13 @@ __global__ __launch_bounds__(kMaxG * 64) void factor_solve_kernel(SolveArgs a) {
     constexpr int U = (kEntries / 4 + 63) / 64;  // 16-byte pieces of an r x r matrix per lane
     const float* gq = a.gram_q + (size_t)bh * (kEntries + R);
     const float* gk = a.gram_k + (size_t)bkv * (kEntries + R);
+    constexpr bool kHoist = U <= 4;  // large r: too many registers to hold them that long
     float4 acc[U], vq[U], vk[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       acc[u] = make_float4(0.f, 0.f, 0.f, 0.f);
       const int e4 = lane + 64 * u;  // issued first: these loads overlap the first round below
-      const bool on = e4 < kEntries / 4;
+      const bool on = kHoist && e4 < kEntries / 4;
       vq[u] = on ? reinterpret_cast<const float4*>(gq)[e4] : acc[u];
       vk[u] = (on && g == 0) ? reinterpret_cast<const float4*>(gk)[e4] : acc[u];
     }
@@ -443,7 +447,7 @@ __global__ __launch_bounds__(kMaxG * 64) void factor_solve_kernel(SolveArgs a) {
     float gsum = 0.0f;
     // chunks whose loads are in flight together (the partials were written by the previous
     // kernel and come from memory, so each round of loads costs a full memory latency)
-    constexpr int SB = U >= 16 ? 2 : (U >= 4 ? 9 : 16);
+    constexpr int SB = U >= 16 ? 2 : (U >= 4 ? 8 : 16);
     const float* go0 = a.gram_om + (size_t)bh * a.nchunk * (kEntries + R);
     for (int s0 = 0; s0 < a.nchunk; s0 += SB) {
       float4 v[SB][U];
@@ -474,6 +478,10 @@ __global__ __launch_bounds__(kMaxG * 64) void factor_solve_kernel(SolveArgs a) {
     for (int u = 0; u < U; ++u) {
       const int e4 = lane + 64 * u;
       if (e4 < kEntries / 4) {
+        if (!kHoist) {
+          vq[u] = reinterpret_cast<const float4*>(gq)[e4];
+          if (g == 0) vk[u] = reinterpret_cast<const float4*>(gk)[e4];
+        }
         const int e = 4 * e4, rr = e / R, cc = e % R;
         lt[rr * (R + 1) + cc + 0] = __builtin_fmaf(a.lam2, acc[u].x, vq[u].x);
         lt[rr * (R + 1) + cc + 1] = __builtin_fmaf(a.lam2, acc[u].y, vq[u].y);
@@ -589,8 +597,9 @@ bool factor_update_supported(const lrqk_shape& s) {
 
 UpdateGeom update_geometry(const lrqk_shape& s) {
   UpdateGeom g;
-  g.chunk_rows = 128;
-  g.nchunk = ceil_div(s.k + s.w, g.chunk_rows);
+  // as few chunks of at most one LDS batch as cover the k + w rows, evenly sized
+  g.nchunk = ceil_div(s.k + s.w, kGramBatch);
+  g.chunk_rows = ceil_div(ceil_div(s.k + s.w, g.nchunk), 16) * 16;
   g.per_gram = (size_t)s.r * s.r + s.r;
   return g;
 }
