@@ -49,6 +49,10 @@ def main():
     ap.add_argument("--mode", choices=["staged", "direct"], default="direct")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--no-alg2", action="store_true",
+                    help="skip the extra section that times the whole of Alg. 2 (factor update, "
+                         "append, then the step)")
+    ap.add_argument("--alg2-steps", type=int, default=64)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -75,25 +79,30 @@ def main():
                          C_slots=cfg.C, d=cfg.d, scale=cfg.scale,
                          kv_dtype=L.LRQK_KV_BF16 if cfg.kv_dtype == "bf16" else L.LRQK_KV_F32)
     mode = L.LRQK_FETCH_STAGED if args.mode == "staged" else L.LRQK_FETCH_DIRECT
+    with_alg2 = not args.no_alg2 and cfg.r in (8, 16, 32, 64)
+    if with_alg2:      # room for the tokens the Alg. 2 section appends after the timed region
+        alg2_per_layer = -(-args.alg2_steps // cfg.layers) + 1
+        shape.l_cap = cfg.l + alg2_per_layer
 
     def log(msg):
         print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
     # ---------------------------------------------------------------- inputs (untimed)
     t0 = time.time()
-    layers, streams = [], []
+    layers, streams, bmats = [], [], []
     oracle_layer = None
     for li in range(nl):
         data = make_layer(cfg, li, device=dev)
         layers.append(L.LayerBuffers(shape, data.A_K, data.K, data.V))
         streams.append(QueryStream(data))
+        bmats.append(data.Bmat)
         if li == 0 and not args.no_cpu_baseline:
             oracle_layer = dict(A_K=as_numpy(data.A_K), K=as_numpy(data.K), V=as_numpy(data.V))
         data.K = data.V = data.A_K = None
         if li % 8 == 7:
             log(f"generated {li + 1}/{nl} layers ({time.time() - t0:.1f}s)")
     torch.cuda.synchronize()
-    plan = L.Plan(shape)
+    plan = L.Plan(shape.with_l(shape.rows))
     out = torch.empty((cfg.B, cfg.Hq, cfg.d), device=dev)
     n_miss = torch.zeros((cfg.B, cfg.Hq), dtype=torch.int32, device=dev)
     dbg = dict(n_miss=n_miss)
@@ -172,6 +181,65 @@ def main():
                   + 2 * cfg.B * cfg.Hq * cfg.d * 4 + 2 * cfg.B * cfg.Hq * cfg.k * 4)
     gpu_us = sum(phases_us.values())
 
+    # ---------------------------------------------------------------- the whole of Alg. 2
+    # (outside the headline metric) factor update -> append -> the step at length l + 1, on the
+    # same layers; B_K starts at the generator's basis, B_Q at its dual basis, k_t, v_t random
+    alg2 = None
+    if with_alg2:
+        i32 = dict(dtype=torch.int32, device=dev)
+        sel_idx = [torch.zeros((cfg.B, cfg.Hq, cfg.k), **i32) for _ in range(nl)]
+        sel_slot = [torch.zeros((cfg.B, cfg.Hq, cfg.k), **i32) for _ in range(nl)]
+        B_Q, B_K = [], []
+        for li in range(nl):
+            Bm = bmats[li]
+            dual = torch.linalg.solve(Bm @ Bm.transpose(-1, -2), Bm)
+            B_Q.append(dual.repeat_interleave(cfg.G, dim=1).contiguous())
+            B_K.append(Bm.clone().contiguous())
+            q, q_hat = streams[li].next()       # leaves this layer's previous selection
+            run_step(li, q, q_hat, debug=dict(sel_idx=sel_idx[li], sel_slot=sel_slot[li]))
+        ws_u = torch.empty(L.lrqk_workspace_bytes(shape.with_l(shape.rows), L.LRQK_WS_UPDATE),
+                           dtype=torch.uint8, device=dev)
+        q_hat_u = torch.zeros((cfg.B, cfg.Hq, cfg.r), device=dev)
+        k_hat_u = torch.zeros((cfg.B, cfg.Hkv, cfg.r), device=dev)
+        n2 = args.alg2_steps
+        kvdt = torch.bfloat16 if cfg.kv_dtype == "bf16" else torch.float32
+        qs2 = [streams[i % nl].next()[0] for i in range(n2)]
+        kn = [torch.randn(cfg.B, cfg.Hkv, cfg.d, device=dev).to(kvdt) for _ in range(n2)]
+        vn = [torch.randn(cfg.B, cfg.Hkv, cfg.d, device=dev).to(kvdt) for _ in range(n2)]
+        l_now = [cfg.l] * nl
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(n2)]
+        torch.cuda.synchronize()
+        t_a = time.perf_counter()
+        for i in range(n2):
+            li = i % nl
+            shp = shape.with_l(l_now[li])
+            ev[i][0].record()
+            L.lrqk_factor_update(shp, layers[li].struct, sel_idx[li], sel_slot[li], qs2[i], kn[i],
+                                 B_Q[li], B_K[li], 1.0, 1.0, 2, q_hat_u, k_hat_u, ws_u)
+            ev[i][1].record()
+            L.lrqk_append_token(shp, layers[li].struct, k_hat_u, kn[i], vn[i])
+            ev[i][2].record()
+            l_now[li] += 1
+            step_no[li] += 1
+            L.lrqk_decode_step(plan, shape.with_l(l_now[li]), step_no[li], layers[li].struct,
+                               q_hat_u, qs2[i], out, mode,
+                               dict(sel_idx=sel_idx[li], sel_slot=sel_slot[li]))
+            ev[i][3].record()
+        torch.cuda.synchronize()
+        t_b = time.perf_counter()
+        skip = min(8, n2 // 2)
+        seg = np.array([[ev[i][j].elapsed_time(ev[i][j + 1]) * 1e3 for j in range(3)]
+                        for i in range(skip, n2)])
+        alg2 = {"steps": n2, "us_per_step_wall": (t_b - t_a) / n2 * 1e6,
+                "factor_update_us": float(seg[:, 0].mean()),
+                "append_token_us": float(seg[:, 1].mean()),
+                "decode_step_us": float(seg[:, 2].mean()),
+                "lambda_d1": 1.0, "lambda_d2": 1.0, "rounds": 2,
+                "note": "HIP-event time of each call on the launch stream; the wall figure "
+                        "includes the Python launch loop"}
+        log(f"Alg. 2: update {alg2['factor_update_us']:.1f} us, append "
+            f"{alg2['append_token_us']:.1f} us, step {alg2['decode_step_us']:.1f} us")
+
     # ---------------------------------------------------------------- CPU oracle baseline
     cpu = None
     if oracle_layer is not None:
@@ -212,6 +280,7 @@ def main():
                      "algorithmic_bytes_per_launch": a_k_bytes},
         "cpu_baseline": cpu,
         "phases_us": phases_us,
+        "alg2": alg2,
         "step_roofline": {"algorithmic_bytes_per_step": step_bytes,
                           "gpu_us_per_step_sum_of_phases": gpu_us,
                           "achieved_GBs_end_to_end": step_bytes / (ms_per_step * 1e-3) / 1e9,
