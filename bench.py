@@ -35,7 +35,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM traffic of one proxy-score launch measured with rocprofv3 --pmc (FETCH_SIZE, then
 # WRITE_SIZE, each scaled by what the same counter reads for lrqk_calib_copy), bytes per launch:
 # profiles/proxy_scores_c3_r32_hbm_traffic.md.  Only for the workload it was measured on.
-MEASURED_TRAFFIC = {"c3_r32": 130618 * 1024 + 2611 * 1024}
+MEASURED_TRAFFIC = {"c3_r32": 130637 * 1024 + 2611 * 1024}
 
 
 def main():
