@@ -66,9 +66,11 @@ enum {
   LRQK_FETCH_STAGED = 0, /* miss list -> host, host gathers rows into a pinned staging
                             buffer, one hipMemcpyAsync on the plan's side stream, then a
                             scatter kernel into the cache slots                        */
-  LRQK_FETCH_DIRECT = 1  /* a kernel reads the rows straight out of the pinned host store
-                            (device-visible host memory) and writes the cache slots;
-                            no host synchronisation                                    */
+  LRQK_FETCH_DIRECT = 1  /* the GPU reads the rows straight out of the pinned host store
+                            (device-visible host memory) and writes the cache slots; no host
+                            synchronisation.  lrqk_fetch_misses does it in a kernel of its
+                            own; lrqk_decode_step does it inside the attention kernel, so the
+                            host-link reads overlap the HBM reads of the rows that hit      */
 };
 
 /*
@@ -250,9 +252,12 @@ typedef struct lrqk_step_debug {
 /*
  * a1..a5 as one call (Alg. 2 from the proxy-attention line to the attention of
  * Sec. 4.3; Fig. 2: selection, then a small cache load overlapped with attention).
- * Scores never leave the library's workspace.  Attention over the hit rows and
- * the lite rows runs on `stream` while the missing rows travel on the plan's
- * side stream (STAGED) and are attended afterwards; partial results are merged.
+ * Scores never leave the library's workspace (for the shapes the filtered proxy-score
+ * pass supports they are not even materialised).  STAGED: attention over the hit rows and
+ * the lite rows runs on `stream` while the missing rows travel on the plan's side stream
+ * and are attended afterwards; partial results are merged.  DIRECT: one attention launch
+ * over all rows, the missing ones read from the host store and written to their slots on
+ * the way.
  *   q_hat  device fp32 [B,Hq,r];  q  device fp32 [B,Hq,d];  out  device fp32 [B,Hq,d]
  *   step   as in lrqk_cache_resolve
  *   mode   LRQK_FETCH_STAGED (one host synchronisation per call, to read the miss

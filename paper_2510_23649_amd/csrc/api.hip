@@ -308,8 +308,9 @@ int lrqk_plan_destroy(lrqk_plan* p) {
   (void)hipGetDevice(&prev);
   (void)hipSetDevice(p->device);
   if (p->side) (void)hipStreamSynchronize(p->side);
-  void* dev[] = {p->scores, p->thr, p->samples, p->filter, p->cand_scores, p->select_ws, p->partials, p->sel_idx, p->sel_slot, p->miss_tok,
-                 p->miss_slot, p->n_miss, p->hit, p->d_stage, p->d_rowdst};
+  void* dev[] = {p->scores,   p->thr,      p->samples,  p->filter,    p->cand_scores,
+                 p->select_ws, p->partials, p->sel_idx,  p->sel_slot,  p->miss_tok,
+                 p->miss_slot, p->n_miss,   p->hit,      p->d_stage,   p->d_rowdst};
   for (void* q : dev)
     if (q) (void)hipFree(q);
   void* host[] = {p->h_nmiss, p->h_miss_tok, p->h_miss_slot, p->h_stage, p->h_rowdst};

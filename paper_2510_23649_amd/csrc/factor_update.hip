@@ -533,7 +533,8 @@ __global__ __launch_bounds__(kMaxG * 64) void factor_solve_kernel(SolveArgs a) {
     __syncthreads();  // the previous round's q_hat has been read by every wavefront
     if (row) qhat_s[g * R + lane] = q_hat;
     __syncthreads();
-    // k_hat = (k B_K^T + lambda_d1 sum_g (q_g.k) q_hat_g)(B_K B_K^T + lambda_d1 sum_g q_hat_g^T q_hat_g)^-1
+    // k_hat = (k B_K^T + lambda_d1 sum_g (q_g.k) q_hat_g)
+    //         (B_K B_K^T + lambda_d1 sum_g q_hat_g^T q_hat_g)^-1
     float rhs = nb;
 #pragma unroll
     for (int c4 = 0; c4 < R / 4; ++c4) {
@@ -589,6 +590,12 @@ hipError_t launch_update_r(const lrqk_shape& s, const GramArgs& ga, const SolveA
   return hipGetLastError();
 }
 
+template <int R>
+hipError_t launch_update_dtype(bool bf16, const lrqk_shape& s, const GramArgs& ga,
+                               const SolveArgs& sa, hipStream_t st) {
+  return bf16 ? launch_update_r<R, true>(s, ga, sa, st) : launch_update_r<R, false>(s, ga, sa, st);
+}
+
 }  // namespace
 
 bool factor_update_supported(const lrqk_shape& s) {
@@ -633,10 +640,10 @@ hipError_t launch_factor_update(const lrqk_shape& s, const float* A_K, const voi
   sa.lam1 = lam1; sa.lam2 = lam2;
   const bool bf16 = s.kv_dtype == LRQK_KV_BF16;
   switch (s.r) {
-    case 8: return bf16 ? launch_update_r<8, true>(s, ga, sa, st) : launch_update_r<8, false>(s, ga, sa, st);
-    case 16: return bf16 ? launch_update_r<16, true>(s, ga, sa, st) : launch_update_r<16, false>(s, ga, sa, st);
-    case 32: return bf16 ? launch_update_r<32, true>(s, ga, sa, st) : launch_update_r<32, false>(s, ga, sa, st);
-    case 64: return bf16 ? launch_update_r<64, true>(s, ga, sa, st) : launch_update_r<64, false>(s, ga, sa, st);
+    case 8: return launch_update_dtype<8>(bf16, s, ga, sa, st);
+    case 16: return launch_update_dtype<16>(bf16, s, ga, sa, st);
+    case 32: return launch_update_dtype<32>(bf16, s, ga, sa, st);
+    case 64: return launch_update_dtype<64>(bf16, s, ga, sa, st);
     default: return hipErrorInvalidValue;
   }
 }

@@ -74,11 +74,13 @@ hipError_t launch_fetch_direct(const lrqk_shape& s, const void* K_host, const vo
   if (s.kv_dtype == LRQK_KV_BF16)
     hipLaunchKernelGGL((fetch_direct_kernel<16>), grid, dim3(kFetchThreads), 0, st,
                        (const uint4*)K_host, (const uint4*)V_host, miss_tok, miss_slot, n_miss,
-                       (uint4*)cacheK, (uint4*)cacheV, s.Hq, s.Hkv, s.l, row_cap(s), s.C, s.k, rows_per_block);
+                       (uint4*)cacheK, (uint4*)cacheV, s.Hq, s.Hkv, s.l, row_cap(s), s.C, s.k,
+                       rows_per_block);
   else
     hipLaunchKernelGGL((fetch_direct_kernel<32>), grid, dim3(kFetchThreads), 0, st,
                        (const uint4*)K_host, (const uint4*)V_host, miss_tok, miss_slot, n_miss,
-                       (uint4*)cacheK, (uint4*)cacheV, s.Hq, s.Hkv, s.l, row_cap(s), s.C, s.k, rows_per_block);
+                       (uint4*)cacheK, (uint4*)cacheV, s.Hq, s.Hkv, s.l, row_cap(s), s.C, s.k,
+                       rows_per_block);
   return hipGetLastError();
 }
 

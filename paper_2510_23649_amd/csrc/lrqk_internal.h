@@ -90,8 +90,8 @@ hipError_t launch_select_only(const lrqk_shape& s, const float* scores, int32_t*
 // kernel works from the materialised `scores` and A_K / q_hat are ignored.
 hipError_t launch_select_resolve(const lrqk_shape& s, float* scores,
                                  const unsigned long long* ext_bitmap, const float* cand_scores,
-                                 const float* A_K,
-                                 const float* q_hat, int32_t* sel_idx, int32_t step, int32_t* slot_of, int32_t* token_of,
+                                 const float* A_K, const float* q_hat, int32_t* sel_idx,
+                                 int32_t step, int32_t* slot_of, int32_t* token_of,
                                  int32_t* last_used, int32_t* sel_slot, uint8_t* hit,
                                  int32_t* miss_tok, int32_t* miss_slot, int32_t* n_miss,
                                  hipStream_t st);

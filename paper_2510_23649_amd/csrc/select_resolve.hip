@@ -6,22 +6,28 @@
 // any traffic between workgroups.  Selection works on an order-preserving 32-bit
 // key of the score (larger score <=> larger key; equal scores: lower position first).
 //
-//  Selection, usual route (two reads of the head's scores, no sorting):
-//   1. a histogram of the top 12 key bits over a 1-in-8 sample of the positions
-//      (all positions when the head is small) gives a bin b_lo at or below the bin
-//      of the k-th largest score, with a safety margin;
-//   2. one pass over all scores marks every position whose bin is >= b_lo in an LDS
-//      bitmap (4 positions per lane, 8 lanes OR-ed into one word: no atomics);
-//   3. a prefix count over the bitmap turns it into an ascending list of m candidate
+//  Selection, usual route (no sorting, the l scores of the head are never read here):
+//   1. a candidate bitmap of the positions whose key is at or above an estimated threshold.
+//      In the fused step it comes from the proxy-score pass (one 64-bit ballot per 64
+//      positions, with the candidates' scores packed 8 per 64-position group beside it)
+//      and is copied into LDS.  Working from a materialised score array (the stand-alone
+//      entry point) the kernel builds it itself: a histogram of the top 12 key bits over a
+//      1-in-8 sample of the positions gives a bin at or below the bin of the k-th largest
+//      score, with a safety margin, and one pass over the scores marks every position at
+//      or above that bin (4 positions per lane, 8 lanes OR-ed into one word: no atomics);
+//   2. a prefix count over the bitmap turns it into an ascending list of m candidate
 //      positions; if k <= m <= capacity the estimate was good (this is checked, not
-//      assumed), the candidates' keys are read back and an exact 3-level radix
-//      select in LDS finds the key of the k-th largest; candidates above it, and the
-//      first ones equal to it in position order, are the selection — already in
-//      ascending position.
-//  Selection, safe route (taken by a head whose check in step 3 fails: a bad sample
-//  or massive ties): full histogram, two 10-bit refinements of the threshold over the
-//  scores, one pass that sets the bitmap (positions with the threshold key counted
-//  in position order), then the same prefix count.  Slower, same result.
+//      assumed).  The candidates' keys are taken from the packed scores (a group with more
+//      than 8 candidates recomputes the others from A_K and q_hat with the same fma chain)
+//      or read back from the score array, and an exact 3-level radix select in LDS finds
+//      the key of the k-th largest; candidates above it, and the first ones equal to it
+//      in position order, are the selection -- already in ascending position.
+//  Selection, safe route (taken by a head whose check in step 2 fails: a bad estimate or
+//  massive ties): the head's scores are needed in full -- in the fused step they are first
+//  recomputed from A_K into the workspace -- then a full histogram, two 10-bit refinements
+//  of the threshold over the scores, one pass that sets the bitmap (positions with the
+//  threshold key counted in position order), and the same prefix count.  Slower, same
+//  result.
 //
 //  Resolution: each selected position looks up slot_of (hit: refresh; miss: ranked in
 //  position order).  Victims are the least recently selected slots: a histogram of
@@ -670,17 +676,16 @@ hipError_t launch_select_only(const lrqk_shape& s, const float* scores, int32_t*
   hipError_t e = raise_lds_limit<false>();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((select_resolve_kernel<false>), dim3(s.B * s.Hq), dim3(kT), lds, st, scores,
-                     nullptr, 0, nullptr, nullptr, nullptr, nullptr, s.r, s.Hq, s.Hkv, s.l, row_cap(s), n, s.k,
-                     sel_idx,
-                     0, s.C, nullptr, nullptr, nullptr, nullptr, nullptr,
-                     nullptr, nullptr, nullptr);
+                     nullptr, 0, nullptr, nullptr, nullptr, nullptr, s.r, s.Hq, s.Hkv, s.l,
+                     row_cap(s), n, s.k, sel_idx, 0, s.C, nullptr, nullptr, nullptr, nullptr,
+                     nullptr, nullptr, nullptr, nullptr);
   return hipGetLastError();
 }
 
 hipError_t launch_select_resolve(const lrqk_shape& s, float* scores,
                                  const unsigned long long* ext_bitmap, const float* cand_scores,
-                                 const float* A_K,
-                                 const float* q_hat, int32_t* sel_idx, int32_t step, int32_t* slot_of, int32_t* token_of,
+                                 const float* A_K, const float* q_hat, int32_t* sel_idx,
+                                 int32_t step, int32_t* slot_of, int32_t* token_of,
                                  int32_t* last_used, int32_t* sel_slot, uint8_t* hit,
                                  int32_t* miss_tok, int32_t* miss_slot, int32_t* n_miss,
                                  hipStream_t st) {
@@ -690,9 +695,9 @@ hipError_t launch_select_resolve(const lrqk_shape& s, float* scores,
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((select_resolve_kernel<true>), dim3(s.B * s.Hq), dim3(kT), lds, st, scores,
                      reinterpret_cast<const uint32_t*>(ext_bitmap), 2 * filter_words64(n),
-                     cand_scores, ext_bitmap ? A_K : nullptr, q_hat, scores, s.r, s.Hq, s.Hkv, s.l, row_cap(s), n, s.k,
-                     sel_idx, step, s.C, slot_of, token_of, last_used, sel_slot, hit,
-                     miss_tok, miss_slot, n_miss);
+                     cand_scores, ext_bitmap ? A_K : nullptr, q_hat, scores, s.r, s.Hq, s.Hkv, s.l,
+                     row_cap(s), n, s.k, sel_idx, step, s.C, slot_of, token_of, last_used,
+                     sel_slot, hit, miss_tok, miss_slot, n_miss);
   return hipGetLastError();
 }
 
