@@ -6,4 +6,5 @@ selection, cache, attention) and is imported by the tests and the benchmark to
 feed the same bits to the CPU oracle and to the HIP library.
 """
 from .configs import CONFIGS, WorkloadConfig, get_config  # noqa: F401
-from .workload import LayerData, QueryStream, make_layer, bf16_bits, as_numpy  # noqa: F401
+from .workload import (LayerData, QueryStream, make_layer, make_prefill_inputs,  # noqa: F401
+                       bf16_bits, as_numpy)

@@ -184,3 +184,24 @@ class QueryStream:
         q_hat = torch.einsum("bhd,bhrd->bhr", q.double(), Bq).to(torch.float32).contiguous()
         self.t += 1
         return q, q_hat
+
+
+def make_prefill_inputs(cfg: WorkloadConfig, data: LayerData, device=None):
+    """Inputs of the prefill factorisation for one layer: the prompt's queries Q [B,Hq,l,d] in
+    the K/V dtype (close to rank r like the keys: Q = Z C + noise with Z ~ N(0,1), C ~ N(0,1/r))
+    and the N(0,1) draws A_Q0 [B,Hq,l,r], A_K0 [B,Hkv,l,r] that Alg. 1 starts from.  The keys
+    are the layer's K.  Nothing of the method is computed here."""
+    dev = torch.device(device) if device is not None else data.A_K.device
+    B, Hq, Hkv, l, r, d = cfg.B, cfg.Hq, cfg.Hkv, cfg.l, cfg.r, cfg.d
+    g = _gen(dev, cfg.seed, data.layer, 8)
+    Q = torch.empty(B, Hq, l, d, device=dev, dtype=data.K.dtype)
+    for b in range(B):
+        for h in range(Hq):
+            Z = torch.randn(l, r, generator=g, device=dev, dtype=torch.float32)
+            Cm = torch.randn(r, d, generator=g, device=dev, dtype=torch.float32) / math.sqrt(r)
+            full = Z @ Cm + cfg.noise * torch.randn(l, d, generator=g, device=dev,
+                                                    dtype=torch.float32)
+            Q[b, h] = full.to(data.K.dtype)
+    A_Q0 = torch.randn(B, Hq, l, r, generator=g, device=dev, dtype=torch.float32)
+    A_K0 = torch.randn(B, Hkv, l, r, generator=g, device=dev, dtype=torch.float32)
+    return Q, A_Q0, A_K0

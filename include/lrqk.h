@@ -96,7 +96,7 @@ typedef struct lrqk_shape {
 } lrqk_shape;
 
 /* Which call a workspace is sized for (lrqk_workspace_bytes). */
-enum { LRQK_WS_SELECT = 1, LRQK_WS_ATTEND = 2, LRQK_WS_UPDATE = 3 };
+enum { LRQK_WS_SELECT = 1, LRQK_WS_ATTEND = 2, LRQK_WS_UPDATE = 3, LRQK_WS_PREFILL = 4 };
 
 int lrqk_version(void);
 const char* lrqk_status_string(int status);
@@ -326,6 +326,36 @@ int lrqk_factor_update(const lrqk_shape* shape, const lrqk_layer* layer,
  */
 int lrqk_append_token(const lrqk_shape* shape, const lrqk_layer* layer, const float* k_hat,
                       const void* k_new, const void* v_new, void* stream);
+
+/*
+ * p1 — prefill factorisation (Alg. 1; Sec. 4.1 "Prefill": Q K^T ~ A_Q A_K^T with Q ~ A_Q B_Q,
+ * K ~ A_K B_K, solved by alternating closed-form updates; App. A.1).  Produces the A_K that
+ * the decode step scans and the B_Q, B_K that lrqk_factor_update continues from.
+ * Starting from the A_Q, A_K handed in (the paper draws them from N(0,1); the caller draws),
+ * n_iter rounds of
+ *   B_Q <- (A_Q^T A_Q)^-1 A_Q^T Q                                  per query head
+ *   B_K <- (A_K^T A_K)^-1 A_K^T K                                  per KV head
+ *   A_K <- K (sum_g Q_g^T A_Q,g + lambda_pK B_K^T)
+ *            (sum_g A_Q,g^T A_Q,g + lambda_pK B_K B_K^T)^-1        per KV head, sums over the
+ *                                                                  G query heads of its group
+ *   A_Q <- Q (K^T A_K + lambda_pQ B_Q^T)(A_K^T A_K + lambda_pQ B_Q B_Q^T)^-1   per query head
+ * in this order (G = 1 gives the paper's rules).  B_Q, B_K are those computed at the top of
+ * the last round.  Exactly n_iter rounds (the paper uses at most 2); no convergence test.
+ * fp32 arithmetic on the matrix cores (App. B.1).  Supported ranks: r in {8, 16, 32, 64}.
+ * Of `shape`, B, Hq, Hkv, d, l, r, kv_dtype and l_cap are used.
+ *   Q     device kv_dtype [B,Hq,l,d]     read
+ *   K     device kv_dtype [B,Hkv,l,d]    read
+ *   A_Q   device fp32 [B,Hq,l,r]         in: initial values, out: result
+ *   A_K   device fp32 [B,Hkv,l_cap,r]    in: initial values, out: result (rows >= l untouched)
+ *   B_Q   device fp32 [B,Hq,r,d]         written
+ *   B_K   device fp32 [B,Hkv,r,d]        written
+ *   lambda_pQ, lambda_pK  >= 0, finite;  1 <= n_iter <= 64
+ *   workspace  device, >= lrqk_workspace_bytes(shape, LRQK_WS_PREFILL), 256-byte aligned
+ * A_Q^T A_Q and A_K^T A_K must be positive definite (they are for generic inputs with l >= r).
+ */
+int lrqk_prefill_factorize(const lrqk_shape* shape, const void* Q, const void* K, float* A_Q,
+                           float* A_K, float* B_Q, float* B_K, float lambda_pQ, float lambda_pK,
+                           int32_t n_iter, void* workspace, size_t ws_bytes, void* stream);
 
 /*
  * Instrumentation (not part of the method): per-phase GPU time of lrqk_decode_step,

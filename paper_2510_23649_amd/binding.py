@@ -13,7 +13,7 @@ _lib = None
 
 LRQK_KV_BF16, LRQK_KV_F32 = 0, 1
 LRQK_FETCH_STAGED, LRQK_FETCH_DIRECT = 0, 1
-LRQK_WS_SELECT, LRQK_WS_ATTEND, LRQK_WS_UPDATE = 1, 2, 3
+LRQK_WS_SELECT, LRQK_WS_ATTEND, LRQK_WS_UPDATE, LRQK_WS_PREFILL = 1, 2, 3, 4
 
 
 class LrqkError(RuntimeError):
@@ -88,6 +88,8 @@ def load_library():
         "lrqk_factor_update": (C.c_int, [sp, C.POINTER(Layer), vp, vp, vp, vp, vp, vp, C.c_float,
                                          C.c_float, i32, vp, vp, vp, sz, vp]),
         "lrqk_append_token": (C.c_int, [sp, C.POINTER(Layer), vp, vp, vp, vp]),
+        "lrqk_prefill_factorize": (C.c_int, [sp, vp, vp, vp, vp, vp, vp, C.c_float, C.c_float,
+                                             i32, vp, sz, vp]),
         "lrqk_plan_create": (C.c_int, [sp, C.POINTER(vp)]),
         "lrqk_plan_destroy": (C.c_int, [vp]),
         "lrqk_fetch_misses": (C.c_int, [vp, sp, vp, vp, vp, vp, vp, vp, vp, C.c_int,
@@ -111,7 +113,8 @@ EXPORTS = ["lrqk_version", "lrqk_status_string", "lrqk_last_hip_error", "lrqk_va
            "lrqk_workspace_bytes", "lrqk_proxy_scores", "lrqk_select_topk", "lrqk_cache_init",
            "lrqk_cache_resolve", "lrqk_sparse_attend", "lrqk_plan_create", "lrqk_plan_destroy",
            "lrqk_fetch_misses", "lrqk_decode_step", "lrqk_plan_profile", "lrqk_plan_profile_read", "lrqk_calib_copy",
-           "lrqk_plan_time_proxy_pass", "lrqk_factor_update", "lrqk_append_token"]
+           "lrqk_plan_time_proxy_pass", "lrqk_factor_update", "lrqk_append_token",
+           "lrqk_prefill_factorize"]
 
 
 def _check(status: int, where: str):
@@ -211,6 +214,15 @@ def lrqk_factor_update(shape, layer, sel_idx_prev, sel_slot_prev, q, k_new, B_Q,
         _dev(B_Q, torch.float32), _dev(B_K, torch.float32), float(lambda_d1), float(lambda_d2),
         int(n_iter), _dev(q_hat, torch.float32), _dev(k_hat, torch.float32), _dev(workspace),
         workspace.numel() * workspace.element_size(), _stream(stream)), "lrqk_factor_update")
+
+
+def lrqk_prefill_factorize(shape, Q, K, A_Q, A_K, B_Q, B_K, lambda_pQ, lambda_pK, n_iter,
+                           workspace, stream=None):
+    _check(load_library().lrqk_prefill_factorize(
+        C.byref(shape), _dev(Q), _dev(K), _dev(A_Q, torch.float32), _dev(A_K, torch.float32),
+        _dev(B_Q, torch.float32), _dev(B_K, torch.float32), float(lambda_pQ), float(lambda_pK),
+        int(n_iter), _dev(workspace), workspace.numel() * workspace.element_size(),
+        _stream(stream)), "lrqk_prefill_factorize")
 
 
 def lrqk_append_token(shape, layer, k_hat, k_new, v_new, stream=None):

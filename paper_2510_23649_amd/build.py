@@ -19,7 +19,7 @@ OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "liblrqk.so")
 
 SOURCES = ["api.hip", "proxy_scores.hip", "select_topk.hip", "cache_resolve.hip", "select_resolve.hip",
-           "sparse_attend.hip", "fetch.hip", "factor_update.hip", "append_token.hip",
+           "sparse_attend.hip", "fetch.hip", "factor_update.hip", "append_token.hip", "prefill.hip",
            "instrument.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -185,6 +185,7 @@ size_t lrqk_workspace_bytes(const lrqk_shape* shape, int which) {
   if (which == LRQK_WS_SELECT) return carve_select_ws(nullptr, BHq, shape->k).bytes;
   if (which == LRQK_WS_ATTEND) return attend_ws_bytes(BHq, shape->k, shape->w, 1);
   if (which == LRQK_WS_UPDATE) return factor_update_supported(*shape) ? update_ws_bytes(*shape) : 0;
+  if (which == LRQK_WS_PREFILL) return prefill_supported(*shape) ? prefill_ws_bytes(*shape) : 0;
   return 0;
 }
 
@@ -297,6 +298,24 @@ int lrqk_append_token(const lrqk_shape* shape, const lrqk_layer* layer, const fl
   LRQK_HIP(launch_append_token(*shape, layer->A_K, layer->K_host, layer->V_host, layer->liteK,
                                layer->liteV, layer->slot_of, k_hat, k_new, v_new,
                                static_cast<hipStream_t>(stream)));
+  return LRQK_OK;
+}
+
+int lrqk_prefill_factorize(const lrqk_shape* shape, const void* Q, const void* K, float* A_Q,
+                           float* A_K, float* B_Q, float* B_K, float lambda_pQ, float lambda_pK,
+                           int32_t n_iter, void* workspace, size_t ws_bytes, void* stream) {
+  const int rc = check_shape(shape);
+  if (rc != LRQK_OK) return rc;
+  if (!prefill_supported(*shape)) return LRQK_ESHAPE;
+  if (n_iter < 1 || n_iter > 64) return LRQK_EINVAL;
+  if (!(lambda_pQ >= 0.0f) || !(lambda_pK >= 0.0f) || std::isinf(lambda_pQ) ||
+      std::isinf(lambda_pK))
+    return LRQK_EINVAL;
+  if (!all_aligned16({Q, K, A_Q, A_K, B_Q, B_K}) || !workspace || !aligned256(workspace))
+    return LRQK_EINVAL;
+  if (ws_bytes < prefill_ws_bytes(*shape)) return LRQK_ENOMEM;
+  LRQK_HIP(launch_prefill(*shape, Q, K, A_Q, A_K, B_Q, B_K, lambda_pQ, lambda_pK, n_iter,
+                          static_cast<float*>(workspace), static_cast<hipStream_t>(stream)));
   return LRQK_OK;
 }
 

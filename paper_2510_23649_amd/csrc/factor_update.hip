@@ -38,6 +38,7 @@
 // All arithmetic is fp32 (App. B.1 runs these updates in fp32).
 #include "lrqk_device.h"
 #include "lrqk_internal.h"
+#include "lrqk_linalg.h"
 
 #ifdef LRQK_KPROF
 __device__ unsigned long long g_kprof_fu[16];
@@ -56,6 +57,8 @@ extern "C" __attribute__((visibility("default"))) int lrqk_kprof_fu_read(unsigne
 
 namespace lrqk {
 namespace {
+
+using namespace linalg;
 
 constexpr int kGramThreads = 256;
 constexpr int kGramBatch = 144;  // rows staged in LDS at a time (a multiple of 16)
@@ -262,97 +265,6 @@ __global__ __launch_bounds__(kGramThreads) void factor_gram_kernel(GramArgs a) {
     for (int e = 0; e < EPT; ++e) out[e0 + e] = acc[e];
   }
   if (t < R) out[kEntries + t] = gacc;
-}
-
-// ------------------------------------------------------------------------------------------
-// r x r symmetric positive definite solve inside one wavefront.
-
-__device__ __forceinline__ float lane_value(float v, int lane) {
-  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
-}
-
-// Building blocks; lane i (< R) holds row i of the matrix in m[], element i of a vector in a
-// scalar.  All loops are fully unrolled, so every register index is a constant.
-//
-// Right-looking Cholesky factorisation M = L L^T, in place: afterwards m[j] of lane i >= j
-// holds L[i][j].  Returns, in lane j, 1 / L[j][j].  Two independent matrices are factorised
-// together so that their dependency chains interleave.
-template <int R>
-__device__ __forceinline__ void chol_factor2(float (&m0)[R], float (&m1)[R], float& dinv0,
-                                             float& dinv1, int lane) {
-  dinv0 = dinv1 = 0.0f;
-#pragma unroll
-  for (int j = 0; j < R; ++j) {
-    const float inv0 = __builtin_amdgcn_rsqf(lane_value(m0[j], j));
-    const float inv1 = __builtin_amdgcn_rsqf(lane_value(m1[j], j));
-    const float l0 = m0[j] * inv0, l1 = m1[j] * inv1;
-    m0[j] = l0;
-    m1[j] = l1;
-    if (lane == j) {
-      dinv0 = inv0;
-      dinv1 = inv1;
-    }
-#pragma unroll
-    for (int c = j + 1; c < R; ++c) {
-      m0[c] = __builtin_fmaf(-l0, lane_value(l0, c), m0[c]);
-      m1[c] = __builtin_fmaf(-l1, lane_value(l1, c), m1[c]);
-    }
-  }
-}
-template <int R>
-__device__ __forceinline__ float chol_factor(float (&m)[R], int lane) {
-  float dinv = 0.0f;
-#pragma unroll
-  for (int j = 0; j < R; ++j) {
-    const float inv = __builtin_amdgcn_rsqf(lane_value(m[j], j));
-    const float lij = m[j] * inv;
-    m[j] = lij;
-    if (lane == j) dinv = inv;
-#pragma unroll
-    for (int c = j + 1; c < R; ++c) m[c] = __builtin_fmaf(-lij, lane_value(lij, c), m[c]);
-  }
-  return dinv;
-}
-// L y = b with L[i][j] = L[j] of lane i
-template <int R>
-__device__ __forceinline__ float tri_forward(const float (&L)[R], float dinv, float b, int lane) {
-  float y = 0.0f;
-#pragma unroll
-  for (int j = 0; j < R; ++j) {
-    const float yj = lane_value(b * dinv, j);
-    if (lane == j) y = yj;
-    b = __builtin_fmaf(-L[j], yj, b);
-  }
-  return y;
-}
-// L^T x = y with the transposed factor: Lt[j] of lane i = L[j][i]
-template <int R>
-__device__ __forceinline__ float tri_backward(const float (&Lt)[R], float dinv, float y, int lane) {
-  float x = 0.0f;
-#pragma unroll
-  for (int j = R - 1; j >= 0; --j) {
-    const float xj = lane_value(y * dinv, j);
-    if (lane == j) x = xj;
-    y = __builtin_fmaf(-Lt[j], xj, y);
-  }
-  return x;
-}
-// out[c] of lane i = in[i] of lane c, through R * (R + 1) floats of LDS owned by the wavefront
-// (in and out may be the same array)
-template <int R>
-__device__ __forceinline__ void transpose_rows(const float (&in)[R], float (&out)[R], float* lt,
-                                               int lane) {
-  __builtin_amdgcn_wave_barrier();
-  if (lane < R) {
-#pragma unroll
-    for (int c = 0; c < R; ++c) lt[lane * (R + 1) + c] = in[c];
-  }
-  __builtin_amdgcn_wave_barrier();
-  if (lane < R) {
-#pragma unroll
-    for (int c = 0; c < R; ++c) out[c] = lt[c * (R + 1) + lane];
-  }
-  __builtin_amdgcn_wave_barrier();
 }
 
 struct SolveArgs {

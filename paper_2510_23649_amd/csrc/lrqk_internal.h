@@ -139,4 +139,11 @@ hipError_t launch_append_token(const lrqk_shape& s, float* A_K, void* K_host, vo
                                void* liteK, void* liteV, int32_t* slot_of, const float* k_hat,
                                const void* k_new, const void* v_new, hipStream_t st);
 
+// Prefill factorisation (prefill.hip): r in {8, 16, 32, 64}.
+bool prefill_supported(const lrqk_shape& s);
+size_t prefill_ws_bytes(const lrqk_shape& s);
+hipError_t launch_prefill(const lrqk_shape& s, const void* Q, const void* K, float* A_Q,
+                          float* A_K, float* B_Q, float* B_K, float lam_pQ, float lam_pK,
+                          int n_iter, float* ws, hipStream_t st);
+
 }  // namespace lrqk

@@ -1,0 +1,535 @@
+// p1 -- prefill factorisation (Alg. 1; Sec. 4.1 "Prefill": the four update rules; App. A.1).
+//
+// Every update of Alg. 1 is made of two kinds of products with one long dimension (l):
+//   "reduce"  X^T Y and X^T X   (r x d and r x r, sums over the l rows)   X = A_Q or A_K
+//   "apply"   X = Y M           (l x r, row by row)                      Y = Q or K, M d x r
+// and r x r solves in between.  Per row of Y (256 bytes in bf16) the products cost
+// 2 r (2 d + r) flops: about 50 flop per byte at r = 32, above what the chip's fp32 rate can
+// do per byte of HBM traffic.  This is the one dense contraction of the method, and it runs
+// on the matrix cores in fp32 (v_mfma_f32_32x32x2_f32; App. B.1 keeps these updates in fp32).
+//
+// prefill_pass_kernel<R, BF16, APPLY, REDUCE>: one workgroup (4 wavefronts) walks a chunk of
+// 2048 rows in tiles of 128.  The tile of Y is read with coalesced 16-byte loads (the next
+// tile's loads are issued before the current tile's MFMAs), converted to fp32 and kept in LDS
+// with an odd row stride, so that both operand shapes the MFMAs need (a column pair of 32
+// rows, a row pair of 32 columns) are conflict-free LDS reads.
+//   APPLY : wavefront w computes rows 32w..32w+31 of X = Y M (64 MFMAs per 32 x 32 block),
+//           writes them to HBM and into LDS;
+//   REDUCE: wavefront w accumulates the 32-column block w of X^T Y over the tile's 128 rows
+//           (64 MFMAs per block) and its quarter of the rows of X^T X; the accumulators stay
+//           in registers across the chunk and leave as one partial per chunk.
+// Fusing the two means Y is read once per update of A and X is never read back.
+// prefill_sum_kernel adds the chunk partials (fixed order); the two solve kernels do the
+// r x r work: a Cholesky factorisation inside one wavefront, then one thread per column of
+// the r x d right-hand side.
+#include "lrqk_device.h"
+#include "lrqk_internal.h"
+#include "lrqk_linalg.h"
+
+namespace lrqk {
+namespace {
+
+using namespace linalg;
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kPfThreads = 256;
+constexpr int kPfTile = 128;          // rows per tile: 32 per wavefront
+constexpr int kPfTilesPerChunk = 16;  // 2048 rows per workgroup
+constexpr int kLDY = kD + 1;          // LDS row stride of the Y tile (odd: conflict-free)
+
+__device__ __forceinline__ f32x16 mfma32(float a, float b, f32x16 c) {
+  // D(32x32) = A(32x2) B(2x32) + C; lane = i + 32 k supplies A[i][k] and B[k][i];
+  // register v of lane l holds D[8 (v / 4) + 4 (l / 32) + v % 4][l % 32]
+  return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ int mfma_row(int v, int lane) {
+  return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+}
+
+template <int R>
+struct PfShape {
+  static constexpr int RB = (R + 31) / 32;  // 32-wide blocks of the rank dimension
+  static constexpr int RP = 32 * RB;        // rank padded to the MFMA block
+  static constexpr int LDX = RP + 1;
+  static constexpr int P = R * (kD + R);    // floats of one partial: X^T Y then X^T X
+  static constexpr size_t lds_floats(bool apply) {
+    return (size_t)kPfTile * kLDY + (size_t)kPfTile * LDX + (apply ? (size_t)kD * RP : 0);
+  }
+};
+
+template <int R, bool BF16, bool APPLY, bool REDUCE>
+__global__ __launch_bounds__(kPfThreads) void prefill_pass_kernel(
+    const void* __restrict__ Y,   // [heads][l][d]
+    float* X,                     // [heads][xrows][R]  read (!APPLY) or written (APPLY)
+    const float* __restrict__ M,  // [heads][d][RP]     (APPLY)
+    float* __restrict__ part,     // [heads][nchunk][P] (REDUCE)
+    int l, int xrows, int nchunk) {
+  using S = PfShape<R>;
+  constexpr int RB = S::RB, RP = S::RP, LDX = S::LDX;
+  constexpr int ROW16 = kD * (BF16 ? 2 : 4) / 16;          // 16-byte pieces per row of Y
+  constexpr int NPRE = kPfTile * ROW16 / kPfThreads;       // pieces per thread and tile
+  extern __shared__ __align__(16) float pf_lds[];
+  float* const Ys = pf_lds;
+  float* const Xs = Ys + kPfTile * kLDY;
+  float* const Ms = Xs + kPfTile * LDX;
+
+  const int head = blockIdx.y, chunk = blockIdx.x;
+  const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+  const int mi = lane & 31, mk = lane >> 5;
+  const uint4* __restrict__ Yh =
+      reinterpret_cast<const uint4*>(static_cast<const char*>(Y) +
+                                     (size_t)head * (size_t)l * (kD * (BF16 ? 2 : 4)));
+  float* Xh = X + (size_t)head * (size_t)xrows * R;
+  const int row_begin = chunk * kPfTile * kPfTilesPerChunk;
+  const int row_end = min(l, row_begin + kPfTile * kPfTilesPerChunk);
+
+  // padding columns of X (rank up to the MFMA block) stay zero for the whole kernel
+  if (RP > R)
+    for (int i = t; i < kPfTile * (RP - R); i += kPfThreads)
+      Xs[(i / (RP - R)) * LDX + R + i % (RP - R)] = 0.0f;
+  if (APPLY) {
+    const float* Mh = M + (size_t)head * kD * RP;
+    for (int i = t; i < kD * RP; i += kPfThreads) Ms[i] = Mh[i];
+  }
+
+  f32x16 accXY[RB], accXX[RB * RB];
+#pragma unroll
+  for (int i = 0; i < RB; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) accXY[i][v] = 0.0f;
+#pragma unroll
+  for (int i = 0; i < RB * RB; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) accXX[i][v] = 0.0f;
+
+  uint4 pre[NPRE];
+  auto prefetch = [&](int row0) {
+#pragma unroll
+    for (int j = 0; j < NPRE; ++j) {
+      const int q = t + kPfThreads * j;
+      const int row = row0 + q / ROW16;
+      pre[j] = row < row_end ? Yh[(size_t)row * ROW16 + q % ROW16] : make_uint4(0u, 0u, 0u, 0u);
+    }
+  };
+  prefetch(row_begin);
+
+  for (int row0 = row_begin; row0 < row_end; row0 += kPfTile) {
+    __syncthreads();  // the previous tile's LDS reads are done
+#pragma unroll
+    for (int j = 0; j < NPRE; ++j) {
+      const int q = t + kPfThreads * j;
+      const int rr = q / ROW16, c = q % ROW16;
+      float* dst = Ys + rr * kLDY;
+      if (BF16) {
+        dst[8 * c + 0] = __uint_as_float(pre[j].x << 16);
+        dst[8 * c + 1] = __uint_as_float(pre[j].x & 0xffff0000u);
+        dst[8 * c + 2] = __uint_as_float(pre[j].y << 16);
+        dst[8 * c + 3] = __uint_as_float(pre[j].y & 0xffff0000u);
+        dst[8 * c + 4] = __uint_as_float(pre[j].z << 16);
+        dst[8 * c + 5] = __uint_as_float(pre[j].z & 0xffff0000u);
+        dst[8 * c + 6] = __uint_as_float(pre[j].w << 16);
+        dst[8 * c + 7] = __uint_as_float(pre[j].w & 0xffff0000u);
+      } else {
+        dst[4 * c + 0] = __uint_as_float(pre[j].x);
+        dst[4 * c + 1] = __uint_as_float(pre[j].y);
+        dst[4 * c + 2] = __uint_as_float(pre[j].z);
+        dst[4 * c + 3] = __uint_as_float(pre[j].w);
+      }
+    }
+    if (!APPLY) {
+      // X tile from HBM: 128 consecutive rows of R floats are one contiguous span
+      for (int i = t; i < kPfTile * R / 4; i += kPfThreads) {
+        const int rr = (4 * i) / R, cc = (4 * i) % R;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (row0 + rr < row_end)
+          v = reinterpret_cast<const float4*>(Xh + (size_t)row0 * R)[i];
+        Xs[rr * LDX + cc + 0] = v.x; Xs[rr * LDX + cc + 1] = v.y;
+        Xs[rr * LDX + cc + 2] = v.z; Xs[rr * LDX + cc + 3] = v.w;
+      }
+    }
+    if (row0 + kPfTile < row_end) prefetch(row0 + kPfTile);
+    __syncthreads();
+
+    if (APPLY) {
+      // rows 32w .. 32w+31 of X = Y M
+#pragma unroll
+      for (int rb = 0; rb < RB; ++rb) {
+        f32x16 acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
+#pragma unroll 8
+        for (int kk = 0; kk < kD; kk += 2) {
+          const float a = Ys[(32 * w + mi) * kLDY + kk + mk];
+          const float b = Ms[(kk + mk) * RP + 32 * rb + mi];
+          acc = mfma32(a, b, acc);
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int i = 32 * w + mfma_row(v, lane), j = 32 * rb + mi;
+          if (j < R) {
+            Xs[i * LDX + j] = acc[v];
+            if (row0 + i < row_end) Xh[(size_t)(row0 + i) * R + j] = acc[v];
+          }
+        }
+      }
+      if (REDUCE) __syncthreads();
+    }
+
+    if (REDUCE) {
+      // block w of the d columns of X^T Y, all 128 rows of the tile
+#pragma unroll 4
+      for (int kk = 0; kk < kPfTile; kk += 2) {
+        const float b = Ys[(kk + mk) * kLDY + 32 * w + mi];
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb)
+          accXY[rb] = mfma32(Xs[(kk + mk) * LDX + 32 * rb + mi], b, accXY[rb]);
+      }
+      // this wavefront's quarter of the rows of X^T X
+#pragma unroll 4
+      for (int kk = 32 * w; kk < 32 * w + 32; kk += 2) {
+        float a[RB];
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) a[rb] = Xs[(kk + mk) * LDX + 32 * rb + mi];
+#pragma unroll
+        for (int r1 = 0; r1 < RB; ++r1)
+#pragma unroll
+          for (int r2 = 0; r2 < RB; ++r2)
+            accXX[r1 * RB + r2] = mfma32(a[r1], a[r2], accXX[r1 * RB + r2]);
+      }
+    }
+  }
+
+  if (REDUCE) {
+    float* out = part + ((size_t)head * nchunk + chunk) * S::P;
+#pragma unroll
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int i = 32 * rb + mfma_row(v, lane);
+        if (i < R) out[(size_t)i * kD + 32 * w + mi] = accXY[rb][v];
+      }
+    // X^T X: add the four wavefronts' parts through LDS (the Y tile's space)
+    __syncthreads();
+    float* red = Ys;  // [4][RP * RP]  (4 * 64 * 64 floats at most = the Y tile's 128 * 129)
+#pragma unroll
+    for (int r1 = 0; r1 < RB; ++r1)
+#pragma unroll
+      for (int r2 = 0; r2 < RB; ++r2)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          red[w * RP * RP + (32 * r1 + mfma_row(v, lane)) * RP + 32 * r2 + mi] =
+              accXX[r1 * RB + r2][v];
+    __syncthreads();
+    for (int e = t; e < R * R; e += kPfThreads) {
+      const int i = e / R, c = e % R;
+      out[(size_t)R * kD + e] = (red[0 * RP * RP + i * RP + c] + red[1 * RP * RP + i * RP + c]) +
+                                (red[2 * RP * RP + i * RP + c] + red[3 * RP * RP + i * RP + c]);
+    }
+  }
+}
+
+// sum[head][e] = sum over chunks of part[head][chunk][e], chunks in order
+__global__ __launch_bounds__(256) void prefill_sum_kernel(const float* __restrict__ part,
+                                                          float* __restrict__ sum, int nchunk,
+                                                          int P) {
+  const int head = blockIdx.y;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= P) return;
+  const float* p = part + (size_t)head * nchunk * P + e;
+  float acc = 0.0f;
+  int c = 0;
+  for (; c + 8 <= nchunk; c += 8) {
+    float v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = p[(size_t)(c + j) * P];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc += v[j];
+  }
+  for (; c < nchunk; ++c) acc += p[(size_t)c * P];
+  sum[(size_t)head * P + e] = acc;
+}
+
+// ------------------------------------------------------------------------------------------
+// Solves S Xs = Ys in place for a symmetric positive definite S (r x r, LDS, row stride R + 1;
+// destroyed) and an r x d right-hand side (LDS, row stride kD + 1).  The first wavefront
+// factorises S (lane = row) and leaves L and 1 / diag(L) in LDS; then thread j < d owns
+// column j and runs the two triangular solves with the factor read as LDS broadcasts.
+// Called by all threads of a 256-thread workgroup.
+template <int R>
+__device__ void spd_solve_columns(float* Ssh, float* dinv_sh, float* Ysh) {
+  constexpr int LDS_ = R + 1;
+  const int t = threadIdx.x;
+  __syncthreads();
+  if (t < 64) {
+    float m[R];
+    const int li = t < R ? t : 0;
+#pragma unroll
+    for (int c = 0; c < R; ++c) m[c] = Ssh[li * LDS_ + c];
+    const float dinv = chol_factor<R>(m, t);
+    if (t < R) {
+#pragma unroll
+      for (int c = 0; c < R; ++c) Ssh[t * LDS_ + c] = m[c];  // L[t][c] for c <= t
+      dinv_sh[t] = dinv;
+    }
+  }
+  __syncthreads();
+  if (t < kD) {
+    // this thread's column stays in LDS (only this thread touches it): L z = y, then L^T x = z
+#pragma unroll 1
+    for (int i = 0; i < R; ++i) {
+      float acc = Ysh[i * kLDY + t];
+#pragma unroll 4
+      for (int c = 0; c < i; ++c) acc = __builtin_fmaf(-Ssh[i * LDS_ + c], Ysh[c * kLDY + t], acc);
+      Ysh[i * kLDY + t] = acc * dinv_sh[i];
+    }
+#pragma unroll 1
+    for (int i = R - 1; i >= 0; --i) {
+      float acc = Ysh[i * kLDY + t];
+#pragma unroll 4
+      for (int c = i + 1; c < R; ++c)
+        acc = __builtin_fmaf(-Ssh[c * LDS_ + i], Ysh[c * kLDY + t], acc);
+      Ysh[i * kLDY + t] = acc * dinv_sh[i];
+    }
+  }
+  __syncthreads();
+}
+
+// S1, one workgroup per (batch, KV head): from the sums (A^T Y | A^T A) of the group's query
+// heads and of the KV head:
+//   B_Q,g = (A_Q^T A_Q)^-1 A_Q^T Q for every query head g,  B_K = (A_K^T A_K)^-1 A_K^T K,
+//   M_K   = (sum_g Q_g^T A_Q,g + lambda_pK B_K^T)(sum_g A_Q,g^T A_Q,g + lambda_pK B_K B_K^T)^-1,
+// the d x r operand of the A_K update, written as [d][RP] (padding columns zero).
+template <int R>
+__global__ __launch_bounds__(256) void prefill_solve_b_kernel(
+    const float* __restrict__ sum_q, const float* __restrict__ sum_k, float* __restrict__ B_Q,
+    float* __restrict__ B_K, float* __restrict__ Mk, int Hq, int Hkv, float lam_pK) {
+  using S = PfShape<R>;
+  constexpr int LDS_ = R + 1, RP = S::RP;
+  extern __shared__ __align__(16) float pf_lds[];
+  float* const Ysh = pf_lds;               // [R][kLDY]
+  float* const Wsh = Ysh + R * kLDY;       // [R][kLDY]
+  float* const Ssh = Wsh + R * kLDY;       // [R][R + 1]
+  float* const Sacc = Ssh + R * LDS_;      // [R][R + 1]
+  float* const dinv_sh = Sacc + R * LDS_;  // [R]
+  const int bkv = blockIdx.x, t = threadIdx.x;
+  const int b = bkv / Hkv, kvh = bkv - b * Hkv, G = Hq / Hkv;
+  for (int e = t; e < R * kD; e += 256) Wsh[(e / kD) * kLDY + e % kD] = 0.0f;
+  for (int e = t; e < R * R; e += 256) Sacc[(e / R) * LDS_ + e % R] = 0.0f;
+  for (int g = 0; g <= G; ++g) {  // the G query heads, then the KV head
+    const bool iskv = g == G;
+    const size_t hq = (size_t)b * Hq + (size_t)kvh * G + g;
+    const float* sm = iskv ? sum_k + (size_t)bkv * S::P : sum_q + hq * S::P;
+    __syncthreads();
+    for (int e = t; e < R * kD; e += 256) {
+      const float v = sm[e];
+      Ysh[(e / kD) * kLDY + e % kD] = v;
+      if (!iskv) Wsh[(e / kD) * kLDY + e % kD] += v;
+    }
+    for (int e = t; e < R * R; e += 256) {
+      const float v = sm[R * kD + e];
+      Ssh[(e / R) * LDS_ + e % R] = v;
+      if (!iskv) Sacc[(e / R) * LDS_ + e % R] += v;
+    }
+    spd_solve_columns<R>(Ssh, dinv_sh, Ysh);
+    float* Bout = iskv ? B_K + (size_t)bkv * R * kD : B_Q + hq * R * kD;
+    for (int e = t; e < R * kD; e += 256) Bout[e] = Ysh[(e / kD) * kLDY + e % kD];
+  }
+  // Ysh holds B_K: W^T += lambda_pK B_K,  S += lambda_pK B_K B_K^T
+  for (int e = t; e < R * R; e += 256) {
+    const int i = e / R, c = e % R;
+    float acc = 0.0f;
+    for (int j = 0; j < kD; ++j) acc = __builtin_fmaf(Ysh[i * kLDY + j], Ysh[c * kLDY + j], acc);
+    Sacc[i * LDS_ + c] = __builtin_fmaf(lam_pK, acc, Sacc[i * LDS_ + c]);
+  }
+  for (int e = t; e < R * kD; e += 256) {
+    const int i = e / kD, j = e % kD;
+    Wsh[i * kLDY + j] = __builtin_fmaf(lam_pK, Ysh[i * kLDY + j], Wsh[i * kLDY + j]);
+  }
+  spd_solve_columns<R>(Sacc, dinv_sh, Wsh);  // M_K^T = S^-1 W^T
+  float* Mo = Mk + (size_t)bkv * kD * RP;
+  for (int e = t; e < kD * RP; e += 256) {
+    const int j = e / RP, i = e % RP;
+    Mo[e] = i < R ? Wsh[i * kLDY + j] : 0.0f;
+  }
+}
+
+// S2, one workgroup per (batch, query head): with the sums of the new A_K,
+//   M_Q = (K^T A_K + lambda_pQ B_Q^T)(A_K^T A_K + lambda_pQ B_Q B_Q^T)^-1,  written as [d][RP].
+template <int R>
+__global__ __launch_bounds__(256) void prefill_solve_q_kernel(const float* __restrict__ sum_k,
+                                                              const float* __restrict__ B_Q,
+                                                              float* __restrict__ Mq, int Hq,
+                                                              int Hkv, float lam_pQ) {
+  using S = PfShape<R>;
+  constexpr int LDS_ = R + 1, RP = S::RP;
+  extern __shared__ __align__(16) float pf_lds[];
+  float* const Ysh = pf_lds;              // [R][kLDY]
+  float* const Bsh = Ysh + R * kLDY;      // [R][kLDY]
+  float* const Ssh = Bsh + R * kLDY;      // [R][R + 1]
+  float* const dinv_sh = Ssh + R * LDS_;  // [R]
+  const int bh = blockIdx.x, t = threadIdx.x;
+  const int b = bh / Hq, h = bh - b * Hq, kvh = h / (Hq / Hkv);
+  const float* sm = sum_k + ((size_t)b * Hkv + kvh) * S::P;
+  const float* Bq = B_Q + (size_t)bh * R * kD;
+  for (int e = t; e < R * kD; e += 256) {
+    const float bq = Bq[e];
+    Bsh[(e / kD) * kLDY + e % kD] = bq;
+    Ysh[(e / kD) * kLDY + e % kD] = __builtin_fmaf(lam_pQ, bq, sm[e]);
+  }
+  __syncthreads();
+  for (int e = t; e < R * R; e += 256) {
+    const int i = e / R, c = e % R;
+    float acc = 0.0f;
+    for (int j = 0; j < kD; ++j) acc = __builtin_fmaf(Bsh[i * kLDY + j], Bsh[c * kLDY + j], acc);
+    Ssh[i * LDS_ + c] = __builtin_fmaf(lam_pQ, acc, sm[R * kD + e]);
+  }
+  spd_solve_columns<R>(Ssh, dinv_sh, Ysh);
+  float* Mo = Mq + (size_t)bh * kD * RP;
+  for (int e = t; e < kD * RP; e += 256) {
+    const int j = e / RP, i = e % RP;
+    Mo[e] = i < R ? Ysh[i * kLDY + j] : 0.0f;
+  }
+}
+
+// Kernels that use more than 64 KB of dynamic LDS have to opt in (once per kernel).
+template <typename K>
+hipError_t allow_lds(K kernel, size_t bytes) {
+  static bool done = false;  // one flag per kernel type
+  if (bytes <= 64 * 1024 || done) return hipSuccess;
+  const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  if (e == hipSuccess) done = true;
+  return e;
+}
+template <int R>
+constexpr size_t solve_lds_bytes() {
+  return ((size_t)2 * R * kLDY + (size_t)2 * R * (R + 1) + R) * sizeof(float);
+}
+
+template <int R, bool BF16, bool APPLY, bool REDUCE>
+hipError_t launch_pass(const void* Y, float* X, const float* M, float* part, int heads, int l,
+                       int xrows, int nchunk, hipStream_t st) {
+  const size_t lds = PfShape<R>::lds_floats(APPLY) * sizeof(float);
+  auto kernel = prefill_pass_kernel<R, BF16, APPLY, REDUCE>;
+  const hipError_t e = allow_lds(kernel, lds);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(kernel, dim3(nchunk, heads), dim3(kPfThreads), lds, st, Y, X, M, part, l,
+                     xrows, nchunk);
+  return hipGetLastError();
+}
+
+struct PrefillWs {
+  float *part_q, *part_k, *sum_q, *sum_k, *Mq, *Mk;
+  size_t floats;
+};
+template <int R>
+PrefillWs carve_prefill(float* base, const lrqk_shape& s) {
+  using S = PfShape<R>;
+  const size_t BHq = (size_t)s.B * s.Hq, BHkv = (size_t)s.B * s.Hkv;
+  const size_t nchunk = (size_t)ceil_div(s.l, kPfTile * kPfTilesPerChunk);
+  PrefillWs w;
+  size_t off = 0;
+  auto take = [&](size_t n) {
+    float* p = base ? base + off : nullptr;
+    off += (n + 63) / 64 * 64;
+    return p;
+  };
+  w.part_q = take(BHq * nchunk * S::P);
+  w.part_k = take(BHkv * nchunk * S::P);
+  w.sum_q = take(BHq * S::P);
+  w.sum_k = take(BHkv * S::P);
+  w.Mq = take(BHq * kD * S::RP);
+  w.Mk = take(BHkv * kD * S::RP);
+  w.floats = off;
+  return w;
+}
+
+template <int R, bool BF16>
+hipError_t run_prefill(const lrqk_shape& s, const void* Q, const void* K, float* A_Q, float* A_K,
+                       float* B_Q, float* B_K, float lam_pQ, float lam_pK, int n_iter, float* ws,
+                       hipStream_t st) {
+  using S = PfShape<R>;
+  const PrefillWs w = carve_prefill<R>(ws, s);
+  const int BHq = s.B * s.Hq, BHkv = s.B * s.Hkv, l = s.l, lk = row_cap(s);
+  const int nchunk = ceil_div(l, kPfTile * kPfTilesPerChunk);
+  const dim3 sum_grid_q(ceil_div(S::P, 256), BHq), sum_grid_k(ceil_div(S::P, 256), BHkv);
+  hipError_t e;
+#define PF_TRY(x)                  \
+  do {                             \
+    e = (x);                       \
+    if (e != hipSuccess) return e; \
+  } while (0)
+  // sums of the initial factors
+  PF_TRY((launch_pass<R, BF16, false, true>(Q, A_Q, nullptr, w.part_q, BHq, l, l, nchunk, st)));
+  PF_TRY((launch_pass<R, BF16, false, true>(K, A_K, nullptr, w.part_k, BHkv, l, lk, nchunk, st)));
+  hipLaunchKernelGGL(prefill_sum_kernel, sum_grid_q, dim3(256), 0, st, w.part_q, w.sum_q, nchunk,
+                     S::P);
+  hipLaunchKernelGGL(prefill_sum_kernel, sum_grid_k, dim3(256), 0, st, w.part_k, w.sum_k, nchunk,
+                     S::P);
+  for (int it = 0; it < n_iter; ++it) {
+    PF_TRY(allow_lds(prefill_solve_b_kernel<R>, solve_lds_bytes<R>()));
+    PF_TRY(allow_lds(prefill_solve_q_kernel<R>, solve_lds_bytes<R>()));
+    hipLaunchKernelGGL((prefill_solve_b_kernel<R>), dim3(BHkv), dim3(256), solve_lds_bytes<R>(),
+                       st, w.sum_q, w.sum_k, B_Q, B_K, w.Mk, s.Hq, s.Hkv, lam_pK);
+    PF_TRY((launch_pass<R, BF16, true, true>(K, A_K, w.Mk, w.part_k, BHkv, l, lk, nchunk, st)));
+    hipLaunchKernelGGL(prefill_sum_kernel, sum_grid_k, dim3(256), 0, st, w.part_k, w.sum_k,
+                       nchunk, S::P);
+    hipLaunchKernelGGL((prefill_solve_q_kernel<R>), dim3(BHq), dim3(256), solve_lds_bytes<R>(),
+                       st, w.sum_k, B_Q, w.Mq, s.Hq, s.Hkv, lam_pQ);
+    if (it + 1 < n_iter) {
+      PF_TRY((launch_pass<R, BF16, true, true>(Q, A_Q, w.Mq, w.part_q, BHq, l, l, nchunk, st)));
+      hipLaunchKernelGGL(prefill_sum_kernel, sum_grid_q, dim3(256), 0, st, w.part_q, w.sum_q,
+                         nchunk, S::P);
+    } else {  // nothing reads the sums of the final A_Q
+      PF_TRY((launch_pass<R, BF16, true, false>(Q, A_Q, w.Mq, nullptr, BHq, l, l, nchunk, st)));
+    }
+  }
+#undef PF_TRY
+  return hipGetLastError();
+}
+
+template <int R>
+hipError_t run_prefill_dtype(const lrqk_shape& s, const void* Q, const void* K, float* A_Q,
+                             float* A_K, float* B_Q, float* B_K, float lam_pQ, float lam_pK,
+                             int n_iter, float* ws, hipStream_t st) {
+  return s.kv_dtype == LRQK_KV_BF16
+             ? run_prefill<R, true>(s, Q, K, A_Q, A_K, B_Q, B_K, lam_pQ, lam_pK, n_iter, ws, st)
+             : run_prefill<R, false>(s, Q, K, A_Q, A_K, B_Q, B_K, lam_pQ, lam_pK, n_iter, ws, st);
+}
+
+}  // namespace
+
+bool prefill_supported(const lrqk_shape& s) {
+  return s.r == 8 || s.r == 16 || s.r == 32 || s.r == 64;
+}
+
+size_t prefill_ws_bytes(const lrqk_shape& s) {
+  size_t f = 0;
+  switch (s.r) {
+    case 8: f = carve_prefill<8>(nullptr, s).floats; break;
+    case 16: f = carve_prefill<16>(nullptr, s).floats; break;
+    case 32: f = carve_prefill<32>(nullptr, s).floats; break;
+    case 64: f = carve_prefill<64>(nullptr, s).floats; break;
+    default: return 0;
+  }
+  return round_up(f * sizeof(float), 256);
+}
+
+hipError_t launch_prefill(const lrqk_shape& s, const void* Q, const void* K, float* A_Q,
+                          float* A_K, float* B_Q, float* B_K, float lam_pQ, float lam_pK,
+                          int n_iter, float* ws, hipStream_t st) {
+  switch (s.r) {
+    case 8:
+      return run_prefill_dtype<8>(s, Q, K, A_Q, A_K, B_Q, B_K, lam_pQ, lam_pK, n_iter, ws, st);
+    case 16:
+      return run_prefill_dtype<16>(s, Q, K, A_Q, A_K, B_Q, B_K, lam_pQ, lam_pK, n_iter, ws, st);
+    case 32:
+      return run_prefill_dtype<32>(s, Q, K, A_Q, A_K, B_Q, B_K, lam_pQ, lam_pK, n_iter, ws, st);
+    case 64:
+      return run_prefill_dtype<64>(s, Q, K, A_Q, A_K, B_Q, B_K, lam_pQ, lam_pK, n_iter, ws, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace lrqk
