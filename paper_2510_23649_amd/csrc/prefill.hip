@@ -19,7 +19,7 @@
 //           (64 MFMAs per block) and its quarter of the rows of X^T X; the accumulators stay
 //           in registers across the chunk and leave as one partial per chunk.
 // Fusing the two means Y is read once per update of A and X is never read back.
-// prefill_sum_kernel adds the chunk partials (fixed order); the two solve kernels do the
+// prefill_sum_kernel adds the chunk partials (fixed order); the three solve kernels do the
 // r x r work: a Cholesky factorisation inside one wavefront, then one thread per column of
 // the r x d right-hand side.
 #include "lrqk_device.h"
@@ -275,78 +275,100 @@ __device__ void spd_solve_columns(float* Ssh, float* dinv_sh, float* Ysh) {
   }
   __syncthreads();
   if (t < kD) {
-    // this thread's column stays in LDS (only this thread touches it): L z = y, then L^T x = z
+    // this thread's column stays in LDS (only this thread touches it): L z = y, then
+    // L^T x = z; four partial sums per row shorten the dependent chain of fmas
 #pragma unroll 1
     for (int i = 0; i < R; ++i) {
-      float acc = Ysh[i * kLDY + t];
-#pragma unroll 4
-      for (int c = 0; c < i; ++c) acc = __builtin_fmaf(-Ssh[i * LDS_ + c], Ysh[c * kLDY + t], acc);
-      Ysh[i * kLDY + t] = acc * dinv_sh[i];
+      float a0 = Ysh[i * kLDY + t], a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+      int c = 0;
+#pragma unroll 2
+      for (; c + 4 <= i; c += 4) {
+        a0 = __builtin_fmaf(-Ssh[i * LDS_ + c + 0], Ysh[(c + 0) * kLDY + t], a0);
+        a1 = __builtin_fmaf(-Ssh[i * LDS_ + c + 1], Ysh[(c + 1) * kLDY + t], a1);
+        a2 = __builtin_fmaf(-Ssh[i * LDS_ + c + 2], Ysh[(c + 2) * kLDY + t], a2);
+        a3 = __builtin_fmaf(-Ssh[i * LDS_ + c + 3], Ysh[(c + 3) * kLDY + t], a3);
+      }
+      for (; c < i; ++c) a0 = __builtin_fmaf(-Ssh[i * LDS_ + c], Ysh[c * kLDY + t], a0);
+      Ysh[i * kLDY + t] = ((a0 + a1) + (a2 + a3)) * dinv_sh[i];
     }
 #pragma unroll 1
     for (int i = R - 1; i >= 0; --i) {
-      float acc = Ysh[i * kLDY + t];
-#pragma unroll 4
-      for (int c = i + 1; c < R; ++c)
-        acc = __builtin_fmaf(-Ssh[c * LDS_ + i], Ysh[c * kLDY + t], acc);
-      Ysh[i * kLDY + t] = acc * dinv_sh[i];
+      float a0 = Ysh[i * kLDY + t], a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
+      int c = i + 1;
+#pragma unroll 2
+      for (; c + 4 <= R; c += 4) {
+        a0 = __builtin_fmaf(-Ssh[(c + 0) * LDS_ + i], Ysh[(c + 0) * kLDY + t], a0);
+        a1 = __builtin_fmaf(-Ssh[(c + 1) * LDS_ + i], Ysh[(c + 1) * kLDY + t], a1);
+        a2 = __builtin_fmaf(-Ssh[(c + 2) * LDS_ + i], Ysh[(c + 2) * kLDY + t], a2);
+        a3 = __builtin_fmaf(-Ssh[(c + 3) * LDS_ + i], Ysh[(c + 3) * kLDY + t], a3);
+      }
+      for (; c < R; ++c) a0 = __builtin_fmaf(-Ssh[c * LDS_ + i], Ysh[c * kLDY + t], a0);
+      Ysh[i * kLDY + t] = ((a0 + a1) + (a2 + a3)) * dinv_sh[i];
     }
   }
   __syncthreads();
 }
 
-// S1, one workgroup per (batch, KV head): from the sums (A^T Y | A^T A) of the group's query
-// heads and of the KV head:
-//   B_Q,g = (A_Q^T A_Q)^-1 A_Q^T Q for every query head g,  B_K = (A_K^T A_K)^-1 A_K^T K,
-//   M_K   = (sum_g Q_g^T A_Q,g + lambda_pK B_K^T)(sum_g A_Q,g^T A_Q,g + lambda_pK B_K B_K^T)^-1,
+// S1a, one workgroup per head (the B*Hq query heads, then the B*Hkv KV heads): from the sums
+// (A^T Y | A^T A) of the head,  B = (A^T A)^-1 A^T Y.
+template <int R>
+__global__ __launch_bounds__(256) void prefill_solve_b_kernel(const float* __restrict__ sum_q,
+                                                              const float* __restrict__ sum_k,
+                                                              float* __restrict__ B_Q,
+                                                              float* __restrict__ B_K, int BHq) {
+  using S = PfShape<R>;
+  constexpr int LDS_ = R + 1;
+  extern __shared__ __align__(16) float pf_lds[];
+  float* const Ysh = pf_lds;              // [R][kLDY]
+  float* const Ssh = Ysh + R * kLDY;      // [R][R + 1]
+  float* const dinv_sh = Ssh + R * LDS_;  // [R]
+  const int t = threadIdx.x;
+  const bool iskv = (int)blockIdx.x >= BHq;
+  const size_t head = iskv ? blockIdx.x - BHq : blockIdx.x;
+  const float* sm = (iskv ? sum_k : sum_q) + head * S::P;
+  for (int e = t; e < R * kD; e += 256) Ysh[(e / kD) * kLDY + e % kD] = sm[e];
+  for (int e = t; e < R * R; e += 256) Ssh[(e / R) * LDS_ + e % R] = sm[R * kD + e];
+  spd_solve_columns<R>(Ssh, dinv_sh, Ysh);
+  float* Bout = (iskv ? B_K : B_Q) + head * R * kD;
+  for (int e = t; e < R * kD; e += 256) Bout[e] = Ysh[(e / kD) * kLDY + e % kD];
+}
+
+// S1b, one workgroup per (batch, KV head):
+//   M_K = (sum_g Q_g^T A_Q,g + lambda_pK B_K^T)(sum_g A_Q,g^T A_Q,g + lambda_pK B_K B_K^T)^-1,
 // the d x r operand of the A_K update, written as [d][RP] (padding columns zero).
 template <int R>
-__global__ __launch_bounds__(256) void prefill_solve_b_kernel(
-    const float* __restrict__ sum_q, const float* __restrict__ sum_k, float* __restrict__ B_Q,
-    float* __restrict__ B_K, float* __restrict__ Mk, int Hq, int Hkv, float lam_pK) {
+__global__ __launch_bounds__(256) void prefill_solve_mk_kernel(const float* __restrict__ sum_q,
+                                                               const float* __restrict__ B_K,
+                                                               float* __restrict__ Mk, int Hq,
+                                                               int Hkv, float lam_pK) {
   using S = PfShape<R>;
   constexpr int LDS_ = R + 1, RP = S::RP;
   extern __shared__ __align__(16) float pf_lds[];
-  float* const Ysh = pf_lds;               // [R][kLDY]
-  float* const Wsh = Ysh + R * kLDY;       // [R][kLDY]
-  float* const Ssh = Wsh + R * kLDY;       // [R][R + 1]
-  float* const Sacc = Ssh + R * LDS_;      // [R][R + 1]
-  float* const dinv_sh = Sacc + R * LDS_;  // [R]
+  float* const Wsh = pf_lds;              // [R][kLDY]  W^T
+  float* const Bsh = Wsh + R * kLDY;      // [R][kLDY]  B_K
+  float* const Ssh = Bsh + R * kLDY;      // [R][R + 1]
+  float* const dinv_sh = Ssh + R * LDS_;  // [R]
   const int bkv = blockIdx.x, t = threadIdx.x;
   const int b = bkv / Hkv, kvh = bkv - b * Hkv, G = Hq / Hkv;
-  for (int e = t; e < R * kD; e += 256) Wsh[(e / kD) * kLDY + e % kD] = 0.0f;
-  for (int e = t; e < R * R; e += 256) Sacc[(e / R) * LDS_ + e % R] = 0.0f;
-  for (int g = 0; g <= G; ++g) {  // the G query heads, then the KV head
-    const bool iskv = g == G;
-    const size_t hq = (size_t)b * Hq + (size_t)kvh * G + g;
-    const float* sm = iskv ? sum_k + (size_t)bkv * S::P : sum_q + hq * S::P;
-    __syncthreads();
-    for (int e = t; e < R * kD; e += 256) {
-      const float v = sm[e];
-      Ysh[(e / kD) * kLDY + e % kD] = v;
-      if (!iskv) Wsh[(e / kD) * kLDY + e % kD] += v;
-    }
-    for (int e = t; e < R * R; e += 256) {
-      const float v = sm[R * kD + e];
-      Ssh[(e / R) * LDS_ + e % R] = v;
-      if (!iskv) Sacc[(e / R) * LDS_ + e % R] += v;
-    }
-    spd_solve_columns<R>(Ssh, dinv_sh, Ysh);
-    float* Bout = iskv ? B_K + (size_t)bkv * R * kD : B_Q + hq * R * kD;
-    for (int e = t; e < R * kD; e += 256) Bout[e] = Ysh[(e / kD) * kLDY + e % kD];
+  const float* sq = sum_q + ((size_t)b * Hq + (size_t)kvh * G) * S::P;  // the group's G heads
+  const float* Bk = B_K + (size_t)bkv * R * kD;
+  for (int e = t; e < R * kD; e += 256) {
+    const float bk = Bk[e];
+    float acc = lam_pK * bk;
+    for (int g = 0; g < G; ++g) acc += sq[(size_t)g * S::P + e];
+    Bsh[(e / kD) * kLDY + e % kD] = bk;
+    Wsh[(e / kD) * kLDY + e % kD] = acc;
   }
-  // Ysh holds B_K: W^T += lambda_pK B_K,  S += lambda_pK B_K B_K^T
+  __syncthreads();
   for (int e = t; e < R * R; e += 256) {
     const int i = e / R, c = e % R;
-    float acc = 0.0f;
-    for (int j = 0; j < kD; ++j) acc = __builtin_fmaf(Ysh[i * kLDY + j], Ysh[c * kLDY + j], acc);
-    Sacc[i * LDS_ + c] = __builtin_fmaf(lam_pK, acc, Sacc[i * LDS_ + c]);
+    float bb = 0.0f;
+    for (int j = 0; j < kD; ++j) bb = __builtin_fmaf(Bsh[i * kLDY + j], Bsh[c * kLDY + j], bb);
+    float acc = lam_pK * bb;
+    for (int g = 0; g < G; ++g) acc += sq[(size_t)g * S::P + R * kD + e];
+    Ssh[i * LDS_ + c] = acc;
   }
-  for (int e = t; e < R * kD; e += 256) {
-    const int i = e / kD, j = e % kD;
-    Wsh[i * kLDY + j] = __builtin_fmaf(lam_pK, Ysh[i * kLDY + j], Wsh[i * kLDY + j]);
-  }
-  spd_solve_columns<R>(Sacc, dinv_sh, Wsh);  // M_K^T = S^-1 W^T
+  spd_solve_columns<R>(Ssh, dinv_sh, Wsh);  // M_K^T = S^-1 W^T
   float* Mo = Mk + (size_t)bkv * kD * RP;
   for (int e = t; e < kD * RP; e += 256) {
     const int j = e / RP, i = e % RP;
@@ -469,9 +491,12 @@ hipError_t run_prefill(const lrqk_shape& s, const void* Q, const void* K, float*
                      S::P);
   for (int it = 0; it < n_iter; ++it) {
     PF_TRY(allow_lds(prefill_solve_b_kernel<R>, solve_lds_bytes<R>()));
+    PF_TRY(allow_lds(prefill_solve_mk_kernel<R>, solve_lds_bytes<R>()));
     PF_TRY(allow_lds(prefill_solve_q_kernel<R>, solve_lds_bytes<R>()));
-    hipLaunchKernelGGL((prefill_solve_b_kernel<R>), dim3(BHkv), dim3(256), solve_lds_bytes<R>(),
-                       st, w.sum_q, w.sum_k, B_Q, B_K, w.Mk, s.Hq, s.Hkv, lam_pK);
+    hipLaunchKernelGGL((prefill_solve_b_kernel<R>), dim3(BHq + BHkv), dim3(256),
+                       solve_lds_bytes<R>(), st, w.sum_q, w.sum_k, B_Q, B_K, BHq);
+    hipLaunchKernelGGL((prefill_solve_mk_kernel<R>), dim3(BHkv), dim3(256), solve_lds_bytes<R>(),
+                       st, w.sum_q, B_K, w.Mk, s.Hq, s.Hkv, lam_pK);
     PF_TRY((launch_pass<R, BF16, true, true>(K, A_K, w.Mk, w.part_k, BHkv, l, lk, nchunk, st)));
     hipLaunchKernelGGL(prefill_sum_kernel, sum_grid_k, dim3(256), 0, st, w.part_k, w.sum_k,
                        nchunk, S::P);
