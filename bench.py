@@ -53,6 +53,8 @@ def main():
                     help="skip the extra section that times the whole of Alg. 2 (factor update, "
                          "append, then the step)")
     ap.add_argument("--alg2-steps", type=int, default=64)
+    ap.add_argument("--no-prefill", action="store_true",
+                    help="skip the extra section that times the prefill factorisation (Alg. 1)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
@@ -240,6 +242,49 @@ def main():
         log(f"Alg. 2: update {alg2['factor_update_us']:.1f} us, append "
             f"{alg2['append_token_us']:.1f} us, step {alg2['decode_step_us']:.1f} us")
 
+    # ---------------------------------------------------------------- prefill factorisation
+    # (outside the headline metric) Alg. 1 for one layer of the same shape: Q, K near rank r,
+    # N(0,1) initial factors, lambda_pQ = lambda_pK = 1, 2 rounds
+    prefill = None
+    if not args.no_prefill and cfg.r in (8, 16, 32, 64):
+        from gen import make_prefill_inputs
+        pdata = make_layer(cfg, 0, device=dev)
+        Qp, A_Q0, A_K0 = make_prefill_inputs(cfg, pdata)
+        Kp = pdata.K
+        pdata.V = pdata.A_K = None
+        pshape = shape.with_l(cfg.l)
+        pshape.l_cap = 0
+        ws_p = torch.empty(L.lrqk_workspace_bytes(pshape, L.LRQK_WS_PREFILL), dtype=torch.uint8,
+                           device=dev)
+        B_Qp = torch.empty((cfg.B, cfg.Hq, cfg.r, cfg.d), device=dev)
+        B_Kp = torch.empty((cfg.B, cfg.Hkv, cfg.r, cfg.d), device=dev)
+        times = []
+        for rep in range(4):
+            A_Qp, A_Kp = A_Q0.clone(), A_K0.clone()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            L.lrqk_prefill_factorize(pshape, Qp, Kp, A_Qp, A_Kp, B_Qp, B_Kp, 1.0, 1.0, 2, ws_p)
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1))
+        ms = float(np.median(times[1:]))
+        rows_q, rows_k, r_, d_ = cfg.B * cfg.Hq * cfg.l, cfg.B * cfg.Hkv * cfg.l, cfg.r, cfg.d
+        # initial sums on both sides; per round: fused apply + sums on K, then on Q (the last
+        # round's Q pass only applies)
+        flops = (2 * r_ * (d_ + r_) * (rows_q + rows_k)
+                 + 2 * 2 * r_ * (2 * d_ + r_) * rows_k
+                 + 2 * r_ * (2 * d_ + r_) * rows_q + 2 * r_ * d_ * rows_q)
+        prefill = {"ms_per_layer": ms, "rounds": 2, "lambda_pQ": 1.0, "lambda_pK": 1.0,
+                   "algorithmic_flops": flops, "achieved_TFLOPs": flops / (ms * 1e-3) / 1e12,
+                   "peak_TFLOPs_fp32_mfma": 157.3,
+                   "frac": flops / (ms * 1e-3) / 1e12 / 157.3,
+                   "note": "HIP-event time of one lrqk_prefill_factorize call (all its launches, "
+                           "r x r solves included) on one layer of the same shape"}
+        log(f"prefill factorisation: {ms:.3f} ms per layer, "
+            f"{prefill['achieved_TFLOPs']:.1f} TFLOP/s")
+        del Qp, A_Q0, A_K0, Kp, ws_p, pdata
+
     # ---------------------------------------------------------------- CPU oracle baseline
     cpu = None
     if oracle_layer is not None:
@@ -281,6 +326,7 @@ def main():
         "cpu_baseline": cpu,
         "phases_us": phases_us,
         "alg2": alg2,
+        "prefill": prefill,
         "step_roofline": {"algorithmic_bytes_per_step": step_bytes,
                           "gpu_us_per_step_sum_of_phases": gpu_us,
                           "achieved_GBs_end_to_end": step_bytes / (ms_per_step * 1e-3) / 1e9,

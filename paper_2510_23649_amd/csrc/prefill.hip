@@ -10,9 +10,11 @@
 //
 // prefill_pass_kernel<R, BF16, APPLY, REDUCE>: one workgroup (4 wavefronts) walks a chunk of
 // 2048 rows in tiles of 128.  The tile of Y is read with coalesced 16-byte loads (the next
-// tile's loads are issued before the current tile's MFMAs), converted to fp32 and kept in LDS
-// with an odd row stride, so that both operand shapes the MFMAs need (a column pair of 32
-// rows, a row pair of 32 columns) are conflict-free LDS reads.
+// tile's loads are issued before the current tile's MFMAs) and kept in LDS as it is (bf16 pairs
+// are widened when an operand is read) with an odd row stride in dwords, so that both operand
+// shapes the MFMAs need (a column pair of 32 rows, a row pair of 32 columns) are conflict-free
+// LDS reads; with bf16 inputs a workgroup needs 66 KB of LDS at r = 32 and two of them share
+// a CU, one running MFMAs while the other moves its tile.
 //   APPLY : wavefront w computes rows 32w..32w+31 of X = Y M (64 MFMAs per 32 x 32 block),
 //           writes them to HBM and into LDS;
 //   REDUCE: wavefront w accumulates the 32-column block w of X^T Y over the tile's 128 rows
@@ -53,8 +55,11 @@ struct PfShape {
   static constexpr int RP = 32 * RB;        // rank padded to the MFMA block
   static constexpr int LDX = RP + 1;
   static constexpr int P = R * (kD + R);    // floats of one partial: X^T Y then X^T X
-  static constexpr size_t lds_floats(bool apply) {
-    return (size_t)kPfTile * kLDY + (size_t)kPfTile * LDX + (apply ? (size_t)kD * RP : 0);
+  // dwords per LDS row of the Y tile: fp32 values, or bf16 pairs as they come from memory;
+  // odd in both cases, so that 32 consecutive rows fall on 32 different banks
+  static constexpr int ldy(bool bf16) { return bf16 ? kD / 2 + 1 : kD + 1; }
+  static constexpr size_t lds_floats(bool bf16, bool apply) {
+    return (size_t)kPfTile * ldy(bf16) + (size_t)kPfTile * LDX + (apply ? (size_t)kD * RP : 0);
   }
 };
 
@@ -70,9 +75,19 @@ __global__ __launch_bounds__(kPfThreads) void prefill_pass_kernel(
   constexpr int ROW16 = kD * (BF16 ? 2 : 4) / 16;          // 16-byte pieces per row of Y
   constexpr int NPRE = kPfTile * ROW16 / kPfThreads;       // pieces per thread and tile
   extern __shared__ __align__(16) float pf_lds[];
-  float* const Ys = pf_lds;
-  float* const Xs = Ys + kPfTile * kLDY;
+  constexpr int YW = S::ldy(BF16);
+  uint32_t* const Yw = reinterpret_cast<uint32_t*>(pf_lds);  // the Y tile, [kPfTile][YW] dwords
+  float* const Xs = pf_lds + kPfTile * YW;
   float* const Ms = Xs + kPfTile * LDX;
+  static_assert(kPfTile * (YW + LDX) >= 4 * RP * RP, "room for the final sum of X^T X");
+  // element (row, col) of the Y tile as fp32
+  auto y_at = [&](int row, int col) -> float {
+    if (BF16) {
+      const uint32_t wd = Yw[row * YW + (col >> 1)];
+      return __uint_as_float((col & 1) ? (wd & 0xffff0000u) : (wd << 16));
+    }
+    return __uint_as_float(Yw[row * YW + col]);
+  };
 
   const int head = blockIdx.y, chunk = blockIdx.x;
   const int t = threadIdx.x, lane = t & 63, w = t >> 6;
@@ -120,22 +135,11 @@ __global__ __launch_bounds__(kPfThreads) void prefill_pass_kernel(
     for (int j = 0; j < NPRE; ++j) {
       const int q = t + kPfThreads * j;
       const int rr = q / ROW16, c = q % ROW16;
-      float* dst = Ys + rr * kLDY;
-      if (BF16) {
-        dst[8 * c + 0] = __uint_as_float(pre[j].x << 16);
-        dst[8 * c + 1] = __uint_as_float(pre[j].x & 0xffff0000u);
-        dst[8 * c + 2] = __uint_as_float(pre[j].y << 16);
-        dst[8 * c + 3] = __uint_as_float(pre[j].y & 0xffff0000u);
-        dst[8 * c + 4] = __uint_as_float(pre[j].z << 16);
-        dst[8 * c + 5] = __uint_as_float(pre[j].z & 0xffff0000u);
-        dst[8 * c + 6] = __uint_as_float(pre[j].w << 16);
-        dst[8 * c + 7] = __uint_as_float(pre[j].w & 0xffff0000u);
-      } else {
-        dst[4 * c + 0] = __uint_as_float(pre[j].x);
-        dst[4 * c + 1] = __uint_as_float(pre[j].y);
-        dst[4 * c + 2] = __uint_as_float(pre[j].z);
-        dst[4 * c + 3] = __uint_as_float(pre[j].w);
-      }
+      uint32_t* dst = Yw + rr * YW + 4 * c;  // bf16: 8 values in 4 dwords; fp32: 4 values
+      dst[0] = pre[j].x;
+      dst[1] = pre[j].y;
+      dst[2] = pre[j].z;
+      dst[3] = pre[j].w;
     }
     if (!APPLY) {
       // X tile from HBM: 128 consecutive rows of R floats are one contiguous span
@@ -160,7 +164,7 @@ __global__ __launch_bounds__(kPfThreads) void prefill_pass_kernel(
         for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
 #pragma unroll 8
         for (int kk = 0; kk < kD; kk += 2) {
-          const float a = Ys[(32 * w + mi) * kLDY + kk + mk];
+          const float a = y_at(32 * w + mi, kk + mk);
           const float b = Ms[(kk + mk) * RP + 32 * rb + mi];
           acc = mfma32(a, b, acc);
         }
@@ -180,7 +184,7 @@ __global__ __launch_bounds__(kPfThreads) void prefill_pass_kernel(
       // block w of the d columns of X^T Y, all 128 rows of the tile
 #pragma unroll 4
       for (int kk = 0; kk < kPfTile; kk += 2) {
-        const float b = Ys[(kk + mk) * kLDY + 32 * w + mi];
+        const float b = y_at(kk + mk, 32 * w + mi);
 #pragma unroll
         for (int rb = 0; rb < RB; ++rb)
           accXY[rb] = mfma32(Xs[(kk + mk) * LDX + 32 * rb + mi], b, accXY[rb]);
@@ -211,7 +215,7 @@ __global__ __launch_bounds__(kPfThreads) void prefill_pass_kernel(
       }
     // X^T X: add the four wavefronts' parts through LDS (the Y tile's space)
     __syncthreads();
-    float* red = Ys;  // [4][RP * RP]  (4 * 64 * 64 floats at most = the Y tile's 128 * 129)
+    float* red = pf_lds;  // [4][RP * RP], over the tiles' space
 #pragma unroll
     for (int r1 = 0; r1 < RB; ++r1)
 #pragma unroll
@@ -432,7 +436,7 @@ constexpr size_t solve_lds_bytes() {
 template <int R, bool BF16, bool APPLY, bool REDUCE>
 hipError_t launch_pass(const void* Y, float* X, const float* M, float* part, int heads, int l,
                        int xrows, int nchunk, hipStream_t st) {
-  const size_t lds = PfShape<R>::lds_floats(APPLY) * sizeof(float);
+  const size_t lds = PfShape<R>::lds_floats(BF16, APPLY) * sizeof(float);
   auto kernel = prefill_pass_kernel<R, BF16, APPLY, REDUCE>;
   const hipError_t e = allow_lds(kernel, lds);
   if (e != hipSuccess) return e;
