@@ -1,0 +1,153 @@
+"""Hit/miss ablation and miss-rate grid on the synthetic workloads (needs a GPU).
+
+    python -m paper_2510_23649_amd.ablation [--grid] [--no-hit-miss] [--steps N] [--drift F]
+
+Two experiments of the paper, re-run on seeded synthetic inputs (its prompts and models are
+not available; the generator's query drift is what sets the level of the miss rate, so the
+numbers show how the mechanism responds to r, the number of active tokens and the number of
+lite tokens, not what a language model would produce):
+
+  --grid         Sec. 5.3: rank r in {8, 16, 32, 64} x active tokens in {128, 256, 512} x lite
+                 tokens in {4, 8}, cache of exactly k slots (the paper's cache), miss rate =
+                 fetched rows / selected rows per step; mean and standard deviation per cell,
+                 and a histogram over all cells and steps.
+  --no-hit-miss  App. C.2, "LRQK no hit/miss": the same decode steps with the cache emptied
+                 before every step, so that every selected row crosses the host link, against
+                 the default (only the missing rows do).
+
+Everything runs through the library's entry points; this module only generates inputs,
+launches and tabulates.
+"""
+from __future__ import annotations
+
+import argparse
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+from . import binding as L
+from .state import LayerBuffers
+
+# the seeded workload generators live beside the package, at the repository root
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+
+
+def _shape(cfg, **kw):
+    return L.Shape.make(B=cfg.B, Hq=cfg.Hq, Hkv=cfg.Hkv, l=cfg.l, r=cfg.r, k=cfg.k, w=cfg.w,
+                        C_slots=cfg.C, d=cfg.d, scale=cfg.scale, **kw)
+
+
+def miss_rate_grid(steps: int, warm: int, drift: float, out=sys.stdout):
+    from gen import get_config, make_layer, QueryStream
+    rates_all = []
+    print("| r | active k | lite w | mean miss rate | std | min | max |", file=out)
+    print("|---|---|---|---|---|---|---|", file=out)
+    for r in (8, 16, 32, 64):
+        for k in (128, 256, 512):
+            for w in (4, 8):
+                cfg = get_config("c2").with_(l=4096, r=r, k=k, w=w, C=k, n_heavy=k // 4,
+                                             pool_mult=4, drift=drift)
+                data = make_layer(cfg, 0, device="cuda")
+                shape = _shape(cfg)
+                lb = LayerBuffers(shape, data.A_K, data.K, data.V)
+                plan = L.Plan(shape)
+                qs = QueryStream(data)
+                out_t = torch.empty((cfg.B, cfg.Hq, cfg.d), device="cuda")
+                n_miss = torch.zeros((cfg.B, cfg.Hq), dtype=torch.int32, device="cuda")
+                rates = []
+                for step in range(1, warm + steps + 1):
+                    q, q_hat = qs.next()
+                    L.lrqk_decode_step(plan, shape, step, lb.struct, q_hat, q, out_t,
+                                       L.LRQK_FETCH_DIRECT, dict(n_miss=n_miss))
+                    if step > warm:
+                        rates.append(n_miss.clamp(min=0).sum().item() / (cfg.B * cfg.Hq * k))
+                plan.close()
+                rates = np.array(rates)
+                rates_all.append(rates)
+                print(f"| {r} | {k} | {w} | {rates.mean():.3f} | {rates.std():.3f} | "
+                      f"{rates.min():.3f} | {rates.max():.3f} |", file=out)
+    allr = np.concatenate(rates_all)
+    print(f"\nAll cells and steps: mean {allr.mean():.3f}, std {allr.std():.3f} "
+          f"({allr.size} step measurements).  Histogram (bin width 0.1):", file=out)
+    hist, edges = np.histogram(allr, bins=10, range=(0.0, 1.0))
+    for h, e in zip(hist, edges[:-1]):
+        print(f"    {e:.1f}-{e + 0.1:.1f}  {h:5d}  {'#' * int(round(60 * h / max(hist.max(), 1)))}",
+              file=out)
+
+
+def no_hit_miss(steps: int, layers: int, out=sys.stdout):
+    from gen import get_config, make_layer, QueryStream
+    cfg = get_config("c3").with_(layers=layers)
+    shape = _shape(cfg)
+    lbs, streams = [], []
+    for li in range(layers):
+        data = make_layer(cfg, li, device="cuda")
+        lbs.append(LayerBuffers(shape, data.A_K, data.K, data.V))
+        streams.append(QueryStream(data))
+    plan = L.Plan(shape)
+    out_t = torch.empty((cfg.B, cfg.Hq, cfg.d), device="cuda")
+    n_miss = torch.zeros((cfg.B, cfg.Hq), dtype=torch.int32, device="cuda")
+    step_no = [0] * layers
+    row_bytes = 2 * cfg.d * 2   # K and V row, bf16
+
+    def run(reset: bool, n: int, timed: bool):
+        qs = [streams[i % layers].next() for i in range(n)]
+        torch.cuda.synchronize()
+        fetched = 0
+        t0 = time.perf_counter()
+        for i in range(n):
+            li = i % layers
+            lb = lbs[li]
+            if reset:
+                L.lrqk_cache_init(shape, lb.slot_of, lb.token_of, lb.last_used)
+            step_no[li] += 1
+            L.lrqk_decode_step(plan, shape, step_no[li], lb.struct, qs[i][1], qs[i][0], out_t,
+                               L.LRQK_FETCH_DIRECT, None if timed else dict(n_miss=n_miss))
+            if not timed:
+                fetched += n_miss.clamp(min=0).sum().item()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n * 1e6, fetched / n
+
+    run(False, 2 * layers, True)                      # warm the caches
+    print("| variant | us per layer-step | rows fetched per step | MB over the host link per step |",
+          file=out)
+    print("|---|---|---|---|", file=out)
+    for name, reset in (("default (hit/miss cache)", False), ("no hit/miss (cache emptied before "
+                                                              "every step)", True)):
+        _, rows = run(reset, steps, False)
+        us, _ = run(reset, steps, True)
+        print(f"| {name} | {us:.1f} | {rows:.0f} | {rows * row_bytes / 1e6:.2f} |", file=out)
+        if reset:
+            run(False, 2 * layers, True)
+    plan.close()
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__.split("\n")[0])
+    ap.add_argument("--grid", action="store_true")
+    ap.add_argument("--no-hit-miss", action="store_true")
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warm", type=int, default=8)
+    ap.add_argument("--layers", type=int, default=8)
+    ap.add_argument("--drift", type=float, default=0.1,
+                    help="fraction of the heavy window the planted query direction moves per "
+                         "step in the grid (the generator's knob for the miss rate)")
+    args = ap.parse_args()
+    if not torch.cuda.is_available():
+        sys.exit("ablation: needs a GPU")
+    both = not (args.grid or args.no_hit_miss)
+    if args.grid or both:
+        print("## Miss-rate grid (Sec. 5.3), l = 4096, 32 q / 8 kv heads, cache of k slots, "
+              f"query drift {args.drift} of the heavy window per step\n")
+        miss_rate_grid(args.steps, args.warm, args.drift)
+    if args.no_hit_miss or both:
+        print("\n## Hit/miss ablation (App. C.2), workload 3 (l = 131072, r = 32, k = 2048), "
+              f"{args.layers} layers rotated\n")
+        no_hit_miss(args.steps, args.layers)
+
+
+if __name__ == "__main__":
+    main()
