@@ -89,6 +89,43 @@ def test_entry_points_reject_bad_arguments_before_any_device_work(lib):
     assert raw.lrqk_plan_create(C.byref(b), C.byref(C.c_void_p())) == -2
 
 
+def test_update_append_prefill_reject_bad_arguments_before_any_device_work(lib):
+    raw = lib.load_library()
+    A = 0x10000
+    s = good(lib)
+    lay = lib.Layer(*([A] * 10))
+    f32 = C.c_float
+    upd = raw.lrqk_factor_update
+    ok_tail = (f32(1.0), f32(1.0), 2, A, A, A, 1 << 30, None)
+    assert upd(C.byref(good(lib, r=12)), C.byref(lay), A, A, A, A, A, A, *ok_tail) == -2   # rank
+    assert upd(C.byref(s), None, A, A, A, A, A, A, *ok_tail) == -1                         # layer
+    assert upd(C.byref(s), C.byref(lay), A, A, A, A, A, A, f32(1.0), f32(1.0), 0, A, A, A,
+               1 << 30, None) == -1                                                        # rounds
+    assert upd(C.byref(s), C.byref(lay), A, A, A, A, A, A, f32(-1.0), f32(1.0), 2, A, A, A,
+               1 << 30, None) == -1                                                        # lambda
+    assert upd(C.byref(s), C.byref(lay), A, A, A, A + 4, A, A, *ok_tail) == -1             # alignment
+    assert upd(C.byref(s), C.byref(lay), A, A, A, A, A, A, f32(1.0), f32(1.0), 2, A, A, A, 64,
+               None) == -4                                                                 # workspace
+    assert lib.lrqk_workspace_bytes(s, lib.LRQK_WS_UPDATE) > 0
+    assert lib.lrqk_workspace_bytes(good(lib, r=12), lib.LRQK_WS_UPDATE) == 0
+    # append needs room for row l
+    app = raw.lrqk_append_token
+    assert app(C.byref(s), C.byref(lay), A, A, A, None) == -2                  # l_cap == l
+    assert app(C.byref(good(lib, l_cap=4000)), C.byref(lay), A, A, A, None) == -2   # l_cap < l
+    roomy = good(lib, l_cap=4100)
+    assert lib.lrqk_validate_shape(roomy) == 0
+    assert app(C.byref(roomy), None, A, A, A, None) == -1
+    assert app(C.byref(roomy), C.byref(lay), None, A, A, None) == -1
+    # prefill
+    pf = raw.lrqk_prefill_factorize
+    assert pf(C.byref(good(lib, r=24)), A, A, A, A, A, A, f32(1.0), f32(1.0), 2, A, 1 << 30, None) == -2
+    assert pf(C.byref(s), A, None, A, A, A, A, f32(1.0), f32(1.0), 2, A, 1 << 30, None) == -1
+    assert pf(C.byref(s), A, A, A, A, A, A, f32(1.0), f32(float("inf")), 2, A, 1 << 30, None) == -1
+    assert pf(C.byref(s), A, A, A, A, A, A, f32(1.0), f32(1.0), 65, A, 1 << 30, None) == -1
+    assert pf(C.byref(s), A, A, A, A, A, A, f32(1.0), f32(1.0), 2, A, 64, None) == -4
+    assert lib.lrqk_workspace_bytes(s, lib.LRQK_WS_PREFILL) > 0
+
+
 def test_product_never_touches_the_oracle():
     """The package, the header and the kernels must not import, include or name oracle/."""
     pkg = os.path.join(ROOT, "paper_2510_23649_amd")
