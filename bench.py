@@ -182,6 +182,7 @@ def main():
     step_bytes = (a_k_bytes + 2 * 2 * cfg.d * (cfg.B * cfg.Hq * cfg.k + cfg.B * cfg.Hkv * cfg.w)
                   + 2 * cfg.B * cfg.Hq * cfg.d * 4 + 2 * cfg.B * cfg.Hq * cfg.k * 4)
     gpu_us = sum(phases_us.values())
+    row_kv_bytes = 2 * cfg.d * (2 if cfg.kv_dtype == "bf16" else 4)   # one K row + one V row
 
     # ---------------------------------------------------------------- the whole of Alg. 2
     # (outside the headline metric) factor update -> append -> the step at length l + 1, on the
@@ -325,6 +326,14 @@ def main():
                      "algorithmic_bytes_per_launch": a_k_bytes},
         "cpu_baseline": cpu,
         "phases_us": phases_us,
+        "host_link": {"rows_per_step": miss_rate * cfg.B * cfg.Hq * cfg.k,
+                      "MB_per_step": miss_rate * cfg.B * cfg.Hq * cfg.k * row_kv_bytes / 1e6,
+                      "attend_phase_us": phases_us.get("attend"),
+                      "GBs_if_the_attend_phase_were_all_link_time":
+                          miss_rate * cfg.B * cfg.Hq * cfg.k * row_kv_bytes
+                          / max(phases_us.get("attend", 0.0), 1e-9) / 1e3,
+                      "note": "missing K and V rows cross the host link inside the attention "
+                              "kernel (direct mode); the step is bound by this leg"},
         "alg2": alg2,
         "prefill": prefill,
         "step_roofline": {"algorithmic_bytes_per_step": step_bytes,
