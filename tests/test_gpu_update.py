@@ -158,7 +158,19 @@ def grow(ost, n_new_cols=1):
 
 @pytest.mark.parametrize("mode", ["direct", "staged"])
 def test_alg2_steps_with_a_growing_context(mode):
-    """update -> append -> proxy scores / top-k / hit-miss / fetch / attention, for 40 new
+    say(f"Alg. 2 with 40 appended tokens ({mode})")
+    cfg = upd_cfg(B=1, Hq=4, Hkv=2, l=1500, r=16, k=128, w=24, C=256, n_heavy=16)
+    new_selected, new_fetched = run_alg2_growing(cfg, 40, mode)
+    assert new_selected > 0 and new_fetched > 0
+
+
+def test_alg2_steps_at_the_headline_shape():
+    say("Alg. 2 with 3 appended tokens at l = 131072, k = 2048, w = 64, r = 32, 32 / 8 heads")
+    run_alg2_growing(get_config("c3").with_(layers=1), 3, "direct")
+
+
+def run_alg2_growing(cfg, n_new, mode, lam1=1.0, lam2=1.0):
+    """update -> append -> proxy scores / top-k / hit-miss / fetch / attention, for n_new new
     tokens.  Each step is compared with the oracle on its own: the oracle's update starts from
     the factors the GPU holds, and its integer decisions use the GPU's q_hat and k_hat (the
     paper's fp32), so rounding differences of the fp32 algebra are measured, never amplified
@@ -166,9 +178,6 @@ def test_alg2_steps_with_a_growing_context(mode):
     from oracle import lrqk_oracle as orc
     from paper_2510_23649_amd.state import lite_ring
     from gpu_harness import compare_resolution
-    say(f"Alg. 2 with appended tokens ({mode})")
-    cfg = upd_cfg(B=1, Hq=4, Hkv=2, l=1500, r=16, k=128, w=24, C=256, n_heavy=16)
-    n_new, lam1, lam2 = 40, 1.0, 1.0
     l_cap = cfg.l + n_new
     data = make_layer(cfg)
     kvd = L.LRQK_KV_BF16
@@ -271,5 +280,5 @@ def test_alg2_steps_with_a_growing_context(mode):
             new_fetched += int((r2["miss_tok"].reshape(B * Hq, k)[bh, :nm] >= cfg.l).sum())
     say(f"   worst update error {worst:.2e}; appended tokens selected {new_selected} times, "
         f"fetched from the host store {new_fetched} times")
-    assert new_selected > 0 and new_fetched > 0
     plan.close()
+    return new_selected, new_fetched
