@@ -1,6 +1,7 @@
 """Hit/miss ablation and miss-rate grid on the synthetic workloads (needs a GPU).
 
-    python -m paper_2510_23649_amd.ablation [--grid] [--no-hit-miss] [--steps N] [--drift F]
+    python -m paper_2510_23649_amd.ablation [--grid] [--no-hit-miss] [--end-to-end]
+                                             [--steps N] [--drift F]
 
 Two experiments of the paper, re-run on seeded synthetic inputs (its prompts and models are
 not available; the generator's query drift is what sets the level of the miss rate, so the
@@ -14,6 +15,10 @@ lite tokens, not what a language model would produce):
   --no-hit-miss  App. C.2, "LRQK no hit/miss": the same decode steps with the cache emptied
                  before every step, so that every selected row crosses the host link, against
                  the default (only the missing rows do).
+  --end-to-end   the whole method in sequence: prefill factorisation of a synthetic prompt,
+                 then decode steps (factor update, append, proxy top-k, fetch, attention) on
+                 the factors it produced; reports the recall of the exact top-k and the
+                 distance of the output from dense attention.
 
 Everything runs through the library's entry points; this module only generates inputs,
 launches and tabulates.
@@ -125,10 +130,95 @@ def no_hit_miss(steps: int, layers: int, out=sys.stdout):
     plan.close()
 
 
+def end_to_end(steps: int, out=sys.stdout):
+    """Prefill factorisation, then Alg. 2 decode steps on the factors it produced; reports how
+    much of the exact top-k of q K^T the proxy selects and how far the sparse attention output
+    is from dense attention.  The exact scores and the dense attention are evaluation code
+    (torch), not part of the path."""
+    from gen import get_config, make_layer, QueryStream
+    cfg = get_config("c2").with_(B=1, Hq=8, Hkv=2, l=8192, r=32, k=512, w=16, C=1024,
+                                 n_heavy=128, pool_mult=4)
+    dev = "cuda"
+    data = make_layer(cfg, 0, device=dev)
+    G, l, k, w, r, d = cfg.G, cfg.l, cfg.k, cfg.w, cfg.r, cfg.d
+    # the prompt's queries: l draws of the same query process the decode steps continue
+    qs = QueryStream(data)
+    Q = torch.empty((cfg.B, cfg.Hq, l, d), device=dev, dtype=data.K.dtype)
+    for i in range(l):
+        Q[:, :, i, :] = qs.next()[0].to(data.K.dtype)
+    gen = torch.Generator(device=dev).manual_seed(1234)
+    n_new = steps
+    shape = _shape(cfg, l_cap=l + n_new)
+    A_Q = torch.randn((cfg.B, cfg.Hq, l, r), generator=gen, device=dev)
+    A_K0 = torch.randn((cfg.B, cfg.Hkv, l, r), generator=gen, device=dev)
+    lb = LayerBuffers(shape, A_K0, data.K, data.V)       # A_K is overwritten by the prefill
+    B_Q = torch.empty((cfg.B, cfg.Hq, r, d), device=dev)
+    B_K = torch.empty((cfg.B, cfg.Hkv, r, d), device=dev)
+    ws = torch.empty(L.lrqk_workspace_bytes(shape, L.LRQK_WS_PREFILL), dtype=torch.uint8,
+                     device=dev)
+    L.lrqk_prefill_factorize(shape, Q, data.K, A_Q, lb.A_K, B_Q, B_K, 1.0, 1.0, 2, ws)
+    Kf = data.K.float()
+    rel_fit = ((lb.A_K[:, :, :l] @ B_K - Kf).norm() / Kf.norm()).item()
+    print(f"prefill: |K - A_K B_K| / |K| = {rel_fit:.3f} (rank {r}, keys = rank-{r} part + "
+          f"{cfg.noise} noise)", file=out)
+    plan = L.Plan(shape.with_l(l + n_new))
+    ws_u = torch.empty(L.lrqk_workspace_bytes(shape.with_l(l + n_new), L.LRQK_WS_UPDATE),
+                       dtype=torch.uint8, device=dev)
+    i32 = dict(dtype=torch.int32, device=dev)
+    sel_idx = torch.zeros((cfg.B, cfg.Hq, k), **i32)
+    sel_slot = torch.full((cfg.B, cfg.Hq, k), -1, **i32)
+    q_hat = torch.zeros((cfg.B, cfg.Hq, r), device=dev)
+    k_hat = torch.zeros((cfg.B, cfg.Hkv, r), device=dev)
+    out_t = torch.empty((cfg.B, cfg.Hq, d), device=dev)
+    Kall = torch.zeros((cfg.B, cfg.Hkv, l + n_new, d), device=dev)
+    Vall = torch.zeros_like(Kall)
+    Kall[:, :, :l], Vall[:, :, :l] = Kf, data.V.float()
+    recalls, errs, mass = [], [], []
+    lcur = l
+    for t in range(1, n_new + 1):
+        q = qs.next()[0]
+        k_new = torch.einsum("bhr,bhrd->bhd",
+                             torch.randn((cfg.B, cfg.Hkv, r), generator=gen, device=dev),
+                             data.Bmat).to(data.K.dtype)
+        v_new = torch.randn((cfg.B, cfg.Hkv, d), generator=gen, device=dev).to(data.K.dtype)
+        shp = shape.with_l(lcur)
+        # the first step has no previous selection: lambda_d2 = 0 leaves Omega out
+        lam2 = 0.0 if t == 1 else 1.0
+        L.lrqk_factor_update(shp, lb.struct, sel_idx, sel_slot, q, k_new, B_Q, B_K, 1.0, lam2, 2,
+                             q_hat, k_hat, ws_u)
+        L.lrqk_append_token(shp, lb.struct, k_hat, k_new, v_new)
+        Kall[:, :, lcur], Vall[:, :, lcur] = k_new.float(), v_new.float()
+        lcur += 1
+        L.lrqk_decode_step(plan, shape.with_l(lcur), t, lb.struct, q_hat, q, out_t,
+                           L.LRQK_FETCH_DIRECT, dict(sel_idx=sel_idx, sel_slot=sel_slot))
+        # evaluation: exact scores, exact top-k over [0, l - w), dense attention
+        Krep = Kall[:, :, :lcur].repeat_interleave(G, dim=1)
+        Vrep = Vall[:, :, :lcur].repeat_interleave(G, dim=1)
+        s = torch.einsum("bhd,bhld->bhl", q, Krep)
+        top = s[:, :, :lcur - w].topk(k, dim=-1).indices
+        hit = torch.zeros_like(s, dtype=torch.bool)
+        hit.scatter_(2, sel_idx.long(), True)
+        recalls.append(hit.gather(2, top).float().mean().item())
+        p = torch.softmax(s * cfg.scale, dim=-1)
+        dense = torch.einsum("bhl,bhld->bhd", p, Vrep)
+        hit[:, :, lcur - w:] = True
+        mass.append((p * hit).sum(-1).mean().item())
+        errs.append(((out_t - dense).norm() / dense.norm()).item())
+    plan.close()
+    print("| steps | recall of the exact top-k | attention mass covered by the k + w rows | "
+          "|out - dense| / |dense| |", file=out)
+    print("|---|---|---|---|", file=out)
+    for name, sl in (("step 1 (no previous selection)", slice(0, 1)),
+                     (f"steps 2..{n_new}", slice(1, None))):
+        print(f"| {name} | {np.mean(recalls[sl]):.3f} | {np.mean(mass[sl]):.3f} | "
+              f"{np.mean(errs[sl]):.3f} |", file=out)
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__.split("\n")[0])
     ap.add_argument("--grid", action="store_true")
     ap.add_argument("--no-hit-miss", action="store_true")
+    ap.add_argument("--end-to-end", action="store_true")
     ap.add_argument("--steps", type=int, default=64)
     ap.add_argument("--warm", type=int, default=8)
     ap.add_argument("--layers", type=int, default=8)
@@ -138,7 +228,7 @@ def main():
     args = ap.parse_args()
     if not torch.cuda.is_available():
         sys.exit("ablation: needs a GPU")
-    both = not (args.grid or args.no_hit_miss)
+    both = not (args.grid or args.no_hit_miss or args.end_to_end)
     if args.grid or both:
         print("## Miss-rate grid (Sec. 5.3), l = 4096, 32 q / 8 kv heads, cache of k slots, "
               f"query drift {args.drift} of the heavy window per step\n")
@@ -147,6 +237,10 @@ def main():
         print("\n## Hit/miss ablation (App. C.2), workload 3 (l = 131072, r = 32, k = 2048), "
               f"{args.layers} layers rotated\n")
         no_hit_miss(args.steps, args.layers)
+    if args.end_to_end or both:
+        print("\n## Prefill factorisation, then Alg. 2 decode steps on its factors: 8 q / 2 kv "
+              "heads, l = 8192, r = 32, k = 512, w = 16\n")
+        end_to_end(min(args.steps, 32))
 
 
 if __name__ == "__main__":
