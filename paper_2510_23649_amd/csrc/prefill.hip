@@ -108,11 +108,11 @@ __global__ __launch_bounds__(kPfThreads) void prefill_pass_kernel(
     for (int i = t; i < kD * RP; i += kPfThreads) Ms[i] = Mh[i];
   }
 
-  f32x16 accXY[RB], accXX[RB * RB];
+  f32x16 accXY[RB], accXY1[RB], accXX[RB * RB];
 #pragma unroll
   for (int i = 0; i < RB; ++i)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) accXY[i][v] = 0.0f;
+    for (int v = 0; v < 16; ++v) accXY[i][v] = accXY1[i][v] = 0.0f;
 #pragma unroll
   for (int i = 0; i < RB * RB; ++i)
 #pragma unroll
@@ -159,15 +159,18 @@ __global__ __launch_bounds__(kPfThreads) void prefill_pass_kernel(
       // rows 32w .. 32w+31 of X = Y M
 #pragma unroll
       for (int rb = 0; rb < RB; ++rb) {
-        f32x16 acc;
+        // two accumulators, so that consecutive MFMAs do not wait for each other's result
+        f32x16 acc, acc1;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[v] = 0.0f;
-#pragma unroll 8
-        for (int kk = 0; kk < kD; kk += 2) {
-          const float a = y_at(32 * w + mi, kk + mk);
-          const float b = Ms[(kk + mk) * RP + 32 * rb + mi];
-          acc = mfma32(a, b, acc);
+        for (int v = 0; v < 16; ++v) acc[v] = acc1[v] = 0.0f;
+#pragma unroll 4
+        for (int kk = 0; kk < kD; kk += 4) {
+          acc = mfma32(y_at(32 * w + mi, kk + mk), Ms[(kk + mk) * RP + 32 * rb + mi], acc);
+          acc1 = mfma32(y_at(32 * w + mi, kk + 2 + mk), Ms[(kk + 2 + mk) * RP + 32 * rb + mi],
+                        acc1);
         }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] += acc1[v];
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int i = 32 * w + mfma_row(v, lane), j = 32 * rb + mi;
@@ -181,26 +184,35 @@ __global__ __launch_bounds__(kPfThreads) void prefill_pass_kernel(
     }
 
     if (REDUCE) {
-      // block w of the d columns of X^T Y, all 128 rows of the tile
-#pragma unroll 4
-      for (int kk = 0; kk < kPfTile; kk += 2) {
-        const float b = y_at(kk + mk, 32 * w + mi);
+      // block w of the d columns of X^T Y over all 128 rows of the tile (two accumulator sets,
+      // row pairs alternate between them), and this wavefront's quarter of the rows of X^T X,
+      // interleaved with it: consecutive MFMAs never wait for each other's result
+      auto xy_step = [&](int kk) {
+        const float b0 = y_at(kk + mk, 32 * w + mi), b1 = y_at(kk + 2 + mk, 32 * w + mi);
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
-          accXY[rb] = mfma32(Xs[(kk + mk) * LDX + 32 * rb + mi], b, accXY[rb]);
+        for (int rb = 0; rb < RB; ++rb) {
+          accXY[rb] = mfma32(Xs[(kk + mk) * LDX + 32 * rb + mi], b0, accXY[rb]);
+          accXY1[rb] = mfma32(Xs[(kk + 2 + mk) * LDX + 32 * rb + mi], b1, accXY1[rb]);
+        }
+      };
+#pragma unroll 2
+      for (int kk = 0; kk < 32; kk += 4) {
+        xy_step(kk);
+#pragma unroll
+        for (int h = 0; h < 4; h += 2) {
+          float a[RB];
+#pragma unroll
+          for (int rb = 0; rb < RB; ++rb)
+            a[rb] = Xs[(32 * w + kk + h + mk) * LDX + 32 * rb + mi];
+#pragma unroll
+          for (int r1 = 0; r1 < RB; ++r1)
+#pragma unroll
+            for (int r2 = 0; r2 < RB; ++r2)
+              accXX[r1 * RB + r2] = mfma32(a[r1], a[r2], accXX[r1 * RB + r2]);
+        }
       }
-      // this wavefront's quarter of the rows of X^T X
 #pragma unroll 4
-      for (int kk = 32 * w; kk < 32 * w + 32; kk += 2) {
-        float a[RB];
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) a[rb] = Xs[(kk + mk) * LDX + 32 * rb + mi];
-#pragma unroll
-        for (int r1 = 0; r1 < RB; ++r1)
-#pragma unroll
-          for (int r2 = 0; r2 < RB; ++r2)
-            accXX[r1 * RB + r2] = mfma32(a[r1], a[r2], accXX[r1 * RB + r2]);
-      }
+      for (int kk = 32; kk < kPfTile; kk += 4) xy_step(kk);
     }
   }
 
@@ -211,7 +223,7 @@ __global__ __launch_bounds__(kPfThreads) void prefill_pass_kernel(
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int i = 32 * rb + mfma_row(v, lane);
-        if (i < R) out[(size_t)i * kD + 32 * w + mi] = accXY[rb][v];
+        if (i < R) out[(size_t)i * kD + 32 * w + mi] = accXY[rb][v] + accXY1[rb][v];
       }
     // X^T X: add the four wavefronts' parts through LDS (the Y tile's space)
     __syncthreads();
