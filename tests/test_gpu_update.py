@@ -49,7 +49,7 @@ def factors_for(cfg, data, seed, perturb=0.05):
     return B_Q.contiguous(), B_K.contiguous(), k_new.contiguous()
 
 
-def run_update_case(cfg, lam1=1.0, lam2=1.0, n_iter=2, warm_steps=2, seed=7):
+def run_update_case(cfg, lam1=1.0, lam2=1.0, n_iter=2, warm_steps=2, seed=7, drop=0):
     data = make_layer(cfg)
     dl = DeviceLayer(cfg, data)
     plan = L.Plan(dl.shape)
@@ -64,9 +64,22 @@ def run_update_case(cfg, lam1=1.0, lam2=1.0, n_iter=2, warm_steps=2, seed=7):
     assert (prev["sel_slot"] >= 0).all()
     q, _ = qs.next()
     B_Q, B_K, k_new = factors_for(cfg, data, seed)
+    omega = upd.omega_positions(prev["sel_idx"], cfg.l, cfg.w)
+    if drop:
+        # entries of the previous selection without a usable slot are left out of Omega
+        rng = np.random.default_rng(seed)
+        keep = np.ones(omega.shape, bool)
+        slots = prev["sel_slot"].copy()
+        for b in range(cfg.B):
+            for h in range(cfg.Hq):
+                gone = rng.choice(cfg.k, size=drop, replace=False)
+                keep[b, h, gone] = False
+                slots[b, h, gone[: drop // 2]] = -1
+                slots[b, h, gone[drop // 2:]] = cfg.C + 3
+        omega = omega[keep].reshape(cfg.B, cfg.Hq, -1)
+        sb.sel_slot.copy_(torch.from_numpy(slots))
     ref = upd.factor_update(as_numpy(q), as_numpy(k_new), as_numpy(B_Q), as_numpy(B_K),
-                            dl.np["A_K"], dl.np["K"],
-                            upd.omega_positions(prev["sel_idx"], cfg.l, cfg.w), lam1, lam2, n_iter)
+                            dl.np["A_K"], dl.np["K"], omega, lam1, lam2, n_iter)
     dBQ, dBK = B_Q.to(DEV), B_K.to(DEV)
     q_hat_d = torch.full((cfg.B, cfg.Hq, cfg.r), float("nan"), device=DEV)
     k_hat_d = torch.full((cfg.B, cfg.Hkv, cfg.r), float("nan"), device=DEV)
@@ -112,6 +125,11 @@ def test_factor_update_fp32_rows_and_ragged_sizes():
 def test_factor_update_lambdas_and_rounds(lam1, lam2, n_iter):
     say(f"factor update lambda_d1={lam1} lambda_d2={lam2} rounds={n_iter}")
     run_update_case(upd_cfg(B=1, Hq=4, Hkv=2, r=16), lam1, lam2, n_iter)
+
+
+def test_factor_update_skips_entries_without_a_slot():
+    say("factor update, 6 entries per head of the previous selection have no valid slot")
+    run_update_case(upd_cfg(B=1, Hq=4, Hkv=2, r=16), drop=6)
 
 
 def test_factor_update_no_lite_window():
