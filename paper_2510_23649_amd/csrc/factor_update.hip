@@ -91,25 +91,78 @@ __device__ __forceinline__ float kv_load(const void* row, int j) {
 }
 
 // q . K_row for the 16 lanes that share a row; lane c of the 16 takes elements 8c .. 8c+7.
+// The load and the arithmetic are separate so that a batch of loads can be issued together.
 template <bool BF16>
-__device__ __forceinline__ float dot_chunk(const void* row, int c, const float (&qv)[8]) {
+struct RowPiece {
+  uint4 lo, hi;  // bf16: lo only
+};
+template <bool BF16>
+__device__ __forceinline__ RowPiece<BF16> load_piece(const void* row, int c) {
+  RowPiece<BF16> p;
+  if (BF16) {
+    p.lo = static_cast<const uint4*>(row)[c];
+    p.hi = p.lo;
+  } else {
+    p.lo = static_cast<const uint4*>(row)[2 * c];
+    p.hi = static_cast<const uint4*>(row)[2 * c + 1];
+  }
+  return p;
+}
+template <bool BF16>
+__device__ __forceinline__ float dot_piece(const RowPiece<BF16>& p, const float (&qv)[8]) {
   float x[8];
   if (BF16) {
-    const uint4 u = static_cast<const uint4*>(row)[c];
+    const uint4 u = p.lo;
     x[0] = __uint_as_float(u.x << 16); x[1] = __uint_as_float(u.x & 0xffff0000u);
     x[2] = __uint_as_float(u.y << 16); x[3] = __uint_as_float(u.y & 0xffff0000u);
     x[4] = __uint_as_float(u.z << 16); x[5] = __uint_as_float(u.z & 0xffff0000u);
     x[6] = __uint_as_float(u.w << 16); x[7] = __uint_as_float(u.w & 0xffff0000u);
   } else {
-    const float4 a = static_cast<const float4*>(row)[2 * c];
-    const float4 b = static_cast<const float4*>(row)[2 * c + 1];
-    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
-    x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+    x[0] = __uint_as_float(p.lo.x); x[1] = __uint_as_float(p.lo.y);
+    x[2] = __uint_as_float(p.lo.z); x[3] = __uint_as_float(p.lo.w);
+    x[4] = __uint_as_float(p.hi.x); x[5] = __uint_as_float(p.hi.y);
+    x[6] = __uint_as_float(p.hi.z); x[7] = __uint_as_float(p.hi.w);
   }
   float acc = 0.0f;
 #pragma unroll
   for (int j = 0; j < 8; ++j) acc = __builtin_fmaf(x[j], qv[j], acc);
   return acc;
+}
+
+// S += sum_i a_i^T a_i and g += sum_i u_i a_i over the kGramBatch rows staged in LDS (a_s: row
+// stride LDA floats, rows past the end are zero), by the 256 threads of a workgroup.
+// S is a dense contraction over the rows and goes through v_mfma_f32_32x32x2_f32, whose two
+// operands are here the same numbers: lane i + 32 kk supplies A[i][kk] = B[kk][i] = element i
+// of row kk of the pair.  r <= 32: one 32 x 32 block (columns >= r read as zero), each
+// wavefront sums a quarter of the rows; r = 64: wavefront (bi, bj) owns block (bi, bj) of S
+// and sums all the rows.  g: thread t sums column t % r over every (256 / r)-th row.
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+template <int R>
+__device__ __forceinline__ void gram_accumulate(const float* a_s, const float* u_s, f32x16& sacc,
+                                                float& gpart, int t) {
+  constexpr int LDA = R + 4;
+  const int wave = t >> 6, lane = t & 63, li = lane & 31, lk = lane >> 5;
+  if constexpr (R <= 32) {
+    constexpr int kRows = kGramBatch / 4;  // rows per wavefront
+    static_assert(kRows % 2 == 0, "rows are consumed in pairs");
+#pragma unroll 6
+    for (int i = 0; i < kRows; i += 2) {
+      const float x = li < R ? a_s[(wave * kRows + i + lk) * LDA + li] : 0.0f;
+      sacc = __builtin_amdgcn_mfma_f32_32x32x2f32(x, x, sacc, 0, 0, 0);
+    }
+  } else {
+    const int bi = wave >> 1, bj = wave & 1;
+#pragma unroll 6
+    for (int i = 0; i < kGramBatch; i += 2) {
+      const float xa = a_s[(i + lk) * LDA + 32 * bi + li];
+      const float xb = a_s[(i + lk) * LDA + 32 * bj + li];
+      sacc = __builtin_amdgcn_mfma_f32_32x32x2f32(xa, xb, sacc, 0, 0, 0);
+    }
+  }
+  constexpr int kSub = kGramThreads / R;
+  const int gc = t % R;
+#pragma unroll 4
+  for (int i = t / R; i < kGramBatch; i += kSub) gpart = __builtin_fmaf(u_s[i], a_s[i * LDA + gc], gpart);
 }
 
 struct GramArgs {
@@ -131,12 +184,11 @@ struct GramArgs {
 template <int R, bool BF16>
 __global__ __launch_bounds__(kGramThreads) void factor_gram_kernel(GramArgs a) {
   constexpr int kEntries = R * R;
-  constexpr int EPT = kEntries >= kGramThreads ? kEntries / kGramThreads : 1;
-  constexpr int kActive = kEntries >= kGramThreads ? kGramThreads : kEntries;
   constexpr int LDA = R + 4;  // padded LDS row, keeps 16-byte alignment
   constexpr size_t ROWB = kD * (BF16 ? 2 : 4);
-  static_assert(EPT <= R && R % EPT == 0, "a thread's entries stay inside one row of S");
   __shared__ __align__(16) float a_s[kGramBatch * LDA];
+  // r <= 32: the partial blocks of wavefronts 1..3; then the partial sums of g
+  __shared__ float red_s[R <= 32 ? 3 * 1024 : kGramThreads];
   __shared__ float u_s[kGramBatch];
   __shared__ int pos_s[kGramBatch];
   __shared__ const char* krow_s[kGramBatch];
@@ -148,12 +200,10 @@ __global__ __launch_bounds__(kGramThreads) void factor_gram_kernel(GramArgs a) {
   const int bkv = b * a.Hkv + kvh;
   if (job == a.nchunk + 1 && h != kvh * G) return;  // the B_K job runs once per KV head
 
-  const int e0 = t * EPT;
-  const int p = e0 / R, q0 = e0 % R;
-  float acc[EPT];
+  f32x16 sacc;
 #pragma unroll
-  for (int e = 0; e < EPT; ++e) acc[e] = 0.0f;
-  float gacc = 0.0f;
+  for (int v = 0; v < 16; ++v) sacc[v] = 0.0f;
+  float gpart = 0.0f;
 
   float* out;
   if (job < a.nchunk) {
@@ -169,6 +219,7 @@ __global__ __launch_bounds__(kGramThreads) void factor_gram_kernel(GramArgs a) {
     float qv[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) qv[j] = a.q[(size_t)bh * kD + c16 * 8 + j];
+    const char* qrow = reinterpret_cast<const char*>(a.q + (size_t)bh * kD);
     const int lite0 = a.l - a.w;  // first position of the lite window
     for (int i0 = i_begin; i0 < i_end; i0 += kGramBatch) {
       __syncthreads();  // the previous batch has been consumed
@@ -197,35 +248,43 @@ __global__ __launch_bounds__(kGramThreads) void factor_gram_kernel(GramArgs a) {
         krow_s[t] = krow;
       }
       __syncthreads();
+      // All the loads of the batch are issued before anything waits for one of them; rows
+      // that do not exist read memory that does (the head's q, which is at least as long as
+      // a K row; row 0 of A_K) and are zeroed afterwards.
       // u_i = q . K_i: 16 lanes per row, 16 rows per pass
+      constexpr int kPasses = kGramBatch / 16;
+      RowPiece<BF16> piece[kPasses];
 #pragma unroll
-      for (int pass = 0; pass < kGramBatch / 16; ++pass) {
+      for (int pass = 0; pass < kPasses; ++pass) {
+        const char* krow = krow_s[pass * 16 + rsub];
+        piece[pass] = load_piece<BF16>(krow ? krow : qrow, c16);
+      }
+      // a_i = A_K[pos_i, :]
+      constexpr int kAPieces = (kGramBatch * (R / 4) + kGramThreads - 1) / kGramThreads;
+      float4 av[kAPieces];
+#pragma unroll
+      for (int u = 0; u < kAPieces; ++u) {
+        const int idx = t + u * kGramThreads;
+        const int rr = min(idx / (R / 4), kGramBatch - 1), c4 = idx % (R / 4);
+        const int pos = pos_s[rr];
+        av[u] = reinterpret_cast<const float4*>(Ahead + (size_t)max(pos, 0) * R)[c4];
+        if (pos < 0) av[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      }
+#pragma unroll
+      for (int pass = 0; pass < kPasses; ++pass) {
         const int rr = pass * 16 + rsub;
-        const char* krow = krow_s[rr];
-        float dot = 0.0f;
-        if (krow) dot = dot_chunk<BF16>(krow, c16, qv);
+        float dot = krow_s[rr] ? dot_piece<BF16>(piece[pass], qv) : 0.0f;
         dot = row16_sum(dot);
         if (c16 == 0) u_s[rr] = dot;
       }
-      // a_i = A_K[pos_i, :]
-      for (int idx = t; idx < kGramBatch * (R / 4); idx += kGramThreads) {
-        const int rr = idx / (R / 4), c4 = idx % (R / 4);
-        const int pos = pos_s[rr];
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (pos >= 0) v = reinterpret_cast<const float4*>(Ahead + (size_t)pos * R)[c4];
-        *reinterpret_cast<float4*>(&a_s[rr * LDA + 4 * c4]) = v;
+#pragma unroll
+      for (int u = 0; u < kAPieces; ++u) {
+        const int idx = t + u * kGramThreads;
+        if (idx < kGramBatch * (R / 4))
+          *reinterpret_cast<float4*>(&a_s[idx / (R / 4) * LDA + 4 * (idx % (R / 4))]) = av[u];
       }
       __syncthreads();
-      if (t < kActive) {
-        for (int i = 0; i < kGramBatch; ++i) {
-          const float ap = a_s[i * LDA + p];
-#pragma unroll
-          for (int e = 0; e < EPT; ++e) acc[e] = __builtin_fmaf(ap, a_s[i * LDA + q0 + e], acc[e]);
-        }
-      }
-      if (t < R) {
-        for (int i = 0; i < kGramBatch; ++i) gacc = __builtin_fmaf(u_s[i], a_s[i * LDA + t], gacc);
-      }
+      gram_accumulate<R>(a_s, u_s, sacc, gpart, t);
     }
   } else {
     // ---- B_Q of this query head, or B_K of this KV head, read column by column ------------
@@ -243,28 +302,61 @@ __global__ __launch_bounds__(kGramThreads) void factor_gram_kernel(GramArgs a) {
                   : kv_load<BF16>(static_cast<const char*>(a.k_new) + (size_t)bkv * ROWB, i);
         u_s[t] = u;
       }
-      for (int idx = t; idx < kGramBatch * R; idx += kGramThreads) {
-        const int c = idx / kGramBatch, ii = idx % kGramBatch;
-        a_s[ii * LDA + c] = i0 + ii < kD ? Bm[(size_t)c * kD + i0 + ii] : 0.0f;
+      // every load is issued before the first is waited for (addresses clamped, the values
+      // past the end zeroed)
+      constexpr int kBPieces = (kGramBatch * R + kGramThreads - 1) / kGramThreads;
+      float bv[kBPieces];
+#pragma unroll
+      for (int u = 0; u < kBPieces; ++u) {
+        const int idx = t + u * kGramThreads;
+        const int c = min(idx / kGramBatch, R - 1), ii = idx % kGramBatch;
+        bv[u] = Bm[(size_t)c * kD + min(i0 + ii, kD - 1)];
+        if (i0 + ii >= kD) bv[u] = 0.0f;
+      }
+#pragma unroll
+      for (int u = 0; u < kBPieces; ++u) {
+        const int idx = t + u * kGramThreads;
+        if (idx < kGramBatch * R) a_s[idx % kGramBatch * LDA + idx / kGramBatch] = bv[u];
       }
       __syncthreads();
-      if (t < kActive) {
-        for (int i = 0; i < kGramBatch; ++i) {
-          const float ap = a_s[i * LDA + p];
-#pragma unroll
-          for (int e = 0; e < EPT; ++e) acc[e] = __builtin_fmaf(ap, a_s[i * LDA + q0 + e], acc[e]);
-        }
-      }
-      if (t < R) {
-        for (int i = 0; i < kGramBatch; ++i) gacc = __builtin_fmaf(u_s[i], a_s[i * LDA + t], gacc);
-      }
+      gram_accumulate<R>(a_s, u_s, sacc, gpart, t);
     }
   }
-  if (t < kActive) {
+  // Register v of lane l of an accumulator holds element [8 (v / 4) + 4 (l / 32) + v % 4][l % 32]
+  // of its block.
+  const int wave = t >> 6, lane = t & 63;
+  if constexpr (R <= 32) {
+    __syncthreads();
+    if (wave > 0) {
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) out[e0 + e] = acc[e];
+      for (int v = 0; v < 16; ++v) red_s[(wave - 1) * 1024 + v * 64 + lane] = sacc[v];
+    }
+    __syncthreads();
+    if (wave == 0) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float sum = ((sacc[v] + red_s[v * 64 + lane]) + red_s[1024 + v * 64 + lane]) +
+                          red_s[2048 + v * 64 + lane];
+        const int pr = 8 * (v / 4) + 4 * (lane >> 5) + v % 4, qc = lane & 31;
+        if (pr < R && qc < R) out[pr * R + qc] = sum;
+      }
+    }
+  } else {
+    const int bi = wave >> 1, bj = wave & 1;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int pr = 32 * bi + 8 * (v / 4) + 4 * (lane >> 5) + v % 4, qc = 32 * bj + (lane & 31);
+      out[pr * R + qc] = sacc[v];
+    }
   }
-  if (t < R) out[kEntries + t] = gacc;
+  __syncthreads();
+  red_s[t] = gpart;
+  __syncthreads();
+  if (t < R) {
+    float g = 0.0f;
+    for (int sub = 0; sub < kGramThreads / R; ++sub) g += red_s[sub * R + t];
+    out[kEntries + t] = g;
+  }
 }
 
 struct SolveArgs {
