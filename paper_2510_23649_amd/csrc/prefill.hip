@@ -267,14 +267,19 @@ __global__ __launch_bounds__(256) void prefill_sum_kernel(const float* __restric
 }
 
 // ------------------------------------------------------------------------------------------
-// Solves S Xs = Ys in place for a symmetric positive definite S (r x r, LDS, row stride R + 1;
-// destroyed) and an r x d right-hand side (LDS, row stride kD + 1).  The first wavefront
+// Solves S Xs = Ys in place for a symmetric positive definite S (r x r, LDS, row stride
+// kLDS<R> = R + 4 floats so that four consecutive elements of a row are one 16-byte read;
+// destroyed) and an r x d right-hand side (LDS, row stride kLDY).  The first wavefront
 // factorises S (lane = row) and leaves L and 1 / diag(L) in LDS; then thread j < d owns
-// column j and runs the two triangular solves with the factor read as LDS broadcasts.
-// Called by all threads of a 256-thread workgroup.
+// column j and runs the two triangular solves in 4 x 4 blocks: the block of the factor is
+// read as broadcasts (four 16-byte reads), four elements of the column come from LDS, sixteen
+// multiply-adds follow.  Called by all threads of a 256-thread workgroup.
+template <int R>
+constexpr int kLDS = R + 4;
 template <int R>
 __device__ void spd_solve_columns(float* Ssh, float* dinv_sh, float* Ysh) {
-  constexpr int LDS_ = R + 1;
+  constexpr int LDS_ = kLDS<R>;
+  static_assert(R % 4 == 0, "4 x 4 blocks");
   const int t = threadIdx.x;
   __syncthreads();
   if (t < 64) {
@@ -291,35 +296,59 @@ __device__ void spd_solve_columns(float* Ssh, float* dinv_sh, float* Ysh) {
   }
   __syncthreads();
   if (t < kD) {
-    // this thread's column stays in LDS (only this thread touches it): L z = y, then
-    // L^T x = z; four partial sums per row shorten the dependent chain of fmas
+    float* const y = Ysh + t;  // this thread's column, element i at y[i * kLDY]
+    auto lrow = [&](int row, int col) {
+      return *reinterpret_cast<const float4*>(&Ssh[row * LDS_ + col]);
+    };
+    // L z = y
 #pragma unroll 1
-    for (int i = 0; i < R; ++i) {
-      float a0 = Ysh[i * kLDY + t], a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
-      int c = 0;
+    for (int I = 0; I < R; I += 4) {
+      float a0 = y[(I + 0) * kLDY], a1 = y[(I + 1) * kLDY], a2 = y[(I + 2) * kLDY],
+            a3 = y[(I + 3) * kLDY];
 #pragma unroll 2
-      for (; c + 4 <= i; c += 4) {
-        a0 = __builtin_fmaf(-Ssh[i * LDS_ + c + 0], Ysh[(c + 0) * kLDY + t], a0);
-        a1 = __builtin_fmaf(-Ssh[i * LDS_ + c + 1], Ysh[(c + 1) * kLDY + t], a1);
-        a2 = __builtin_fmaf(-Ssh[i * LDS_ + c + 2], Ysh[(c + 2) * kLDY + t], a2);
-        a3 = __builtin_fmaf(-Ssh[i * LDS_ + c + 3], Ysh[(c + 3) * kLDY + t], a3);
+      for (int C = 0; C < I; C += 4) {
+        const float z0 = y[(C + 0) * kLDY], z1 = y[(C + 1) * kLDY], z2 = y[(C + 2) * kLDY],
+                    z3 = y[(C + 3) * kLDY];
+        const float4 l0 = lrow(I + 0, C), l1 = lrow(I + 1, C), l2 = lrow(I + 2, C),
+                     l3 = lrow(I + 3, C);
+        a0 = __builtin_fmaf(-l0.w, z3, __builtin_fmaf(-l0.z, z2, __builtin_fmaf(-l0.y, z1, __builtin_fmaf(-l0.x, z0, a0))));
+        a1 = __builtin_fmaf(-l1.w, z3, __builtin_fmaf(-l1.z, z2, __builtin_fmaf(-l1.y, z1, __builtin_fmaf(-l1.x, z0, a1))));
+        a2 = __builtin_fmaf(-l2.w, z3, __builtin_fmaf(-l2.z, z2, __builtin_fmaf(-l2.y, z1, __builtin_fmaf(-l2.x, z0, a2))));
+        a3 = __builtin_fmaf(-l3.w, z3, __builtin_fmaf(-l3.z, z2, __builtin_fmaf(-l3.y, z1, __builtin_fmaf(-l3.x, z0, a3))));
       }
-      for (; c < i; ++c) a0 = __builtin_fmaf(-Ssh[i * LDS_ + c], Ysh[c * kLDY + t], a0);
-      Ysh[i * kLDY + t] = ((a0 + a1) + (a2 + a3)) * dinv_sh[i];
+      const float4 l1 = lrow(I + 1, I), l2 = lrow(I + 2, I), l3 = lrow(I + 3, I);
+      a0 *= dinv_sh[I];
+      a1 = __builtin_fmaf(-l1.x, a0, a1) * dinv_sh[I + 1];
+      a2 = __builtin_fmaf(-l2.y, a1, __builtin_fmaf(-l2.x, a0, a2)) * dinv_sh[I + 2];
+      a3 = __builtin_fmaf(-l3.z, a2, __builtin_fmaf(-l3.y, a1, __builtin_fmaf(-l3.x, a0, a3))) *
+           dinv_sh[I + 3];
+      y[(I + 0) * kLDY] = a0; y[(I + 1) * kLDY] = a1;
+      y[(I + 2) * kLDY] = a2; y[(I + 3) * kLDY] = a3;
     }
+    // L^T x = z: the block of L^T for rows I.. and columns C.. is rows C.. of L at columns I..
 #pragma unroll 1
-    for (int i = R - 1; i >= 0; --i) {
-      float a0 = Ysh[i * kLDY + t], a1 = 0.0f, a2 = 0.0f, a3 = 0.0f;
-      int c = i + 1;
+    for (int I = R - 4; I >= 0; I -= 4) {
+      float a0 = y[(I + 0) * kLDY], a1 = y[(I + 1) * kLDY], a2 = y[(I + 2) * kLDY],
+            a3 = y[(I + 3) * kLDY];
 #pragma unroll 2
-      for (; c + 4 <= R; c += 4) {
-        a0 = __builtin_fmaf(-Ssh[(c + 0) * LDS_ + i], Ysh[(c + 0) * kLDY + t], a0);
-        a1 = __builtin_fmaf(-Ssh[(c + 1) * LDS_ + i], Ysh[(c + 1) * kLDY + t], a1);
-        a2 = __builtin_fmaf(-Ssh[(c + 2) * LDS_ + i], Ysh[(c + 2) * kLDY + t], a2);
-        a3 = __builtin_fmaf(-Ssh[(c + 3) * LDS_ + i], Ysh[(c + 3) * kLDY + t], a3);
+      for (int C = I + 4; C < R; C += 4) {
+        const float x0 = y[(C + 0) * kLDY], x1 = y[(C + 1) * kLDY], x2 = y[(C + 2) * kLDY],
+                    x3 = y[(C + 3) * kLDY];
+        const float4 l0 = lrow(C + 0, I), l1 = lrow(C + 1, I), l2 = lrow(C + 2, I),
+                     l3 = lrow(C + 3, I);
+        a0 = __builtin_fmaf(-l3.x, x3, __builtin_fmaf(-l2.x, x2, __builtin_fmaf(-l1.x, x1, __builtin_fmaf(-l0.x, x0, a0))));
+        a1 = __builtin_fmaf(-l3.y, x3, __builtin_fmaf(-l2.y, x2, __builtin_fmaf(-l1.y, x1, __builtin_fmaf(-l0.y, x0, a1))));
+        a2 = __builtin_fmaf(-l3.z, x3, __builtin_fmaf(-l2.z, x2, __builtin_fmaf(-l1.z, x1, __builtin_fmaf(-l0.z, x0, a2))));
+        a3 = __builtin_fmaf(-l3.w, x3, __builtin_fmaf(-l2.w, x2, __builtin_fmaf(-l1.w, x1, __builtin_fmaf(-l0.w, x0, a3))));
       }
-      for (; c < R; ++c) a0 = __builtin_fmaf(-Ssh[c * LDS_ + i], Ysh[c * kLDY + t], a0);
-      Ysh[i * kLDY + t] = ((a0 + a1) + (a2 + a3)) * dinv_sh[i];
+      const float4 l1 = lrow(I + 1, I), l2 = lrow(I + 2, I), l3 = lrow(I + 3, I);
+      a3 *= dinv_sh[I + 3];
+      a2 = __builtin_fmaf(-l3.z, a3, a2) * dinv_sh[I + 2];
+      a1 = __builtin_fmaf(-l3.y, a3, __builtin_fmaf(-l2.y, a2, a1)) * dinv_sh[I + 1];
+      a0 = __builtin_fmaf(-l3.x, a3, __builtin_fmaf(-l2.x, a2, __builtin_fmaf(-l1.x, a1, a0))) *
+           dinv_sh[I];
+      y[(I + 0) * kLDY] = a0; y[(I + 1) * kLDY] = a1;
+      y[(I + 2) * kLDY] = a2; y[(I + 3) * kLDY] = a3;
     }
   }
   __syncthreads();
@@ -333,16 +362,19 @@ __global__ __launch_bounds__(256) void prefill_solve_b_kernel(const float* __res
                                                               float* __restrict__ B_Q,
                                                               float* __restrict__ B_K, int BHq) {
   using S = PfShape<R>;
-  constexpr int LDS_ = R + 1;
+  constexpr int LDS_ = kLDS<R>;
   extern __shared__ __align__(16) float pf_lds[];
   float* const Ysh = pf_lds;              // [R][kLDY]
-  float* const Ssh = Ysh + R * kLDY;      // [R][R + 1]
+  float* const Ssh = Ysh + R * kLDY;      // [R][R + 4]
   float* const dinv_sh = Ssh + R * LDS_;  // [R]
   const int t = threadIdx.x;
   const bool iskv = (int)blockIdx.x >= BHq;
   const size_t head = iskv ? blockIdx.x - BHq : blockIdx.x;
   const float* sm = (iskv ? sum_k : sum_q) + head * S::P;
+  // (unrolled: the loads of several trips are in flight together)
+#pragma unroll 8
   for (int e = t; e < R * kD; e += 256) Ysh[(e / kD) * kLDY + e % kD] = sm[e];
+#pragma unroll 4
   for (int e = t; e < R * R; e += 256) Ssh[(e / R) * LDS_ + e % R] = sm[R * kD + e];
   spd_solve_columns<R>(Ssh, dinv_sh, Ysh);
   float* Bout = (iskv ? B_K : B_Q) + head * R * kD;
@@ -358,31 +390,53 @@ __global__ __launch_bounds__(256) void prefill_solve_mk_kernel(const float* __re
                                                                float* __restrict__ Mk, int Hq,
                                                                int Hkv, float lam_pK) {
   using S = PfShape<R>;
-  constexpr int LDS_ = R + 1, RP = S::RP;
+  constexpr int LDS_ = kLDS<R>, RP = S::RP;
   extern __shared__ __align__(16) float pf_lds[];
   float* const Wsh = pf_lds;              // [R][kLDY]  W^T
   float* const Bsh = Wsh + R * kLDY;      // [R][kLDY]  B_K
-  float* const Ssh = Bsh + R * kLDY;      // [R][R + 1]
+  float* const Ssh = Bsh + R * kLDY;      // [R][R + 4]
   float* const dinv_sh = Ssh + R * LDS_;  // [R]
   const int bkv = blockIdx.x, t = threadIdx.x;
   const int b = bkv / Hkv, kvh = bkv - b * Hkv, G = Hq / Hkv;
   const float* sq = sum_q + ((size_t)b * Hq + (size_t)kvh * G) * S::P;  // the group's G heads
   const float* Bk = B_K + (size_t)bkv * R * kD;
-  for (int e = t; e < R * kD; e += 256) {
+  // The group's sums are added head by head with the element loops innermost and unrolled, so
+  // that the loads of one head are all in flight together (G is not a compile-time constant).
+  constexpr int kT1 = R * kD / 256, kT2 = (R * R + 255) / 256;
+  float w[kT1], gs[kT2];
+#pragma unroll
+  for (int u = 0; u < kT1; ++u) {
+    const int e = t + 256 * u;
     const float bk = Bk[e];
-    float acc = lam_pK * bk;
-    for (int g = 0; g < G; ++g) acc += sq[(size_t)g * S::P + e];
     Bsh[(e / kD) * kLDY + e % kD] = bk;
-    Wsh[(e / kD) * kLDY + e % kD] = acc;
+    w[u] = lam_pK * bk;
+  }
+#pragma unroll
+  for (int u = 0; u < kT2; ++u) gs[u] = 0.0f;
+  for (int g = 0; g < G; ++g) {
+    const float* sg = sq + (size_t)g * S::P;
+#pragma unroll
+    for (int u = 0; u < kT1; ++u) w[u] += sg[t + 256 * u];
+#pragma unroll
+    for (int u = 0; u < kT2; ++u)
+      if (t + 256 * u < R * R) gs[u] += sg[R * kD + t + 256 * u];
+  }
+#pragma unroll
+  for (int u = 0; u < kT1; ++u) {
+    const int e = t + 256 * u;
+    Wsh[(e / kD) * kLDY + e % kD] = w[u];
   }
   __syncthreads();
-  for (int e = t; e < R * R; e += 256) {
-    const int i = e / R, c = e % R;
-    float bb = 0.0f;
-    for (int j = 0; j < kD; ++j) bb = __builtin_fmaf(Bsh[i * kLDY + j], Bsh[c * kLDY + j], bb);
-    float acc = lam_pK * bb;
-    for (int g = 0; g < G; ++g) acc += sq[(size_t)g * S::P + R * kD + e];
-    Ssh[i * LDS_ + c] = acc;
+#pragma unroll
+  for (int u = 0; u < kT2; ++u) {
+    const int e = t + 256 * u;
+    if (e < R * R) {
+      const int i = e / R, c = e % R;
+      float bb = 0.0f;
+#pragma unroll 16
+      for (int j = 0; j < kD; ++j) bb = __builtin_fmaf(Bsh[i * kLDY + j], Bsh[c * kLDY + j], bb);
+      Ssh[i * LDS_ + c] = __builtin_fmaf(lam_pK, bb, gs[u]);
+    }
   }
   spd_solve_columns<R>(Ssh, dinv_sh, Wsh);  // M_K^T = S^-1 W^T
   float* Mo = Mk + (size_t)bkv * kD * RP;
@@ -400,16 +454,17 @@ __global__ __launch_bounds__(256) void prefill_solve_q_kernel(const float* __res
                                                               float* __restrict__ Mq, int Hq,
                                                               int Hkv, float lam_pQ) {
   using S = PfShape<R>;
-  constexpr int LDS_ = R + 1, RP = S::RP;
+  constexpr int LDS_ = kLDS<R>, RP = S::RP;
   extern __shared__ __align__(16) float pf_lds[];
   float* const Ysh = pf_lds;              // [R][kLDY]
   float* const Bsh = Ysh + R * kLDY;      // [R][kLDY]
-  float* const Ssh = Bsh + R * kLDY;      // [R][R + 1]
+  float* const Ssh = Bsh + R * kLDY;      // [R][R + 4]
   float* const dinv_sh = Ssh + R * LDS_;  // [R]
   const int bh = blockIdx.x, t = threadIdx.x;
   const int b = bh / Hq, h = bh - b * Hq, kvh = h / (Hq / Hkv);
   const float* sm = sum_k + ((size_t)b * Hkv + kvh) * S::P;
   const float* Bq = B_Q + (size_t)bh * R * kD;
+#pragma unroll 8
   for (int e = t; e < R * kD; e += 256) {
     const float bq = Bq[e];
     Bsh[(e / kD) * kLDY + e % kD] = bq;
@@ -419,6 +474,7 @@ __global__ __launch_bounds__(256) void prefill_solve_q_kernel(const float* __res
   for (int e = t; e < R * R; e += 256) {
     const int i = e / R, c = e % R;
     float acc = 0.0f;
+#pragma unroll 16
     for (int j = 0; j < kD; ++j) acc = __builtin_fmaf(Bsh[i * kLDY + j], Bsh[c * kLDY + j], acc);
     Ssh[i * LDS_ + c] = __builtin_fmaf(lam_pQ, acc, sm[R * kD + e]);
   }
@@ -442,7 +498,7 @@ hipError_t allow_lds(K kernel, size_t bytes) {
 }
 template <int R>
 constexpr size_t solve_lds_bytes() {
-  return ((size_t)2 * R * kLDY + (size_t)2 * R * (R + 1) + R) * sizeof(float);
+  return ((size_t)2 * R * kLDY + (size_t)R * kLDS<R> + R) * sizeof(float);
 }
 
 template <int R, bool BF16, bool APPLY, bool REDUCE>
