@@ -267,6 +267,10 @@ __global__ __launch_bounds__(256) void prefill_sum_kernel(const float* __restric
 }
 
 // ------------------------------------------------------------------------------------------
+// LDS row stride of an r x r system: four consecutive elements of a row are one 16-byte read.
+template <int R>
+constexpr int kLDS = R + 4;
+
 // Solves S Xs = Ys in place for a symmetric positive definite S (r x r, LDS, row stride
 // kLDS<R> = R + 4 floats so that four consecutive elements of a row are one 16-byte read;
 // destroyed) and an r x d right-hand side (LDS, row stride kLDY).  The first wavefront
@@ -274,8 +278,6 @@ __global__ __launch_bounds__(256) void prefill_sum_kernel(const float* __restric
 // column j and runs the two triangular solves in 4 x 4 blocks: the block of the factor is
 // read as broadcasts (four 16-byte reads), four elements of the column come from LDS, sixteen
 // multiply-adds follow.  Called by all threads of a 256-thread workgroup.
-template <int R>
-constexpr int kLDS = R + 4;
 template <int R>
 __device__ void spd_solve_columns(float* Ssh, float* dinv_sh, float* Ysh) {
   constexpr int LDS_ = kLDS<R>;
