@@ -379,8 +379,12 @@ int lrqk_plan_profile_read(lrqk_plan* plan, double* ms_sum, int* n_steps_out);
  * thresholds estimated once for q_hat; the plain proxy-score kernel for shapes that do not
  * use the filter), n_launches times back to back on `stream`, cycling through the n_list
  * device arrays A_K_list[i] (each [B,Hkv,l,r] fp32, e.g. one per layer, so that no cache
- * holds them), bracketed by two HIP events.  Synchronises; *avg_us_out = microseconds per
- * launch.  Results go to the plan's workspace and are discarded.
+ * holds them), bracketed by two HIP events: microseconds per launch, gaps between launches
+ * included.  For the filtered kernel a second series of at most 64 launches attaches a pair
+ * of events to every kernel (they hold that kernel's own start and end); the average of
+ * those durations is reported instead when it is positive and not above the bracketed
+ * figure.  Synchronises; *avg_us_out = microseconds per launch.  Results go to the plan's
+ * workspace and are discarded.
  */
 int lrqk_plan_time_proxy_pass(lrqk_plan* plan, const lrqk_shape* shape,
                               const float* const* A_K_list, int n_list, const float* q_hat,

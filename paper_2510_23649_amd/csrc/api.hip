@@ -651,7 +651,36 @@ int lrqk_plan_time_proxy_pass(lrqk_plan* plan, const lrqk_shape* shape,
   (void)hipEventDestroy(e0);
   if (e1) (void)hipEventDestroy(e1);
   LRQK_HIP(e);
-  *avg_us_out = 1e3f * ms / (float)n_launches;
+  const float bracketed_us = 1e3f * ms / (float)n_launches;
+  *avg_us_out = bracketed_us;
+  if (!filtered) return LRQK_OK;
+  // The bracketed average includes the gap between consecutive launches.  A second series
+  // attaches a pair of events to every kernel, which then hold that kernel's own start and
+  // end; their average is reported if it is plausible (positive, not above the bracketed one).
+  const int n2 = n_launches < 64 ? n_launches : 64;
+  hipEvent_t ev[128] = {};
+  e = hipSuccess;
+  for (int i = 0; i < 2 * n2 && e == hipSuccess; ++i) e = hipEventCreate(&ev[i]);
+  for (int i = 0; i < n2 && e == hipSuccess; ++i) {
+    proxy_filter_time_next_launch(ev[2 * i], ev[2 * i + 1]);
+    e = pass(A_K_list[i % n_list]);
+  }
+  proxy_filter_time_next_launch(nullptr, nullptr);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  double sum_us = 0.0;
+  for (int i = 0; i < n2 && e == hipSuccess; ++i) {
+    float k_ms = 0.f;
+    e = hipEventElapsedTime(&k_ms, ev[2 * i], ev[2 * i + 1]);
+    sum_us += 1e3 * k_ms;
+  }
+  for (int i = 0; i < 2 * n2; ++i)
+    if (ev[i]) (void)hipEventDestroy(ev[i]);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();  // the bracketed figure stands
+    return LRQK_OK;
+  }
+  const float per_kernel_us = (float)(sum_us / n2);
+  if (per_kernel_us > 0.f && per_kernel_us <= bracketed_us) *avg_us_out = per_kernel_us;
   return LRQK_OK;
 }
 

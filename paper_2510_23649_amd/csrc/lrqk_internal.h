@@ -73,6 +73,9 @@ hipError_t launch_proxy_threshold(const lrqk_shape& s, const float* A_K, const f
                                   float* samples, uint32_t* thr, hipStream_t st);
 constexpr int kCandPerGroup = 8;  // candidate scores kept per head and 64-row group
 // cand_scores: [BHq][words64][kCandPerGroup] floats
+// Timing aid: the next filtered proxy-score launches of the calling thread record the
+// kernel's own start and end in these events (both null: back to plain launches).
+void proxy_filter_time_next_launch(hipEvent_t start, hipEvent_t stop);
 hipError_t launch_proxy_scores_filter(const lrqk_shape& s, const float* A_K, const float* q_hat,
                                       float* scores, const uint32_t* thr,
                                       unsigned long long* bitmap, float* cand_scores,

@@ -18,6 +18,9 @@
 // load -> LDS -> compute chain of each other; measured on MI355X this beats fewer
 // workgroups that loop over tiles with a register prefetch.
 // The chain order (j ascending from 0.0f) makes the scores bit-reproducible.
+#include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
+
 #include "lrqk_device.h"
 #include "lrqk_internal.h"
 
@@ -290,13 +293,20 @@ __global__ __launch_bounds__(256) void proxy_scores_generic_kernel(
   }
 }
 
+// Events that the next filtered launch of this thread attaches to its kernel (null: none).
+thread_local hipEvent_t g_time_start = nullptr, g_time_stop = nullptr;
+
 template <int R, int G>
 hipError_t launch_fast(const lrqk_shape& s, const float* A_K, const float* q_hat, float* scores,
                        const uint32_t* thr, unsigned long long* bitmap, float* cand_scores,
                        hipStream_t st) {
   dim3 grid(ceil_div(s.l, kTileRows), s.B * s.Hkv);
   const int n = s.l - s.w;
-  if (thr)
+  if (thr && g_time_start)  // timing run: the events take the kernel's own start and end
+    hipExtLaunchKernelGGL((proxy_scores_kernel<R, G, true>), grid, dim3(kTileRows), 0, st,
+                          g_time_start, g_time_stop, 0, A_K, q_hat, scores, s.l, row_cap(s), s.Hq,
+                          s.Hkv, n, thr, bitmap, cand_scores, filter_words64(n));
+  else if (thr)
     hipLaunchKernelGGL((proxy_scores_kernel<R, G, true>), grid, dim3(kTileRows), 0, st, A_K,
                        q_hat, scores, s.l, row_cap(s), s.Hq, s.Hkv, n, thr, bitmap, cand_scores,
                        filter_words64(n));
@@ -345,6 +355,11 @@ hipError_t launch_proxy_threshold(const lrqk_shape& s, const float* A_K, const f
   hipLaunchKernelGGL(proxy_threshold_kernel, dim3(s.B * s.Hq), dim3(kThrThreads), 0, st, samples,
                      n, s.k, SS, ns, thr);
   return hipGetLastError();
+}
+
+void proxy_filter_time_next_launch(hipEvent_t start, hipEvent_t stop) {
+  g_time_start = start;
+  g_time_stop = stop;
 }
 
 hipError_t launch_proxy_scores_filter(const lrqk_shape& s, const float* A_K, const float* q_hat,
