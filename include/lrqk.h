@@ -198,6 +198,23 @@ int lrqk_sparse_attend(const lrqk_shape* shape, const float* q, const void* cach
                        void* stream);
 
 /*
+ * a5 for callers that cannot allocate: code under HIP graph capture, tight serving loops and
+ * harnesses that forbid hipMalloc, which have no workspace to hand over either.  Same
+ * arguments, kernels and results as lrqk_sparse_attend, without `workspace`: the partial
+ * softmax states sit in a fixed array of LRQK_NOALLOC_SCRATCH_BYTES of device memory inside
+ * the library (one copy per GPU, held until the process ends).  The call allocates and frees
+ * nothing, on the host side of HIP or the device.
+ *   LRQK_ENOMEM if lrqk_workspace_bytes(shape, LRQK_WS_ATTEND) exceeds the array (nothing is
+ *   enqueued).  At the headline shape (32 heads, k = 2048, w = 64) the call needs 0.6 MB.
+ * Every call on a GPU uses that GPU's one array: two calls whose work overlaps on the same
+ * GPU (different streams, or threads) race.  Calls on one stream are ordered and safe.
+ */
+#define LRQK_NOALLOC_SCRATCH_BYTES (4u << 20)
+int lrqk_sparse_attend_noalloc(const lrqk_shape* shape, const float* q, const void* cacheK,
+                               const void* cacheV, const int32_t* sel_slot, const void* liteK,
+                               const void* liteV, float* out, void* stream);
+
+/*
  * A plan owns what the fused step and the fetch leg need beyond the caller's
  * buffers: device workspace, a side stream with events, and pinned staging
  * memory sized for `max_shape` (every later call must use a shape whose

@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     lrqk_prefill_factorize, LrqkError, Layer, Plan, Shape, library_path, load_library,
     lrqk_cache_init, lrqk_cache_resolve, lrqk_calib_copy, lrqk_decode_step, lrqk_fetch_misses,
     lrqk_last_hip_error, lrqk_proxy_scores, lrqk_select_topk, lrqk_sparse_attend,
+    lrqk_sparse_attend_noalloc,
     lrqk_status_string, lrqk_validate_shape, lrqk_version, lrqk_workspace_bytes, make_layer,
 )
 from .state import LayerBuffers  # noqa: F401

@@ -85,6 +85,7 @@ def load_library():
         "lrqk_cache_init": (C.c_int, [sp, vp, vp, vp, vp]),
         "lrqk_cache_resolve": (C.c_int, [sp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "lrqk_sparse_attend": (C.c_int, [sp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
+        "lrqk_sparse_attend_noalloc": (C.c_int, [sp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "lrqk_factor_update": (C.c_int, [sp, C.POINTER(Layer), vp, vp, vp, vp, vp, vp, C.c_float,
                                          C.c_float, i32, vp, vp, vp, sz, vp]),
         "lrqk_append_token": (C.c_int, [sp, C.POINTER(Layer), vp, vp, vp, vp]),
@@ -114,7 +115,7 @@ EXPORTS = ["lrqk_version", "lrqk_status_string", "lrqk_last_hip_error", "lrqk_va
            "lrqk_cache_resolve", "lrqk_sparse_attend", "lrqk_plan_create", "lrqk_plan_destroy",
            "lrqk_fetch_misses", "lrqk_decode_step", "lrqk_plan_profile", "lrqk_plan_profile_read", "lrqk_calib_copy",
            "lrqk_plan_time_proxy_pass", "lrqk_factor_update", "lrqk_append_token",
-           "lrqk_prefill_factorize"]
+           "lrqk_prefill_factorize", "lrqk_sparse_attend_noalloc"]
 
 
 def _check(status: int, where: str):
@@ -204,6 +205,13 @@ def lrqk_sparse_attend(shape, q, cacheK, cacheV, sel_slot, liteK, liteV, out, wo
         _dev(sel_slot, torch.int32), _dev(liteK), _dev(liteV), _dev(out, torch.float32),
         _dev(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
         "lrqk_sparse_attend")
+
+
+def lrqk_sparse_attend_noalloc(shape, q, cacheK, cacheV, sel_slot, liteK, liteV, out, stream=None):
+    _check(load_library().lrqk_sparse_attend_noalloc(
+        C.byref(shape), _dev(q, torch.float32), _dev(cacheK), _dev(cacheV),
+        _dev(sel_slot, torch.int32), _dev(liteK), _dev(liteV), _dev(out, torch.float32),
+        _stream(stream)), "lrqk_sparse_attend_noalloc")
 
 
 def lrqk_factor_update(shape, layer, sel_idx_prev, sel_slot_prev, q, k_new, B_Q, B_K, lambda_d1,

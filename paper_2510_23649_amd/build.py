@@ -1,6 +1,6 @@
 """Build liblrqk.so (HIP kernels + C ABI) for gfx950, in-tree.
 
-    python -m paper_2510_23649_amd.build
+    python -m paper_2510_23649_amd.build [--changed]
 
 Each source is compiled by hipcc to an object under _build/ and the objects are
 linked into paper_2510_23649_amd/liblrqk.so.  The library targets MI355X only.
@@ -20,7 +20,7 @@ LIB = os.path.join(PKG, "liblrqk.so")
 
 SOURCES = ["api.hip", "proxy_scores.hip", "select_topk.hip", "cache_resolve.hip", "select_resolve.hip",
            "sparse_attend.hip", "fetch.hip", "factor_update.hip", "append_token.hip", "prefill.hip",
-           "instrument.hip"]
+           "instrument.hip", "noalloc.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
@@ -43,10 +43,23 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(verbose: bool = True) -> str:
+def _stale(src: str) -> bool:
+    """True if the object of `src` is missing or older than the source or any header."""
+    obj = os.path.join(OBJ, src.replace(".hip", ".o"))
+    if not os.path.exists(obj):
+        return True
+    deps = [os.path.join(CSRC, src), os.path.join(ROOT, "include", "lrqk.h")]
+    deps += [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
+    return any(os.path.getmtime(d) > os.path.getmtime(obj) for d in deps)
+
+
+def build(verbose: bool = True, only_changed: bool = False) -> str:
+    """Compile every source (or, with only_changed, those whose object is out of date) and link."""
     os.makedirs(OBJ, exist_ok=True)
+    todo = [s for s in SOURCES if not only_changed or _stale(s)]
     with ThreadPoolExecutor(max_workers=min(6, os.cpu_count() or 1)) as ex:
-        objs = list(ex.map(_compile, SOURCES))
+        list(ex.map(_compile, todo))
+    objs = [os.path.join(OBJ, s.replace(".hip", ".o")) for s in SOURCES]
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
@@ -61,4 +74,4 @@ def is_built() -> bool:
 
 
 if __name__ == "__main__":
-    build()
+    build(only_changed="--changed" in sys.argv[1:])

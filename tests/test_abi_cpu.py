@@ -75,6 +75,10 @@ def test_entry_points_reject_bad_arguments_before_any_device_work(lib):
     # workspace too small
     assert raw.lrqk_select_topk(C.byref(s), A, A, A, 16, None) == -4
     assert raw.lrqk_sparse_attend(C.byref(s), A, A, A, A, A, A, A, A, 16, None) == -4
+    # the entry point without a workspace: null pointer, then partial states beyond its fixed array
+    assert raw.lrqk_sparse_attend_noalloc(C.byref(s), None, A, A, A, A, A, A, None) == -1
+    big = lib.Shape.make(B=2048, Hq=8, Hkv=8, l=8192, r=4, k=4096, w=0, C_slots=4096)
+    assert raw.lrqk_sparse_attend_noalloc(C.byref(big), A, A, A, A, A, A, A, None) == -4
     # bad shape wins over everything else
     b = good(lib, r=30)
     assert raw.lrqk_proxy_scores(C.byref(b), A, A, A, None) == -2
