@@ -112,8 +112,11 @@ def main():
 
     def run_step(li, q, q_hat, debug=None):
         step_no[li] += 1
+        # a layer's first step estimates its candidate thresholds from a sample; later steps
+        # carry them over
+        flags = L.LRQK_SELECT_FRESH if step_no[li] == 1 else 0
         return L.lrqk_decode_step(plan, shape, step_no[li], layers[li].struct, q_hat, q, out,
-                                  mode, debug)
+                                  mode | flags, debug)
 
     # prime the caches: two untimed passes over all layers
     oracle_queries = []
@@ -167,7 +170,8 @@ def main():
     # over the layers' A_K, bracketed by HIP events on the launch stream inside the library
     # (a Python loop of single launches would be bound by the interpreter, not by the GPU)
     n_k = max(args.steps, 64)
-    k1_us = plan.time_proxy_pass(shape, [lb.A_K for lb in layers], queries[0][1], n_k)
+    k1_us = plan.time_proxy_pass(shape, [lb.A_K for lb in layers], queries[0][1], n_k,
+                                  sel_thr=layers[0].sel_thr)
     a_k_bytes = cfg.B * cfg.Hkv * cfg.l * cfg.r * 4 + cfg.B * cfg.Hq * cfg.r * 4
     k1_gbs = a_k_bytes / (k1_us * 1e-6) / 1e9
 

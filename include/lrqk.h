@@ -72,6 +72,12 @@ enum {
                             own; lrqk_decode_step does it inside the attention kernel, so the
                             host-link reads overlap the HBM reads of the rows that hit      */
 };
+/* May be OR-ed into the `mode` of lrqk_decode_step: estimate the candidate thresholds of the
+ * selection from a sample of this step's proxy scores even though the layer carries thresholds
+ * from its previous step (lrqk_layer.sel_thr).  For the first decode step of a sequence and
+ * after anything that changes the score distribution wholesale.  Results never depend on it,
+ * only speed does. */
+#define LRQK_SELECT_FRESH 0x100
 
 /*
  * Problem sizes of one layer's decode step.
@@ -253,7 +259,16 @@ typedef struct lrqk_layer {
   int32_t* last_used;  /* int32 [B,Hq,C]  in/out */
   void* cacheK;        /* kv_dtype [B,Hq,C,d] in/out */
   void* cacheV;        /* kv_dtype [B,Hq,C,d] in/out */
+  float* sel_thr;      /* fp32 [B,Hq] in/out, or NULL: candidate threshold of the selection
+                          carried from one step of this layer to the next (see lrqk_decode_step);
+                          set up with lrqk_select_state_init.  Only lrqk_decode_step uses it */
 } lrqk_layer;
+
+/*
+ * Marks the carried selection thresholds of a layer as unknown (every entry NaN).
+ *   sel_thr  device fp32 [B,Hq]  written
+ */
+int lrqk_select_state_init(const lrqk_shape* shape, float* sel_thr, void* stream);
 
 /* Optional device outputs of the fused step (any may be NULL): the integer
  * results of a2/a3, bit-identical to what the separate calls produce. */
@@ -275,10 +290,19 @@ typedef struct lrqk_step_debug {
  * and are attended afterwards; partial results are merged.  DIRECT: one attention launch
  * over all rows, the missing ones read from the host store and written to their slots on
  * the way.
+ * Selection (shapes the filtered proxy-score pass supports): the pass over A_K keeps only the
+ * positions whose score reaches a per-head candidate threshold, and the selection is made
+ * exactly among those; a head whose candidates turn out unusable (fewer than k) is redone
+ * exactly from all its scores, so the threshold affects speed, never the result.  The
+ * threshold is estimated from a sample of this step's scores (two small launches) when
+ * layer->sel_thr is NULL or `mode` carries LRQK_SELECT_FRESH; otherwise it is
+ * layer->sel_thr[b,h] * |q_hat[b,h]|, the value the previous step's selection left there (the
+ * score at rank 1.5 k, per unit of |q_hat|), and every step rewrites sel_thr for the next one.
+ * An entry that is NaN (lrqk_select_state_init) sends its head down the exact, slow route.
  *   q_hat  device fp32 [B,Hq,r];  q  device fp32 [B,Hq,d];  out  device fp32 [B,Hq,d]
  *   step   as in lrqk_cache_resolve
  *   mode   LRQK_FETCH_STAGED (one host synchronisation per call, to read the miss
- *          list) or LRQK_FETCH_DIRECT (fully asynchronous)
+ *          list) or LRQK_FETCH_DIRECT (fully asynchronous), optionally | LRQK_SELECT_FRESH
  *   dbg    optional
  *   total_miss_out  host int64*, optional (STAGED: rows fetched; DIRECT: -1)
  */
@@ -392,9 +416,11 @@ int lrqk_plan_profile_read(lrqk_plan* plan, double* ms_sum, int* n_steps_out);
 
 /*
  * Instrumentation: time the dominant kernel alone.  Runs step a1's pass over A_K exactly as
- * lrqk_decode_step launches it for this shape (the filtered proxy-score kernel with the
- * thresholds estimated once for q_hat; the plain proxy-score kernel for shapes that do not
- * use the filter), n_launches times back to back on `stream`, cycling through the n_list
+ * lrqk_decode_step launches it for this shape (the filtered proxy-score kernel, its thresholds
+ * taken from sel_thr [B,Hq] as in a step that carries them (device, a layer's array after a
+ * step with this kind of q_hat), or, with sel_thr NULL, estimated once from a sample for q_hat;
+ * the plain proxy-score kernel for shapes that do not use the filter), n_launches times back
+ * to back on `stream`, cycling through the n_list
  * device arrays A_K_list[i] (each [B,Hkv,l,r] fp32, e.g. one per layer, so that no cache
  * holds them), bracketed by two HIP events: microseconds per launch, gaps between launches
  * included.  For the filtered kernel a second series of at most 64 launches attaches a pair
@@ -405,7 +431,8 @@ int lrqk_plan_profile_read(lrqk_plan* plan, double* ms_sum, int* n_steps_out);
  */
 int lrqk_plan_time_proxy_pass(lrqk_plan* plan, const lrqk_shape* shape,
                               const float* const* A_K_list, int n_list, const float* q_hat,
-                              int n_launches, float* avg_us_out, void* stream);
+                              const float* sel_thr, int n_launches, float* avg_us_out,
+                              void* stream);
 
 /*
  * Instrumentation: copy `bytes` (a multiple of 16) from src to dst, both device memory,

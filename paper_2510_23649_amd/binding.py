@@ -13,6 +13,7 @@ _lib = None
 
 LRQK_KV_BF16, LRQK_KV_F32 = 0, 1
 LRQK_FETCH_STAGED, LRQK_FETCH_DIRECT = 0, 1
+LRQK_SELECT_FRESH = 0x100
 LRQK_WS_SELECT, LRQK_WS_ATTEND, LRQK_WS_UPDATE, LRQK_WS_PREFILL = 1, 2, 3, 4
 
 
@@ -50,7 +51,8 @@ class Shape(C.Structure):
 class Layer(C.Structure):
     """lrqk_layer: raw pointers of one layer's buffers."""
     _fields_ = [(n, C.c_void_p) for n in ("A_K", "K_host", "V_host", "liteK", "liteV", "slot_of",
-                                          "token_of", "last_used", "cacheK", "cacheV")]
+                                          "token_of", "last_used", "cacheK", "cacheV",
+                                          "sel_thr")]
 
 
 class _StepDebug(C.Structure):
@@ -83,6 +85,7 @@ def load_library():
         "lrqk_proxy_scores": (C.c_int, [sp, vp, vp, vp, vp]),
         "lrqk_select_topk": (C.c_int, [sp, vp, vp, vp, sz, vp]),
         "lrqk_cache_init": (C.c_int, [sp, vp, vp, vp, vp]),
+        "lrqk_select_state_init": (C.c_int, [sp, vp, vp]),
         "lrqk_cache_resolve": (C.c_int, [sp, vp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp]),
         "lrqk_sparse_attend": (C.c_int, [sp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]),
         "lrqk_sparse_attend_noalloc": (C.c_int, [sp, vp, vp, vp, vp, vp, vp, vp, vp]),
@@ -98,7 +101,7 @@ def load_library():
         "lrqk_decode_step": (C.c_int, [vp, sp, i32, C.POINTER(Layer), vp, vp, vp, C.c_int,
                                        C.POINTER(_StepDebug), C.POINTER(C.c_int64), vp]),
         "lrqk_calib_copy": (C.c_int, [vp, vp, sz, vp]),
-        "lrqk_plan_time_proxy_pass": (C.c_int, [vp, sp, C.POINTER(vp), C.c_int, vp, C.c_int,
+        "lrqk_plan_time_proxy_pass": (C.c_int, [vp, sp, C.POINTER(vp), C.c_int, vp, vp, C.c_int,
                                                 C.POINTER(C.c_float), vp]),
         "lrqk_plan_profile": (C.c_int, [vp, C.c_int]),
         "lrqk_plan_profile_read": (C.c_int, [vp, C.POINTER(C.c_double), C.POINTER(C.c_int)]),
@@ -115,7 +118,7 @@ EXPORTS = ["lrqk_version", "lrqk_status_string", "lrqk_last_hip_error", "lrqk_va
            "lrqk_cache_resolve", "lrqk_sparse_attend", "lrqk_plan_create", "lrqk_plan_destroy",
            "lrqk_fetch_misses", "lrqk_decode_step", "lrqk_plan_profile", "lrqk_plan_profile_read", "lrqk_calib_copy",
            "lrqk_plan_time_proxy_pass", "lrqk_factor_update", "lrqk_append_token",
-           "lrqk_prefill_factorize", "lrqk_sparse_attend_noalloc"]
+           "lrqk_prefill_factorize", "lrqk_sparse_attend_noalloc", "lrqk_select_state_init"]
 
 
 def _check(status: int, where: str):
@@ -187,6 +190,11 @@ def lrqk_cache_init(shape, slot_of, token_of, last_used, stream=None):
                                           _dev(token_of, torch.int32),
                                           _dev(last_used, torch.int32), _stream(stream)),
            "lrqk_cache_init")
+
+
+def lrqk_select_state_init(shape, sel_thr, stream=None):
+    _check(load_library().lrqk_select_state_init(C.byref(shape), _dev(sel_thr, torch.float32),
+                                                 _stream(stream)), "lrqk_select_state_init")
 
 
 def lrqk_cache_resolve(shape, sel_idx, step, slot_of, token_of, last_used, sel_slot, hit,
@@ -270,13 +278,15 @@ class Plan:
                "lrqk_plan_profile_read")
         return dict(zip(self.PHASES, list(ms))), n.value
 
-    def time_proxy_pass(self, shape, A_K_list, q_hat, n_launches, stream=None) -> float:
+    def time_proxy_pass(self, shape, A_K_list, q_hat, n_launches, sel_thr=None,
+                        stream=None) -> float:
         """lrqk_plan_time_proxy_pass: microseconds per launch of step a1's pass over A_K."""
         ptrs = (C.c_void_p * len(A_K_list))(*[_dev(a, torch.float32) for a in A_K_list])
         us = C.c_float(0.0)
         _check(load_library().lrqk_plan_time_proxy_pass(
             self.handle, C.byref(shape), ptrs, len(A_K_list), _dev(q_hat, torch.float32),
-            int(n_launches), C.byref(us), _stream(stream)), "lrqk_plan_time_proxy_pass")
+            _dev(sel_thr, torch.float32), int(n_launches), C.byref(us), _stream(stream)),
+            "lrqk_plan_time_proxy_pass")
         return us.value
 
     def close(self):
@@ -303,10 +313,11 @@ def lrqk_fetch_misses(plan: Plan, shape, K_host, V_host, miss_tok, miss_slot, n_
 
 
 def make_layer(*, A_K, K_host, V_host, liteK, liteV, slot_of, token_of, last_used, cacheK,
-               cacheV) -> Layer:
+               cacheV, sel_thr=None) -> Layer:
     return Layer(_dev(A_K, torch.float32), _pinned(K_host), _pinned(V_host), _dev(liteK),
                  _dev(liteV), _dev(slot_of, torch.int32), _dev(token_of, torch.int32),
-                 _dev(last_used, torch.int32), _dev(cacheK), _dev(cacheV))
+                 _dev(last_used, torch.int32), _dev(cacheK), _dev(cacheV),
+                 _dev(sel_thr, torch.float32))
 
 
 def lrqk_decode_step(plan: Plan, shape, step, layer: Layer, q_hat, q, out,

@@ -19,6 +19,7 @@ OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "liblrqk.so")
 
 SOURCES = ["api.hip", "proxy_scores.hip", "select_topk.hip", "cache_resolve.hip", "select_resolve.hip",
+           "select_packed.hip",
            "sparse_attend.hip", "fetch.hip", "factor_update.hip", "append_token.hip", "prefill.hip",
            "instrument.hip", "noalloc.hip"]
 
@@ -26,8 +27,7 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
-         "-Wall", "-Wno-unused-command-line-argument",
-         *os.environ.get("LRQK_EXTRA_FLAGS", "").split()]
+         "-Wall", "-Wno-unused-command-line-argument"]
 
 
 def _compile(src: str) -> str:

@@ -116,7 +116,8 @@ struct lrqk_plan {
   int BHq;
   // device
   float* scores;
-  uint32_t* thr;               // [BHq] sampled threshold bin of each head
+  uint32_t* thr;               // [BHq] threshold key of each head estimated from a sample
+  uint32_t* thr_used;          // [BHq] the keys the last filtered proxy-score pass used
   float* samples;              // [BHq][kThrMaxSamples] sample scores behind thr
   unsigned long long* filter;  // [BHq][words64] candidate bitmap from the proxy-score pass
   float* cand_scores;          // [BHq][words64][kCandPerGroup] the candidates' scores
@@ -220,6 +221,15 @@ int lrqk_cache_init(const lrqk_shape* shape, int32_t* slot_of, int32_t* token_of
   if (!all_aligned16({slot_of, token_of, last_used})) return LRQK_EINVAL;
   LRQK_HIP(launch_cache_init(*shape, slot_of, token_of, last_used,
                              static_cast<hipStream_t>(stream)));
+  return LRQK_OK;
+}
+
+int lrqk_select_state_init(const lrqk_shape* shape, float* sel_thr, void* stream) {
+  const int rc = check_shape(shape);
+  if (rc != LRQK_OK) return rc;
+  if (!all_aligned16({sel_thr})) return LRQK_EINVAL;
+  LRQK_HIP(launch_fill_i32(reinterpret_cast<int32_t*>(sel_thr), (size_t)shape->B * shape->Hq,
+                           0x7fc00000, static_cast<hipStream_t>(stream)));  // quiet NaN
   return LRQK_OK;
 }
 
@@ -327,7 +337,7 @@ int lrqk_plan_destroy(lrqk_plan* p) {
   (void)hipGetDevice(&prev);
   (void)hipSetDevice(p->device);
   if (p->side) (void)hipStreamSynchronize(p->side);
-  void* dev[] = {p->scores,   p->thr,      p->samples,  p->filter,    p->cand_scores,
+  void* dev[] = {p->thr_used, p->scores,   p->thr,      p->samples,  p->filter,    p->cand_scores,
                  p->select_ws, p->partials, p->sel_idx,  p->sel_slot,  p->miss_tok,
                  p->miss_slot, p->n_miss,   p->hit,      p->d_stage,   p->d_rowdst};
   for (void* q : dev)
@@ -371,6 +381,7 @@ int lrqk_plan_create(const lrqk_shape* max_shape, lrqk_plan** plan_out) {
   };
   dmalloc((void**)&p->scores, BHq * s.l * sizeof(float));
   dmalloc((void**)&p->thr, BHq * 4);
+  dmalloc((void**)&p->thr_used, BHq * 4);
   dmalloc((void**)&p->samples, BHq * (size_t)kThrMaxSamples * 4);
   dmalloc((void**)&p->filter, BHq * (size_t)filter_words64(s.l) * 8);
   dmalloc((void**)&p->cand_scores, BHq * (size_t)filter_words64(s.l) * kCandPerGroup * 4);
@@ -518,12 +529,14 @@ int lrqk_fetch_misses(lrqk_plan* plan, const lrqk_shape* shape, const void* K_ho
 
 int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
                      const lrqk_layer* L, const float* q_hat, const float* q, float* out,
-                     int mode, const lrqk_step_debug* dbg, int64_t* total_miss_out,
+                     int mode_flags, const lrqk_step_debug* dbg, int64_t* total_miss_out,
                      void* stream) {
   int rc = check_shape(shape);
   if (rc != LRQK_OK) return rc;
   if (!L || step < 0 || step == INT32_MAX) return LRQK_EINVAL;
+  const int mode = mode_flags & ~LRQK_SELECT_FRESH;
   if (mode != LRQK_FETCH_STAGED && mode != LRQK_FETCH_DIRECT) return LRQK_EINVAL;
+  if (L->sel_thr && !aligned16(L->sel_thr)) return LRQK_EINVAL;
   if (!all_aligned16({L->A_K, L->K_host, L->V_host, L->slot_of, L->token_of, L->last_used,
                       L->cacheK, L->cacheV, q_hat, q, out}))
     return LRQK_EINVAL;
@@ -544,20 +557,32 @@ int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
 
   const SelectWs ws = carve_select_ws(plan->select_ws, BHq, s.k);
   LRQK_HIP(prof_mark(plan, 0, st));
-  const bool one_wg = select_resolve_fits(s, true);
+  const bool packed = select_packed_fits(s) && proxy_filter_supported(s);
+  const bool one_wg = packed || select_resolve_fits(s, true);
   const bool filtered = one_wg && proxy_filter_supported(s);
   if (filtered) {
-    // sampled threshold, then one pass over A_K that leaves only the candidate bitmap
-    LRQK_HIP(launch_proxy_threshold(s, L->A_K, q_hat, plan->samples, plan->thr, st));
+    // candidate thresholds: carried over from the layer's previous step, or estimated from a
+    // sample of this step's scores; then one pass over A_K that leaves only the candidate
+    // bitmap and the candidates' scores
+    const bool fresh = !packed || !L->sel_thr || (mode_flags & LRQK_SELECT_FRESH);
+    if (fresh) LRQK_HIP(launch_proxy_threshold(s, L->A_K, q_hat, plan->samples, plan->thr, st));
     LRQK_HIP(prof_mark(plan, 1, st));
-    LRQK_HIP(launch_proxy_scores_filter(s, L->A_K, q_hat, plan->scores, plan->thr, plan->filter,
-                                        plan->cand_scores, st));
+    LRQK_HIP(launch_proxy_scores_filter(s, L->A_K, q_hat, plan->scores,
+                                        fresh ? plan->thr : nullptr, fresh ? nullptr : L->sel_thr,
+                                        plan->thr_used, plan->filter, plan->cand_scores, st));
   } else {
     LRQK_HIP(prof_mark(plan, 1, st));
     LRQK_HIP(launch_proxy_scores(s, L->A_K, q_hat, plan->scores, st));
   }
   LRQK_HIP(prof_mark(plan, 2, st));
-  if (one_wg) {
+  if (packed) {
+    // selection and resolution in one launch; the profile books it all under "selection"
+    LRQK_HIP(launch_select_packed(s, plan->filter, plan->cand_scores, plan->thr_used, L->A_K,
+                                  q_hat, plan->scores, L->sel_thr, sel_idx, step, L->slot_of,
+                                  L->token_of, L->last_used, sel_slot, hit, miss_tok, miss_slot,
+                                  n_miss, st));
+    LRQK_HIP(prof_mark(plan, 3, st));
+  } else if (one_wg) {
     // selection and resolution in one launch; the profile books it all under "selection"
     LRQK_HIP(launch_select_resolve(s, plan->scores, filtered ? plan->filter : nullptr,
                                    plan->cand_scores, L->A_K, q_hat, sel_idx, step, L->slot_of,
@@ -618,11 +643,13 @@ int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
 
 int lrqk_plan_time_proxy_pass(lrqk_plan* plan, const lrqk_shape* shape,
                               const float* const* A_K_list, int n_list, const float* q_hat,
-                              int n_launches, float* avg_us_out, void* stream) {
+                              const float* sel_thr, int n_launches, float* avg_us_out,
+                              void* stream) {
   int rc = check_shape(shape);
   if (rc != LRQK_OK) return rc;
   if (!A_K_list || n_list < 1 || n_launches < 1 || !avg_us_out || !all_aligned16({q_hat}))
     return LRQK_EINVAL;
+  if (sel_thr && !aligned16(sel_thr)) return LRQK_EINVAL;
   for (int i = 0; i < n_list; ++i)
     if (!all_aligned16({A_K_list[i]})) return LRQK_EINVAL;
   rc = check_plan_fits(plan, shape);
@@ -631,17 +658,22 @@ int lrqk_plan_time_proxy_pass(lrqk_plan* plan, const lrqk_shape* shape,
   const bool filtered = select_resolve_fits(*shape, true) && proxy_filter_supported(*shape);
   auto pass = [&](const float* A_K) -> hipError_t {
     if (filtered)
-      return launch_proxy_scores_filter(*shape, A_K, q_hat, plan->scores, plan->thr, plan->filter,
-                                        plan->cand_scores, st);
+      return launch_proxy_scores_filter(*shape, A_K, q_hat, plan->scores,
+                                        sel_thr ? nullptr : plan->thr, sel_thr, plan->thr_used,
+                                        plan->filter, plan->cand_scores, st);
     return launch_proxy_scores(*shape, A_K, q_hat, plan->scores, st);
   };
   // thresholds for this q_hat, then a few untimed launches
-  if (filtered)
+  if (filtered && !sel_thr)
     LRQK_HIP(launch_proxy_threshold(*shape, A_K_list[0], q_hat, plan->samples, plan->thr, st));
   for (int i = 0; i < (n_list < 4 ? n_list : 4); ++i) LRQK_HIP(pass(A_K_list[i]));
   hipEvent_t e0 = nullptr, e1 = nullptr;
   LRQK_HIP(hipEventCreate(&e0));
   hipError_t e = hipEventCreate(&e1);
+  if (e != hipSuccess) {
+    (void)hipEventDestroy(e0);
+    LRQK_HIP(e);
+  }
   if (e == hipSuccess) e = hipEventRecord(e0, st);
   for (int i = 0; i < n_launches && e == hipSuccess; ++i) e = pass(A_K_list[i % n_list]);
   if (e == hipSuccess) e = hipEventRecord(e1, st);

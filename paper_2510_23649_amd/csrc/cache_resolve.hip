@@ -12,36 +12,19 @@
 //      (last_used + 1) << 32 | slot are sorted in LDS (all other slots sort last);
 //   3. miss j takes sorted[j]: evict its token, install the new one.
 // All of it is integer work with a fixed order, so the result is deterministic.
+#include "lrqk_device.h"
 #include "lrqk_internal.h"
 
 namespace lrqk {
 namespace {
+
+using dev::bitonic_sort_lds;
 
 constexpr int kResThreads = 1024;
 
 __global__ __launch_bounds__(256) void fill_i32_kernel(int32_t* p, size_t n, int32_t v) {
   const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i < n) p[i] = v;
-}
-
-template <typename T>
-__device__ __forceinline__ void bitonic_sort_lds(T* a, int n) {
-  for (int size = 2; size <= n; size <<= 1) {
-    for (int stride = size >> 1; stride > 0; stride >>= 1) {
-      __syncthreads();
-      for (int i = threadIdx.x; i < (n >> 1); i += blockDim.x) {
-        const int pos = 2 * i - (i & (stride - 1));
-        const int j = pos + stride;
-        const bool up = (pos & size) == 0;
-        const T x = a[pos], y = a[j];
-        if ((x > y) == up) {
-          a[pos] = y;
-          a[j] = x;
-        }
-      }
-    }
-  }
-  __syncthreads();
 }
 
 // dynamic LDS: uint64 keys[Cpad]
@@ -151,6 +134,12 @@ __global__ __launch_bounds__(kResThreads) void cache_resolve_kernel(
 }
 
 }  // namespace
+
+hipError_t launch_fill_i32(int32_t* p, size_t n, int32_t v, hipStream_t st) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, n, v);
+  return hipGetLastError();
+}
 
 hipError_t launch_cache_init(const lrqk_shape& s, int32_t* slot_of, int32_t* token_of,
                              int32_t* last_used, hipStream_t st) {

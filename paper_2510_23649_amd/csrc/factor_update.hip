@@ -40,21 +40,6 @@
 #include "lrqk_internal.h"
 #include "lrqk_linalg.h"
 
-#ifdef LRQK_KPROF
-__device__ unsigned long long g_kprof_fu[16];
-#define FKPROF(i)                                                            \
-  do {                                                                       \
-    if (blockIdx.x == 0 && threadIdx.x == 0) g_kprof_fu[i] = wall_clock64(); \
-  } while (0)
-extern "C" __attribute__((visibility("default"))) int lrqk_kprof_fu_read(unsigned long long* out) {
-  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_kprof_fu), sizeof(g_kprof_fu));
-}
-#else
-#define FKPROF(i) \
-  do {            \
-  } while (0)
-#endif
-
 namespace lrqk {
 namespace {
 
@@ -420,8 +405,6 @@ __global__ __launch_bounds__(kMaxG * 64) void factor_solve_kernel(SolveArgs a) {
   const int bh = b * a.Hq + kvh * G + g;
   const bool row = lane < R;
   const int li = row ? lane : 0;  // keeps the loads of idle lanes in bounds
-
-  FKPROF(0);
   const float* qp = a.q + (size_t)bh * kD;
   const char* kp = static_cast<const char*>(a.k_new) + (size_t)bkv * ROWB;
   const float qk_part = qp[lane] * kv_load<BF16>(kp, lane) +
@@ -508,12 +491,9 @@ __global__ __launch_bounds__(kMaxG * 64) void factor_solve_kernel(SolveArgs a) {
   // q . k of this query head
   const float qk = wave_sum(qk_part);
   if (lane == 0) qk_s[g] = qk;
-
-  FKPROF(1);
   // Factorise N (for the initial guess) and P (kept for every round) together.
   float dN, dP;
   chol_factor2<R>(m, p, dN, dP, lane);
-  FKPROF(2);
   // initial guess (lambda_d1 = 0): k_hat = k B_K^T (B_K B_K^T)^-1
   float k_hat = tri_forward<R>(m, dN, nb, lane);
   transpose_rows<R>(m, m, lt, lane);
@@ -521,8 +501,6 @@ __global__ __launch_bounds__(kMaxG * 64) void factor_solve_kernel(SolveArgs a) {
   // y0 = cvec P^-1
   transpose_rows<R>(p, pt, lt, lane);
   const float y0 = tri_backward<R>(pt, dP, tri_forward<R>(p, dP, cvec, lane), lane);
-
-  FKPROF(3);
   float q_hat = 0.0f;
   for (int it = 0; it < a.n_iter; ++it) {
     // q_hat = m_lq M_rq^-1 with M_rq = P + lambda_d1 k_hat^T k_hat a rank-one change of P:
@@ -533,7 +511,6 @@ __global__ __launch_bounds__(kMaxG * 64) void factor_solve_kernel(SolveArgs a) {
     const float kv_ = wave_sum(row ? k_hat * v : 0.0f);
     const float kz = wave_sum(row ? k_hat * z : 0.0f);
     q_hat = __builtin_fmaf(-z, a.lam1 * kv_ / __builtin_fmaf(a.lam1, kz, 1.0f), v);
-    if (it == 0) FKPROF(4);
     __syncthreads();  // the previous round's q_hat has been read by every wavefront
     if (row) qhat_s[g * R + lane] = q_hat;
     __syncthreads();
@@ -551,14 +528,11 @@ __global__ __launch_bounds__(kMaxG * 64) void factor_solve_kernel(SolveArgs a) {
 #pragma unroll
       for (int c = 0; c < R; ++c) m[c] = __builtin_fmaf(a.lam1 * qi, qhat_s[gg * R + c], m[c]);
     }
-    if (it == 0) FKPROF(5);
     const float dM = chol_factor<R>(m, lane);
     k_hat = tri_forward<R>(m, dM, rhs, lane);
     transpose_rows<R>(m, m, lt, lane);
     k_hat = tri_backward<R>(m, dM, k_hat, lane);
-    if (it == 0) FKPROF(6);
   }
-  FKPROF(7);
   if (row) a.q_hat[(size_t)bh * R + lane] = q_hat;
   if (row && g == 0) a.k_hat[(size_t)bkv * R + lane] = k_hat;
 
@@ -567,7 +541,6 @@ __global__ __launch_bounds__(kMaxG * 64) void factor_solve_kernel(SolveArgs a) {
   if (g == 0)
     line_search_step<R>(k_hat, a.B_K + (size_t)bkv * R * kD,
                         [&](int j) { return kv_load<BF16>(kp, j); }, lane);
-  FKPROF(8);
 }
 
 template <int R, bool BF16>

@@ -14,6 +14,32 @@ __device__ __forceinline__ uint32_t order_key(float s) {
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 
+// Inverse of order_key (the key of -0.0f comes back as +0.0f).
+__device__ __forceinline__ float key_to_float(uint32_t key) {
+  return __uint_as_float((key & 0x80000000u) ? (key & 0x7fffffffu) : ~key);
+}
+
+// In-LDS bitonic sort, ascending, n a power of two; every thread of the workgroup takes part.
+template <typename T>
+__device__ __forceinline__ void bitonic_sort_lds(T* a, int n) {
+  for (int size = 2; size <= n; size <<= 1) {
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      __syncthreads();
+      for (int i = threadIdx.x; i < (n >> 1); i += blockDim.x) {
+        const int pos = 2 * i - (i & (stride - 1));
+        const int j = pos + stride;
+        const bool up = (pos & size) == 0;
+        const T x = a[pos], y = a[j];
+        if ((x > y) == up) {
+          a[pos] = y;
+          a[j] = x;
+        }
+      }
+    }
+  }
+  __syncthreads();
+}
+
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
   return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xf, 0xf, false);

@@ -76,10 +76,14 @@ constexpr int kCandPerGroup = 8;  // candidate scores kept per head and 64-row g
 // Timing aid: the next filtered proxy-score launches of the calling thread record the
 // kernel's own start and end in these events (both null: back to plain launches).
 void proxy_filter_time_next_launch(hipEvent_t start, hipEvent_t stop);
+// The threshold key of each head comes from `thr` (keys, e.g. from launch_proxy_threshold) or,
+// if `thr` is null, from thr_norm[head] * |q_hat[head]| (the value the previous step's
+// selection left for this layer).  Exactly one of the two is given.  thr_out [BHq] receives
+// the keys used.
 hipError_t launch_proxy_scores_filter(const lrqk_shape& s, const float* A_K, const float* q_hat,
-                                      float* scores, const uint32_t* thr,
-                                      unsigned long long* bitmap, float* cand_scores,
-                                      hipStream_t st);
+                                      float* scores, const uint32_t* thr, const float* thr_norm,
+                                      uint32_t* thr_out, unsigned long long* bitmap,
+                                      float* cand_scores, hipStream_t st);
 hipError_t launch_select_topk(const lrqk_shape& s, const float* scores, int32_t* sel_idx,
                               const SelectWs& ws, hipStream_t st);
 // One workgroup per head, everything in LDS (select_resolve.hip); usable when the
@@ -98,6 +102,20 @@ hipError_t launch_select_resolve(const lrqk_shape& s, float* scores,
                                  int32_t* last_used, int32_t* sel_slot, uint8_t* hit,
                                  int32_t* miss_tok, int32_t* miss_slot, int32_t* n_miss,
                                  hipStream_t st);
+// Selection and resolution straight from the bitmap and packed scores of the filtered
+// proxy-score pass (select_packed.hip); usable when select_packed_fits.  thr_used [BHq]: the
+// keys that pass filtered with.  sel_thr (may be null) [BHq]: receives the threshold, divided
+// by |q_hat|, that the layer's next step should filter with.  scores_w [BHq][l]: scratch for
+// heads that need every score.
+bool select_packed_fits(const lrqk_shape& s);
+hipError_t launch_select_packed(const lrqk_shape& s, const unsigned long long* bitmap,
+                                const float* cand_scores, const uint32_t* thr_used,
+                                const float* A_K, const float* q_hat, float* scores_w,
+                                float* sel_thr, int32_t* sel_idx, int32_t step, int32_t* slot_of,
+                                int32_t* token_of, int32_t* last_used, int32_t* sel_slot,
+                                uint8_t* hit, int32_t* miss_tok, int32_t* miss_slot,
+                                int32_t* n_miss, hipStream_t st);
+hipError_t launch_fill_i32(int32_t* p, size_t n, int32_t v, hipStream_t st);
 hipError_t launch_cache_init(const lrqk_shape& s, int32_t* slot_of, int32_t* token_of,
                              int32_t* last_used, hipStream_t st);
 hipError_t launch_cache_resolve(const lrqk_shape& s, const int32_t* sel_idx, int32_t step,

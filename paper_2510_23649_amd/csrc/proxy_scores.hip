@@ -43,10 +43,16 @@ __device__ __forceinline__ float4 load_streaming(const float4* p) {
 // the selection kernel recomputes the others from A_K).  The fused step therefore never
 // writes the l-sized score array: about 5 MB leave this kernel instead of 16.8 MB at
 // l = 131072.
+// The threshold key of a head comes either from thr (keys estimated from a sample for this
+// very q_hat) or, when thr_norm is given, from the value the selection of the layer's previous
+// step left behind: thr_norm[head] * |q_hat[head]| (a NaN there gives a key above every score:
+// no candidates, and the selection falls back to its exact route).  The keys used are written
+// to thr_out by the first workgroup of each KV head.
 template <int R, int G, bool FILTER>
 __global__ __launch_bounds__(kTileRows) void proxy_scores_kernel(
     const float* __restrict__ A_K, const float* __restrict__ q_hat, float* __restrict__ scores,
     int l, int lrows, int Hq, int Hkv, int n, const uint32_t* __restrict__ thr,
+    const float* __restrict__ thr_norm, uint32_t* __restrict__ thr_out,
     unsigned long long* __restrict__ bitmap, float* __restrict__ cand_scores, int words64) {
   // The tile goes through LDS in column phases of at most 32 floats, so that the LDS
   // footprint (and with it the number of resident workgroups) does not grow with r; the
@@ -57,6 +63,12 @@ __global__ __launch_bounds__(kTileRows) void proxy_scores_kernel(
   constexpr int ROW4 = V4 + 1;         // padded LDS row stride in 16-byte units
   static_assert(R % CH == 0, "rank must be a multiple of the phase width");
   __shared__ float4 tile[kTileRows * ROW4];
+  // threshold key of head g: kept in the padding chunk of tile row 255 - g, which neither the
+  // tile stores nor the staging of the packed scores below touch (no LDS of its own: the
+  // number of resident workgroups is set by the tile)
+  auto thr_slot = [&](int g) {
+    return reinterpret_cast<uint32_t*>(&tile[(kTileRows - 1 - g) * ROW4 + V4]);
+  };
 
   const int bkv = blockIdx.y;
   const int b = bkv / Hkv, kv = bkv - b * Hkv;
@@ -68,6 +80,7 @@ __global__ __launch_bounds__(kTileRows) void proxy_scores_kernel(
   const float4* __restrict__ src = reinterpret_cast<const float4*>(A + (size_t)row0 * R);
   const int rows_valid = min(kTileRows, l - row0);
 
+  const size_t bh0 = (size_t)b * Hq + (size_t)kv * G;  // first head of the group
   // all phases' loads are issued up front: chunk idx of phase p is row idx / V4,
   // 16-byte column p * V4 + idx % V4 (8 lanes read 128 contiguous bytes of a row)
   float4 pre[NPH][V4];
@@ -80,6 +93,30 @@ __global__ __launch_bounds__(kTileRows) void proxy_scores_kernel(
       pre[p][i] = rr < rows_valid ? load_streaming(src + (size_t)rr * (R / 4) + p * V4 + cc)
                                   : make_float4(0.f, 0.f, 0.f, 0.f);
     }
+
+  // (the tile's loads stay ahead of what follows: it is meant to run in their shadow)
+  __builtin_amdgcn_sched_barrier(0);
+  // Threshold key of each head of the group.  With carried thresholds |q_hat| is needed:
+  // q_hat is wave-uniform (scalar loads, the same ones the products below use), so the first
+  // wavefront sums the squares with no memory instruction of its own while the tile's loads are
+  // in flight, and hands the keys to the others through LDS (published by the barrier that
+  // follows the tile store).
+  if (FILTER && t < 64) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      uint32_t key;
+      if (thr_norm != nullptr) {
+        float q2 = 0.0f;
+#pragma unroll
+        for (int j = 0; j < R; ++j) q2 = __builtin_fmaf(qh[g * R + j], qh[g * R + j], q2);
+        const float tf = thr_norm[bh0 + g] * __builtin_sqrtf(q2);
+        key = (tf != tf) ? 0xffffffffu : dev::order_key(tf);
+      } else {
+        key = thr[bh0 + g];
+      }
+      if (t == 0) *thr_slot(g) = key;
+    }
+  }
 
   float acc[G];
 #pragma unroll
@@ -120,8 +157,10 @@ __global__ __launch_bounds__(kTileRows) void proxy_scores_kernel(
     float* stage = reinterpret_cast<float*>(&tile[(t & ~63) * ROW4]);
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      const size_t bh = (size_t)b * Hq + (size_t)kv * G + g;
-      const bool in = row < n && dev::order_key(acc[g]) >= thr[bh];
+      const size_t bh = bh0 + g;
+      const uint32_t thr_g = *thr_slot(g);
+      if (blockIdx.x == 0 && t == 0) thr_out[bh] = thr_g;
+      const bool in = row < n && dev::order_key(acc[g]) >= thr_g;
       const unsigned long long mask = __ballot(in);
       if (lane == 0 && wrow < n) bitmap[bh * words64 + (wrow >> 6)] = mask;
       if (mask != 0ull) {  // wave-uniform
@@ -130,7 +169,7 @@ __global__ __launch_bounds__(kTileRows) void proxy_scores_kernel(
         __builtin_amdgcn_wave_barrier();
         if (in && rank < kCandPerGroup) stage[g * kCandPerGroup + rank] = acc[g];
         __builtin_amdgcn_wave_barrier();
-        // one full 64-byte store per wavefront and head instead of scattered 4-byte ones
+        // one 32-byte store per wavefront and head instead of scattered 4-byte ones
         if (lane < kCandPerGroup)
           cand_scores[(bh * words64 + (wrow >> 6)) * kCandPerGroup + lane] =
               stage[g * kCandPerGroup + lane];
@@ -296,37 +335,45 @@ __global__ __launch_bounds__(256) void proxy_scores_generic_kernel(
 // Events that the next filtered launch of this thread attaches to its kernel (null: none).
 thread_local hipEvent_t g_time_start = nullptr, g_time_stop = nullptr;
 
+struct FilterOut {
+  const uint32_t* thr;    // threshold keys (null: take them from thr_norm)
+  const float* thr_norm;  // carried thresholds / |q_hat| (null: take the keys in thr)
+  uint32_t* thr_out;      // keys used
+  unsigned long long* bitmap;
+  float* cand_scores;
+};
+
 template <int R, int G>
 hipError_t launch_fast(const lrqk_shape& s, const float* A_K, const float* q_hat, float* scores,
-                       const uint32_t* thr, unsigned long long* bitmap, float* cand_scores,
-                       hipStream_t st) {
+                       const FilterOut* f, hipStream_t st) {
   dim3 grid(ceil_div(s.l, kTileRows), s.B * s.Hkv);
   const int n = s.l - s.w;
-  if (thr && g_time_start)  // timing run: the events take the kernel's own start and end
+  if (f && g_time_start)  // timing run: the events take the kernel's own start and end
     hipExtLaunchKernelGGL((proxy_scores_kernel<R, G, true>), grid, dim3(kTileRows), 0, st,
                           g_time_start, g_time_stop, 0, A_K, q_hat, scores, s.l, row_cap(s), s.Hq,
-                          s.Hkv, n, thr, bitmap, cand_scores, filter_words64(n));
-  else if (thr)
+                          s.Hkv, n, f->thr, f->thr_norm, f->thr_out, f->bitmap, f->cand_scores,
+                          filter_words64(n));
+  else if (f)
     hipLaunchKernelGGL((proxy_scores_kernel<R, G, true>), grid, dim3(kTileRows), 0, st, A_K,
-                       q_hat, scores, s.l, row_cap(s), s.Hq, s.Hkv, n, thr, bitmap, cand_scores,
-                       filter_words64(n));
+                       q_hat, scores, s.l, row_cap(s), s.Hq, s.Hkv, n, f->thr, f->thr_norm,
+                       f->thr_out, f->bitmap, f->cand_scores, filter_words64(n));
   else
     hipLaunchKernelGGL((proxy_scores_kernel<R, G, false>), grid, dim3(kTileRows), 0, st, A_K,
-                       q_hat, scores, s.l, row_cap(s), s.Hq, s.Hkv, n, nullptr, nullptr, nullptr, 0);
+                       q_hat, scores, s.l, row_cap(s), s.Hq, s.Hkv, n, nullptr, nullptr, nullptr,
+                       nullptr, nullptr, 0);
   return hipGetLastError();
 }
 
 template <int R>
 hipError_t dispatch_G(const lrqk_shape& s, const float* A_K, const float* q_hat, float* scores,
-                      const uint32_t* thr, unsigned long long* bitmap, float* cand_scores,
-                      hipStream_t st, bool* handled) {
+                      const FilterOut* f, hipStream_t st, bool* handled) {
   *handled = true;
   switch (s.Hq / s.Hkv) {
-    case 1: return launch_fast<R, 1>(s, A_K, q_hat, scores, thr, bitmap, cand_scores, st);
-    case 2: return launch_fast<R, 2>(s, A_K, q_hat, scores, thr, bitmap, cand_scores, st);
-    case 4: return launch_fast<R, 4>(s, A_K, q_hat, scores, thr, bitmap, cand_scores, st);
-    case 7: return launch_fast<R, 7>(s, A_K, q_hat, scores, thr, bitmap, cand_scores, st);
-    case 8: return launch_fast<R, 8>(s, A_K, q_hat, scores, thr, bitmap, cand_scores, st);
+    case 1: return launch_fast<R, 1>(s, A_K, q_hat, scores, f, st);
+    case 2: return launch_fast<R, 2>(s, A_K, q_hat, scores, f, st);
+    case 4: return launch_fast<R, 4>(s, A_K, q_hat, scores, f, st);
+    case 7: return launch_fast<R, 7>(s, A_K, q_hat, scores, f, st);
+    case 8: return launch_fast<R, 8>(s, A_K, q_hat, scores, f, st);
     default: *handled = false; return hipSuccess;
   }
 }
@@ -363,15 +410,17 @@ void proxy_filter_time_next_launch(hipEvent_t start, hipEvent_t stop) {
 }
 
 hipError_t launch_proxy_scores_filter(const lrqk_shape& s, const float* A_K, const float* q_hat,
-                                      float* scores, const uint32_t* thr,
-                                      unsigned long long* bitmap, float* cand_scores,
-                                      hipStream_t st) {
+                                      float* scores, const uint32_t* thr, const float* thr_norm,
+                                      uint32_t* thr_out, unsigned long long* bitmap,
+                                      float* cand_scores, hipStream_t st) {
+  if ((thr == nullptr) == (thr_norm == nullptr) || !thr_out) return hipErrorInvalidValue;
+  const FilterOut f{thr, thr_norm, thr_out, bitmap, cand_scores};
   bool handled = false;
   hipError_t e = hipErrorInvalidValue;
   switch (s.r) {
-    case 16: e = dispatch_G<16>(s, A_K, q_hat, scores, thr, bitmap, cand_scores, st, &handled); break;
-    case 32: e = dispatch_G<32>(s, A_K, q_hat, scores, thr, bitmap, cand_scores, st, &handled); break;
-    case 64: e = dispatch_G<64>(s, A_K, q_hat, scores, thr, bitmap, cand_scores, st, &handled); break;
+    case 16: e = dispatch_G<16>(s, A_K, q_hat, scores, &f, st, &handled); break;
+    case 32: e = dispatch_G<32>(s, A_K, q_hat, scores, &f, st, &handled); break;
+    case 64: e = dispatch_G<64>(s, A_K, q_hat, scores, &f, st, &handled); break;
     default: break;
   }
   return handled ? e : hipErrorInvalidValue;
@@ -382,9 +431,9 @@ hipError_t launch_proxy_scores(const lrqk_shape& s, const float* A_K, const floa
   bool handled = false;
   hipError_t e = hipSuccess;
   switch (s.r) {
-    case 16: e = dispatch_G<16>(s, A_K, q_hat, scores, nullptr, nullptr, nullptr, st, &handled); break;
-    case 32: e = dispatch_G<32>(s, A_K, q_hat, scores, nullptr, nullptr, nullptr, st, &handled); break;
-    case 64: e = dispatch_G<64>(s, A_K, q_hat, scores, nullptr, nullptr, nullptr, st, &handled); break;
+    case 16: e = dispatch_G<16>(s, A_K, q_hat, scores, nullptr, st, &handled); break;
+    case 32: e = dispatch_G<32>(s, A_K, q_hat, scores, nullptr, st, &handled); break;
+    case 64: e = dispatch_G<64>(s, A_K, q_hat, scores, nullptr, st, &handled); break;
     default: break;
   }
   if (handled) return e;

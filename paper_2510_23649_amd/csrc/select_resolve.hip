@@ -39,83 +39,12 @@
 // scheduling.
 #include "lrqk_device.h"
 #include "lrqk_internal.h"
-
-#ifdef LRQK_KPROF
-__device__ unsigned long long g_kprof[16];
-#define KPROF(i)                                                          \
-  do {                                                                    \
-    if (blockIdx.x == 0 && threadIdx.x == 0) g_kprof[i] = wall_clock64(); \
-  } while (0)
-extern "C" __attribute__((visibility("default"))) int lrqk_kprof_read(unsigned long long* out) {
-  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_kprof), sizeof(g_kprof));
-}
-#else
-#define KPROF(i) \
-  do {           \
-  } while (0)
-#endif
+#include "select_common.h"
 
 namespace lrqk {
 namespace {
 
 using namespace dev;
-
-constexpr int kT = 1024;  // threads per workgroup
-constexpr int kWaves = kT / 64;
-constexpr int kIter = kT * 4;  // scores per workgroup iteration (one float4 per lane)
-constexpr int kBatch = 8;      // iterations whose loads are issued together
-constexpr int kAgeBins = 2048;
-constexpr int kSampleStride = 8;
-
-struct Keys4 {
-  uint32_t k[4];
-  bool ok[4];
-};
-struct Raw4 {
-  float v[4];
-};
-// Four consecutive scores starting at element e (e % 4 == 0); 0 beyond n.  Rows are
-// 16-byte aligned only if l % 4 == 0 (vec_ok).
-__device__ __forceinline__ Raw4 load_raw4(const float* __restrict__ s, int e, int n, bool vec_ok) {
-  Raw4 r;
-  if (vec_ok && e + 3 < n) {
-    const float4 x = *reinterpret_cast<const float4*>(s + e);
-    r.v[0] = x.x; r.v[1] = x.y; r.v[2] = x.z; r.v[3] = x.w;
-  } else {
-#pragma unroll
-    for (int c = 0; c < 4; ++c) r.v[c] = (e + c < n) ? s[e + c] : 0.0f;
-  }
-  return r;
-}
-__device__ __forceinline__ Keys4 keys_of(const Raw4& r, int e, int n) {
-  Keys4 q;
-#pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    q.ok[c] = e + c < n;
-    q.k[c] = q.ok[c] ? order_key(r.v[c]) : 0u;
-  }
-  return q;
-}
-
-template <typename T>
-__device__ __forceinline__ void bitonic_sort_lds(T* a, int n) {
-  for (int size = 2; size <= n; size <<= 1) {
-    for (int stride = size >> 1; stride > 0; stride >>= 1) {
-      __syncthreads();
-      for (int i = threadIdx.x; i < (n >> 1); i += kT) {
-        const int pos = 2 * i - (i & (stride - 1));
-        const int j = pos + stride;
-        const bool up = (pos & size) == 0;
-        const T x = a[pos], y = a[j];
-        if ((x > y) == up) {
-          a[pos] = y;
-          a[j] = x;
-        }
-      }
-    }
-  }
-  __syncthreads();
-}
 
 __host__ __device__ inline int cand_capacity(int k) {
   int c = 2 * k + 2048;
@@ -185,19 +114,6 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
     Arow = A_K + ((size_t)b * Hkv + kvh) * (size_t)lrows * r;
     qh = q_hat + (size_t)bh * r;
   }
-  // proxy score of one row: the same fused-multiply-add chain as the proxy-score kernels
-  auto score_of_row = [&](int row) -> float {
-    const float4* __restrict__ a4 = reinterpret_cast<const float4*>(Arow + (size_t)row * r);
-    float acc = 0.0f;
-    for (int c = 0; c < r / 4; ++c) {
-      const float4 a = a4[c];
-      acc = __builtin_fmaf(a.x, qh[4 * c + 0], acc);
-      acc = __builtin_fmaf(a.y, qh[4 * c + 1], acc);
-      acc = __builtin_fmaf(a.z, qh[4 * c + 2], acc);
-      acc = __builtin_fmaf(a.w, qh[4 * c + 3], acc);
-    }
-    return acc;
-  };
   const int n_iter = (n + kIter - 1) / kIter;
   const int words = (n + 31) / 32;
   const int wpt = (words + kT - 1) / kT;  // bitmap words per thread in the prefix counts
@@ -206,7 +122,6 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
     sh_nmiss = 0u;
     sh_bad = 0u;
   }
-  KPROF(0);
   if (ext_bitmap != nullptr) {
     // the proxy-score pass already marked the candidates of this head
     const uint32_t* __restrict__ eb = ext_bitmap + (size_t)bh * ext_words;
@@ -275,7 +190,6 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
   __syncthreads();
 
   }
-  KPROF(1);
   // ---- 3. candidates -> exact selection -----------------------------------------------------
   uint32_t m;
   {
@@ -304,7 +218,6 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
     }
   }
   __syncthreads();
-  KPROF(2);
   if (m >= (uint32_t)k && m <= (uint32_t)cap) {
     for (int i = t; i < kBins; i += kT) hist[i] = 0u;
     if (recompute) {
@@ -312,13 +225,12 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
           cand_scores + (size_t)bh * (size_t)(ext_words >> 1) * kCandPerGroup;
       for (uint32_t i = t; i < m; i += kT) {
         const uint32_t slot = ckey[i];
-        ckey[i] = order_key(slot != 0xffffffffu ? cs[slot] : score_of_row(clist[i]));
+        ckey[i] = order_key(slot != 0xffffffffu ? cs[slot] : proxy_score_of_row(Arow, qh, r, clist[i]));
       }
     } else {
       for (uint32_t i = t; i < m; i += kT) ckey[i] = order_key(s[clist[i]]);
     }
     __syncthreads();
-  KPROF(3);
     // exact key of the k-th largest candidate: digits [31:21], [20:10], [9:0]
     uint32_t prefix = 0, remaining = (uint32_t)k;
     uint32_t n_eq_total = 0;
@@ -341,7 +253,6 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
       n_eq_total = lh[res[0]];
       __syncthreads();
     }
-  KPROF(4);
     const uint32_t tau = prefix, need_eq = remaining;
     // candidates are in ascending position: take key > tau, and the first need_eq with key == tau
     const uint32_t per = (m + kT - 1) / kT;
@@ -375,107 +286,18 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
       }
   } else {
     // ---- safe route --------------------------------------------------------------------------
-#ifdef LRQK_KPROF
-    if (t == 0) atomicAdd(&g_kprof[15], 1ull);
-#endif
-    uint32_t bin, above;
     if (recompute) {
       // every score of this head is needed now: compute them into the score array
       float* sw = scores_w + (size_t)bh * l;
-      for (int row = t; row < n; row += kT) sw[row] = score_of_row(row);
+      for (int row = t; row < n; row += kT) sw[row] = proxy_score_of_row(Arow, qh, r, row);
       __threadfence_block();
       __syncthreads();
     }
-    // complete histogram
-    for (int i = t; i < kBins; i += kT) hist[i] = 0u;
-    __syncthreads();
-    for (int it0 = 0; it0 < n_iter; it0 += kBatch) {
-      Raw4 raw[kBatch];
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u) raw[u] = load_raw4(s, (it0 + u) * kIter + 4 * t, n, vec_ok);
-#pragma unroll
-      for (int u = 0; u < kBatch; ++u) {
-        const Keys4 q = keys_of(raw[u], (it0 + u) * kIter + 4 * t, n);
-#pragma unroll
-        for (int c = 0; c < 4; ++c)
-          if (q.ok[c]) atomicAdd(&hist[q.k[c] >> kBinShift], 1u);
-      }
-    }
-    __syncthreads();
-    find_from_top_4096(hist, (uint32_t)k, wave_tot, res, &bin, &above);
-    // refine the threshold inside the bin: two 10-bit levels over the low 20 key bits
-    uint32_t prefix = bin, remaining = (uint32_t)k - above;
-    int shift = kBinShift;
-    for (int level = 0; level < 2; ++level) {
-      for (int i = t; i < 2048; i += kT) hist[i] = 0u;
-      __syncthreads();
-      const int nshift = shift - 10;
-      for (int it0 = 0; it0 < n_iter; it0 += kBatch) {
-        Raw4 raw[kBatch];
-#pragma unroll
-        for (int u = 0; u < kBatch; ++u)
-          raw[u] = load_raw4(s, (it0 + u) * kIter + 4 * t, n, vec_ok);
-#pragma unroll
-        for (int u = 0; u < kBatch; ++u) {
-          const Keys4 q = keys_of(raw[u], (it0 + u) * kIter + 4 * t, n);
-#pragma unroll
-          for (int c = 0; c < 4; ++c)
-            if (q.ok[c] && (q.k[c] >> shift) == prefix)
-              atomicAdd(&hist[(q.k[c] >> nshift) & 1023u], 1u);
-        }
-      }
-      __syncthreads();
-      find_from_top(hist, remaining, wave_tot, res);
-      prefix = (prefix << 10) | res[0];
-      remaining -= res[1];
-      shift = nshift;
-      __syncthreads();
-    }
-    const uint32_t tau = prefix, need_eq = remaining;
-    // bitmap of the selection; positions with key == tau are counted in position order
-    uint32_t taken = 0;
-    for (int it = 0; it < n_iter; ++it) {
-      const int e = it * kIter + 4 * t;
-      const Keys4 q = keys_of(load_raw4(s, e, n, vec_ok), e, n);
-      uint32_t cnt = 0;
-#pragma unroll
-      for (int c = 0; c < 4; ++c) cnt += (q.ok[c] && q.k[c] == tau) ? 1u : 0u;
-      uint32_t tot;
-      uint32_t rank = taken + block_exclusive_scan(cnt, wave_tot, &tot);
-      uint32_t nib = 0;
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        if (!q.ok[c]) continue;
-        if (q.k[c] > tau) nib |= 1u << c;
-        if (q.k[c] == tau) {
-          if (rank < need_eq) nib |= 1u << c;
-          ++rank;
-        }
-      }
-      taken += tot;
-      const uint32_t word = or_reduce8(nib << (4 * (lane & 7)));
-      const int wi = e >> 5;
-      if ((lane & 7) == 0 && wi < words) bitmap[wi] = word;
-    }
-    __syncthreads();
-    uint32_t cnt = 0;
-    for (int j = 0; j < wpt; ++j)
-      if (t * wpt + j < words) cnt += (uint32_t)__popc(bitmap[t * wpt + j]);
-    uint32_t tot;
-    uint32_t off = block_exclusive_scan(cnt, wave_tot, &tot);
-    for (int j = 0; j < wpt; ++j) {
-      if (t * wpt + j >= words) break;
-      uint32_t wbits = bitmap[t * wpt + j];
-      while (wbits) {
-        const int bpos = __ffs((int)wbits) - 1;
-        wbits &= wbits - 1;
-        if (off < (uint32_t)k) sel[off] = (t * wpt + j) * 32 + bpos;
-        ++off;
-      }
-    }
+    uint32_t bin_unused;
+    exact_select_from_scores<true>(s, n, k, vec_ok, (uint32_t)k, hist, bitmap, sel, wave_tot, res,
+                             &bin_unused);
   }
   __syncthreads();
-  KPROF(5);
   for (int i = t; i < k; i += kT) sel_idx[(size_t)bh * k + i] = sel[i];
   if (!RESOLVE) return;
 
@@ -496,11 +318,9 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
   int32_t* const vsorted = reinterpret_cast<int32_t*>(vlist + kpad);  // [k] victims in rank order
 
   __syncthreads();  // the selection buffers are dead from here on
-  KPROF(6);
   for (int i = t; i < C; i += kT) lu_s[i] = lu[i];
   for (int i = t; i < kAgeBins; i += kT) ahist[i] = 0u;
   __syncthreads();
-  KPROF(7);
   {
     // thread t owns the selected positions [t*jp, (t+1)*jp) (jp <= 4): one prefix count
     // ranks all misses in position order
@@ -542,7 +362,6 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
     if (t == 0) sh_nmiss = tot;
     __syncthreads();
   }
-  KPROF(8);
   const int nm = (int)sh_nmiss;
   if (nm > 0) {
     // ages of the slots not used in this step; thread t owns slots [t*spt, (t+1)*spt)
@@ -553,7 +372,6 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
       if (u != step) atomicAdd(&ahist[min((uint32_t)(step - 1 - u), (uint32_t)(kAgeBins - 1))], 1u);
     }
     __syncthreads();
-  KPROF(9);
     find_from_top(ahist, (uint32_t)nm, wave_tot, res);
     const uint32_t Ta = res[0], c_older = res[1], n_elig = res[2];
     __syncthreads();
@@ -590,7 +408,6 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
         if (flags & (1u << (v - s0)))
           vlist[pos++] = (((uint64_t)(uint32_t)(lu_s[v] + 1)) << 32) | (uint32_t)v;
       __syncthreads();
-  KPROF(10);
       if (nv <= kT) {
         // rank every victim among the victims by direct comparison
         if (t < nv) {
@@ -620,7 +437,6 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
       nv = (int)min((uint32_t)nm, n_elig);
       sorted64 = vlist;
     }
-  KPROF(11);
     for (int j = t; j < nm; j += kT) {
       if (j >= nv) {  // ran out of victims (the caller reused `step`)
         atomicOr(&sh_bad, 1u);
@@ -637,14 +453,12 @@ __global__ __launch_bounds__(kT) void select_resolve_kernel(
       ms[j] = v;
     }
     __syncthreads();
-  KPROF(12);
     for (int j = t; j < k; j += kT) {
       const int32_t v = sel[j];
       if (v <= -2) ss[j] = ms[-(v + 2)];
     }
   }
   __syncthreads();
-  KPROF(13);
   if (t == 0) n_miss[bh] = sh_bad ? -1 : nm;
 }
 

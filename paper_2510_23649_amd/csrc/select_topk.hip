@@ -17,6 +17,7 @@
 // themselves; the result is the same, only slower.
 // Everything is integer work on keys, so the result does not depend on the
 // order in which workgroups or atomics run.
+#include "lrqk_device.h"
 #include "lrqk_internal.h"
 
 namespace lrqk {
@@ -26,12 +27,8 @@ constexpr int kSelThreads = 256;
 constexpr int kSelChunk = 4096;      // scores per workgroup in passes 1 and 2
 constexpr int kFinThreads = 1024;
 
-// Larger score <=> larger key.  -0.0f and +0.0f map to the same key.
-__device__ __forceinline__ uint32_t order_key(float s) {
-  uint32_t u = __float_as_uint(s);
-  if (u == 0x80000000u) u = 0u;
-  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
+using dev::bitonic_sort_lds;
+using dev::order_key;
 
 __device__ __forceinline__ uint32_t load_u32_coherent(const uint32_t* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -151,27 +148,6 @@ __global__ __launch_bounds__(kSelThreads) void select_collect_kernel(
       ++pc;
     }
   }
-}
-
-// In-LDS bitonic sort, ascending, n a power of two, all threads of the workgroup take part.
-template <typename T>
-__device__ __forceinline__ void bitonic_sort_lds(T* a, int n) {
-  for (int size = 2; size <= n; size <<= 1) {
-    for (int stride = size >> 1; stride > 0; stride >>= 1) {
-      __syncthreads();
-      for (int i = threadIdx.x; i < (n >> 1); i += blockDim.x) {
-        const int pos = 2 * i - (i & (stride - 1));
-        const int j = pos + stride;
-        const bool up = (pos & size) == 0;
-        const T x = a[pos], y = a[j];
-        if ((x > y) == up) {
-          a[pos] = y;
-          a[j] = x;
-        }
-      }
-    }
-  }
-  __syncthreads();
 }
 
 // Block-wide exclusive prefix of a 0/1 flag in thread order, plus the block total.

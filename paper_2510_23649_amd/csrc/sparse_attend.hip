@@ -24,13 +24,7 @@ namespace {
 
 constexpr int kAttThreads = 256;
 constexpr int kRowsPerPass = 16;  // 4 wavefronts x 4 row groups
-#ifndef LRQK_ATT_UNROLL
-#define LRQK_ATT_UNROLL 4
-#endif
-#ifndef LRQK_ATT_MIN_RPB
-#define LRQK_ATT_MIN_RPB (kRowsPerPass * kUnroll)
-#endif
-constexpr int kUnroll = LRQK_ATT_UNROLL;  // passes whose loads are in flight together
+constexpr int kUnroll = 4;  // passes whose loads are in flight together
 constexpr float kLog2e = 1.4426950408889634f;
 
 template <int CTRL>
@@ -345,7 +339,7 @@ __global__ __launch_bounds__(kCombThreads) void attend_combine_kernel(
 AttendGeom attend_geometry(int BHq, int k, int w) {
   const int rows = k + w;
   AttendGeom g;
-  g.rows_per_block = LRQK_ATT_MIN_RPB;
+  g.rows_per_block = kRowsPerPass * kUnroll;
   // fewer, larger workgroups once there are plenty of them
   while (g.rows_per_block < 512 && (long)ceil_div(rows, g.rows_per_block * 2) * BHq >= 2048)
     g.rows_per_block *= 2;

@@ -21,7 +21,9 @@ class LayerBuffers:
 
     A_K [B,Hkv,l,r] fp32 and K, V [B,Hkv,l,d] (bf16 or fp32) may live on any device;
     A_K is moved to the GPU, K and V into pinned host memory, the last w rows of K
-    and V (the lite tokens) are also kept on the GPU, as a ring (lite_ring).  The cache starts empty.
+    and V (the lite tokens) are also kept on the GPU, as a ring (lite_ring).  The cache starts
+    empty and the carried selection thresholds unknown (pass LRQK_SELECT_FRESH with the first
+    step of the layer).
     """
 
     def __init__(self, shape: L.Shape, A_K: torch.Tensor, K: torch.Tensor, V: torch.Tensor,
@@ -49,8 +51,10 @@ class LayerBuffers:
         self.last_used = torch.empty((B, Hq, C), **i32)
         self.cacheK = torch.zeros((B, Hq, C, d), dtype=K.dtype, device=device)
         self.cacheV = torch.zeros((B, Hq, C, d), dtype=K.dtype, device=device)
+        self.sel_thr = torch.empty((B, Hq), dtype=torch.float32, device=device)
         L.lrqk_cache_init(shape, self.slot_of, self.token_of, self.last_used)
+        L.lrqk_select_state_init(shape, self.sel_thr)
         self.struct = L.make_layer(A_K=self.A_K, K_host=self.K_host, V_host=self.V_host,
                                    liteK=self.liteK, liteV=self.liteV, slot_of=self.slot_of,
                                    token_of=self.token_of, last_used=self.last_used,
-                                   cacheK=self.cacheK, cacheV=self.cacheV)
+                                   cacheK=self.cacheK, cacheV=self.cacheV, sel_thr=self.sel_thr)

@@ -7,11 +7,19 @@ import numpy as np
 import torch
 
 import paper_2510_23649_amd as L
-from paper_2510_23649_amd.state import lite_ring
 from gen import as_numpy
 from oracle import lrqk_oracle as orc
 
 DEV = "cuda"
+
+
+def lite_ring(X: torch.Tensor, l: int, w: int) -> torch.Tensor:
+    """Rows of the positions [l-w, l) of X [B,Hkv,>=l,d] as the library keeps them: row j of the
+    result holds the position p of the window with p mod w == j."""
+    if w == 0:
+        return X[:, :, l:l, :]
+    row_of = {p % w: p for p in range(l - w, l)}      # position p sits at row p mod w
+    return X[:, :, torch.tensor([row_of[j] for j in range(w)]), :]
 
 
 def shape_of(cfg) -> L.Shape:
@@ -28,7 +36,8 @@ def workspace(nbytes: int) -> torch.Tensor:
 class DeviceLayer:
     """Device + pinned-host buffers of one layer, and the matching oracle-side copies."""
 
-    def __init__(self, cfg, data, identity: bool = False):
+    def __init__(self, cfg, data, identity: bool = False, carry: bool = True):
+        """carry: give the layer a carried-threshold array (lrqk_layer.sel_thr), set to unknown."""
         self.cfg = cfg
         B, Hq, Hkv, l, C, d, G = cfg.B, cfg.Hq, cfg.Hkv, cfg.l, cfg.C, cfg.d, cfg.G
         kvdt = data.K.dtype
@@ -44,6 +53,10 @@ class DeviceLayer:
         self.cacheV = torch.zeros((B, Hq, C, d), dtype=kvdt, device=DEV)
         self.shape = shape_of(cfg)
         L.lrqk_cache_init(self.shape, self.slot_of, self.token_of, self.last_used)
+        self.sel_thr = None
+        if carry:
+            self.sel_thr = torch.zeros((B, Hq), dtype=torch.float32, device=DEV)
+            L.lrqk_select_state_init(self.shape, self.sel_thr)
         # oracle side
         self.np = dict(A_K=as_numpy(data.A_K), K=as_numpy(data.K), V=as_numpy(data.V))
         self.ost = orc.CacheState(B, Hq, l, C)
@@ -69,7 +82,8 @@ class DeviceLayer:
         from paper_2510_23649_amd.binding import make_layer
         return make_layer(A_K=self.A_K, K_host=self.K_host, V_host=self.V_host, liteK=self.liteK,
                           liteV=self.liteV, slot_of=self.slot_of, token_of=self.token_of,
-                          last_used=self.last_used, cacheK=self.cacheK, cacheV=self.cacheV)
+                          last_used=self.last_used, cacheK=self.cacheK, cacheV=self.cacheV,
+                          sel_thr=self.sel_thr)
 
     def state_np(self):
         torch.cuda.synchronize()

@@ -238,10 +238,15 @@ def test_sparse_attend_closed_forms():
 
 # ------------------------------------------------------------------------------- a1..a5
 
-def run_steps_against_oracle(cfg, n_steps, mode, identity=False, data=None, check_unfused=True):
-    """Drive lrqk_decode_step for n_steps and compare every step with the oracle."""
+def run_steps_against_oracle(cfg, n_steps, mode, identity=False, data=None, check_unfused=True,
+                             carry="fresh_first"):
+    """Drive lrqk_decode_step for n_steps and compare every step with the oracle.
+    carry: how the selection's candidate thresholds are obtained -- "off": estimated from a sample
+    in every step (no lrqk_layer.sel_thr); "fresh_first": from a sample in the first step
+    (LRQK_SELECT_FRESH), carried from step to step afterwards; "unknown_first": carried, the first
+    step starting from unknown (NaN) thresholds, which sends every head down the exact route."""
     data = data or make_layer(cfg)
-    dl = DeviceLayer(cfg, data, identity=identity)
+    dl = DeviceLayer(cfg, data, identity=identity, carry=carry != "off")
     plan = L.Plan(dl.shape)
     lay = dl.struct()
     qs = QueryStream(data)
@@ -254,7 +259,9 @@ def run_steps_against_oracle(cfg, n_steps, mode, identity=False, data=None, chec
         qd, qhd = q.to(DEV), q_hat.to(DEV)
         if check_unfused and step == 1:
             unfused = run_unfused(cfg, dl, qd, qhd, step)      # on copies of the state
-        total = L.lrqk_decode_step(plan, dl.shape, step, lay, qhd, qd, out, fmode, sb.debug())
+        flags = L.LRQK_SELECT_FRESH if (carry == "fresh_first" and step == 1) else 0
+        total = L.lrqk_decode_step(plan, dl.shape, step, lay, qhd, qd, out, fmode | flags,
+                                   sb.debug())
         got = sb.to_np()
         ref = orc.decode_step(dl.np["A_K"], as_numpy(q_hat), as_numpy(q), dl.np["K"], dl.np["V"],
                               dl.ost, dl.ocK, dl.ocV, step, cfg.k, cfg.w, cfg.scale)
@@ -307,6 +314,46 @@ def test_decode_step_small(kvd, mode):
     say(f"decode_step small kv={kvd} mode={mode}")
     rates = run_steps_against_oracle(small_cfg(kv_dtype=kvd), 5, mode)
     assert rates[0] == 1.0 and rates[-1] < 1.0
+
+
+@pytest.mark.parametrize("carry", ["off", "unknown_first"])
+def test_decode_step_threshold_sources(carry):
+    say(f"decode_step small, candidate thresholds: {carry}")
+    run_steps_against_oracle(small_cfg(), 5, "direct", carry=carry, check_unfused=False)
+
+
+def test_decode_step_carried_threshold_survives_a_change_of_scale():
+    say("decode_step: the carried threshold meets scores 40x larger, then 1000x smaller")
+    cfg = small_cfg(B=1, Hq=8, Hkv=2, l=70000, r=32, k=1024, w=64, C=2048, n_heavy=64)
+    data = make_layer(cfg)
+    dl = DeviceLayer(cfg, data)
+    plan = L.Plan(dl.shape)
+    qs = QueryStream(data)
+    sb = StepBuffers(cfg)
+    out = torch.empty((cfg.B, cfg.Hq, cfg.d), device=DEV)
+    thr_seen = []
+    for step, factor in enumerate([1.0, 1.0, 40.0, 40.0, 0.04, 0.04, 1.0], start=1):
+        q, q_hat = qs.next()
+        # heads 0..3 keep their scale: only |q_hat| of heads 4..7 jumps, and with it (the carried
+        # value is per unit of |q_hat|) nothing should go wrong; A_K is then rescaled for real
+        q_hat = q_hat.clone()
+        q_hat[:, 4:] *= factor
+        if step == 5:
+            dl.A_K[:, 0] *= 0.001          # every score of KV head 0 shrinks: thresholds far too high
+            dl.np["A_K"] = dl.A_K.cpu().numpy()
+        flags = L.LRQK_SELECT_FRESH if step == 1 else 0
+        L.lrqk_decode_step(plan, dl.shape, step, dl.struct(), q_hat.to(DEV), q.to(DEV), out,
+                           L.LRQK_FETCH_DIRECT | flags, sb.debug())
+        got = sb.to_np()
+        ref = orc.decode_step(dl.np["A_K"], as_numpy(q_hat), as_numpy(q), dl.np["K"], dl.np["V"],
+                              dl.ost, dl.ocK, dl.ocV, step, cfg.k, cfg.w, cfg.scale)
+        assert np.array_equal(got["sel_idx"], ref["sel_idx"]), f"step {step}: selection differs"
+        compare_resolution(got, ref, f"step {step}")
+        compare_state(dl, f"step {step}")
+        assert np.abs(out.cpu().numpy() - ref["out"]).max() <= TOL[cfg.kv_dtype]
+        thr_seen.append(dl.sel_thr.cpu().numpy().copy())
+    assert all(np.isfinite(t).all() for t in thr_seen)
+    plan.close()
 
 
 @pytest.mark.parametrize("mode", ["staged", "direct"])
@@ -368,10 +415,11 @@ def test_config2_shape(mode):
     run_steps_against_oracle(get_config("c2"), 4, mode, check_unfused=False)
 
 
+@pytest.mark.parametrize("mode", ["staged", "direct"])
 @pytest.mark.parametrize("r", [16, 32, 64])
-def test_config3_one_layer_full_size(r):
-    say(f"config 3, one layer at full size: l=131072 k=2048 w=64 C=4096 r={r}")
-    run_steps_against_oracle(get_config("c3", r=r, layers=1), 3, "staged", check_unfused=False)
+def test_config3_one_layer_full_size(r, mode):
+    say(f"config 3, one layer at full size: l=131072 k=2048 w=64 C=4096 r={r} ({mode})")
+    run_steps_against_oracle(get_config("c3", r=r, layers=1), 3, mode, check_unfused=False)
 
 
 def test_config4_qwen_shape_reduced_batch():

@@ -194,7 +194,7 @@ def run_alg2_growing(cfg, n_new, mode, lam1=1.0, lam2=1.0):
     paper's fp32), so rounding differences of the fp32 algebra are measured, never amplified
     into a different selection."""
     from oracle import lrqk_oracle as orc
-    from paper_2510_23649_amd.state import lite_ring
+    from gpu_harness import lite_ring
     from gpu_harness import compare_resolution
     l_cap = cfg.l + n_new
     data = make_layer(cfg)
