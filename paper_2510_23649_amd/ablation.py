@@ -66,7 +66,8 @@ def miss_rate_grid(steps: int, warm: int, drift: float, out=sys.stdout):
                 for step in range(1, warm + steps + 1):
                     q, q_hat = qs.next()
                     L.lrqk_decode_step(plan, shape, step, lb.struct, q_hat, q, out_t,
-                                       L.LRQK_FETCH_DIRECT, dict(n_miss=n_miss))
+                                       L.LRQK_FETCH_DIRECT | (L.LRQK_SELECT_FRESH if step == 1 else 0),
+                                       dict(n_miss=n_miss))
                     if step > warm:
                         rates.append(n_miss.clamp(min=0).sum().item() / (cfg.B * cfg.Hq * k))
                 plan.close()
@@ -110,7 +111,8 @@ def no_hit_miss(steps: int, layers: int, out=sys.stdout):
                 L.lrqk_cache_init(shape, lb.slot_of, lb.token_of, lb.last_used)
             step_no[li] += 1
             L.lrqk_decode_step(plan, shape, step_no[li], lb.struct, qs[i][1], qs[i][0], out_t,
-                               L.LRQK_FETCH_DIRECT, None if timed else dict(n_miss=n_miss))
+                               L.LRQK_FETCH_DIRECT | (L.LRQK_SELECT_FRESH if step_no[li] == 1 else 0),
+                               None if timed else dict(n_miss=n_miss))
             if not timed:
                 fetched += n_miss.clamp(min=0).sum().item()
         torch.cuda.synchronize()
@@ -190,7 +192,8 @@ def end_to_end(steps: int, out=sys.stdout):
         Kall[:, :, lcur], Vall[:, :, lcur] = k_new.float(), v_new.float()
         lcur += 1
         L.lrqk_decode_step(plan, shape.with_l(lcur), t, lb.struct, q_hat, q, out_t,
-                           L.LRQK_FETCH_DIRECT, dict(sel_idx=sel_idx, sel_slot=sel_slot))
+                           L.LRQK_FETCH_DIRECT | (L.LRQK_SELECT_FRESH if t == 1 else 0),
+                           dict(sel_idx=sel_idx, sel_slot=sel_slot))
         # evaluation: exact scores, exact top-k over [0, l - w), dense attention
         Krep = Kall[:, :, :lcur].repeat_interleave(G, dim=1)
         Vrep = Vall[:, :, :lcur].repeat_interleave(G, dim=1)
