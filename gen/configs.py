@@ -36,6 +36,9 @@ class WorkloadConfig:
     gamma: float = math.sqrt(128.0)  # size of the planted component of the query
     rho: float = 0.95            # AR(1) correlation of the background query across steps
     noise: float = 0.05          # full-rank residual added to A_K B
+    group_share: float = 0.0     # how much the query heads of a KV group want the same tokens:
+                                 # shared fraction of the heavy-token pools and of the
+                                 # background query (see gen/workload.py)
     prefill: str = "warm"        # "identity": slot i holds token i (needs C == l); "warm": run steps
     seed: int = 20251023
 

@@ -14,6 +14,12 @@ Recipe (all draws from torch generators seeded from (config seed, layer, purpose
   that its rank-r image has gamma * (cos, sin) on the head's plane.  Pool tokens
   whose phase is near theta_t get the largest scores; theta_t advances a
   fraction of the heavy window per step (drift) or jumps (re-draw).
+* group_share = s > 0 makes the query heads of a KV group want some of the same tokens at the
+  same steps: that fraction of every head's pool sits at the positions of the first head's
+  pool (same phases) on the first head's plane, the group's queries share their phase and
+  that plane, and the background queries of
+  the group share a component (sqrt(s) of a draw per KV head + sqrt(1 - s) of the head's own).
+  With 0 (the workloads' default) every head owns its heavy tokens and its query.
 * q_hat = q B^T: the lambda = 0 closed form of the paper's decode update
   when B_K = B and B_Q is its dual basis.  It is an *input* of the hot path.
 
@@ -77,7 +83,10 @@ class LayerData:
 
 
 def _plane(cfg: WorkloadConfig, hg: int):
-    """Coordinates of R^r spanned by the plane of the hg-th query head of a group."""
+    """Coordinates of R^r spanned by the plane of the hg-th query head of a group (with
+    group_share > 0 the whole group looks for its heavy tokens on the first head's plane)."""
+    if cfg.group_share > 0.0:
+        hg = 0
     return (2 * hg) % cfg.r, (2 * hg + 1) % cfg.r
 
 
@@ -96,11 +105,20 @@ def make_layer(cfg: WorkloadConfig, layer: int = 0, device="cpu") -> LayerData:
     # pool positions: one permutation of [0, l-w) per (batch, KV head), cut into G pools
     gp = _gen("cpu", cfg.seed, layer, 3)
     pool_pos = torch.empty(B, Hq, P, dtype=torch.int64)
+    n_shared = int(round(cfg.group_share * P))   # pool entries that a head shares with head 0
+    shared_idx = [[None] * Hkv for _ in range(B)]
     for b in range(B):
         for kv in range(Hkv):
             perm = torch.randperm(l - cfg.w, generator=gp)[: G * P]
             for hg in range(G):
                 pool_pos[b, kv * G + hg] = perm[hg * P:(hg + 1) * P]
+            if n_shared > 0:
+                # the same pool indices (hence phases) for every head of the group, so that the
+                # heads want those tokens at the same steps
+                shared = torch.randperm(P, generator=gp)[:n_shared]
+                shared_idx[b][kv] = shared
+                for hg in range(1, G):
+                    pool_pos[b, kv * G + hg, shared] = pool_pos[b, kv * G, shared]
     pool_phase = cfg.phase_spread * 2.0 * math.pi * torch.arange(P, dtype=torch.float64) / P
 
     # plant the pools in factor space
@@ -112,8 +130,14 @@ def make_layer(cfg: WorkloadConfig, layer: int = 0, device="cpu") -> LayerData:
         for b in range(B):
             for kv in range(Hkv):
                 pos = pp[b, kv * G + hg]
-                A_K[b, kv, pos, c1] += cosp
-                A_K[b, kv, pos, c2] += sinp
+                if hg > 0 and n_shared > 0:      # shared entries were planted with the first head
+                    own = torch.ones(P, dtype=torch.bool, device=dev)
+                    own[shared_idx[b][kv].to(dev)] = False
+                    A_K[b, kv, pos[own], c1] += cosp[own]
+                    A_K[b, kv, pos[own], c2] += sinp[own]
+                else:
+                    A_K[b, kv, pos, c1] += cosp
+                    A_K[b, kv, pos, c2] += sinp
 
     gk = _gen(dev, cfg.seed, layer, 4)
     gv = _gen(dev, cfg.seed, layer, 5)
@@ -140,10 +164,11 @@ class QueryStream:
         c = self.cfg
         self._g = _gen(self.dev, c.seed, data.layer, 6)
         self._gth = _gen("cpu", c.seed, data.layer, 7)
-        self._bg = torch.randn(c.B, c.Hq, c.d, generator=self._g, device=self.dev,
-                               dtype=torch.float32)
+        self._bg = self._draw_background()
         self._theta0 = 2.0 * math.pi * torch.rand(c.B, c.Hq, generator=self._gth,
                                                   dtype=torch.float64) * c.phase_spread
+        if c.group_share > 0.0:      # the heads of a KV group move through their pools together
+            self._theta0 = self._theta0[:, ::c.G].repeat_interleave(c.G, dim=1)
         # planted directions b1, b2 per query head
         G = c.G
         b1 = torch.empty(c.B, c.Hq, c.d, dtype=torch.float32, device=self.dev)
@@ -156,6 +181,17 @@ class QueryStream:
             b1[:, h] = r1 / (r1 * r1).sum(-1, keepdim=True)
             b2[:, h] = r2 / (r2 * r2).sum(-1, keepdim=True)
         self._b1, self._b2, self._Bm = b1, b2, Bm
+
+    def _draw_background(self) -> torch.Tensor:
+        """N(0,1) per query head; with group_share = s > 0 the heads of a KV group share a
+        component: sqrt(s) * (one draw per KV head) + sqrt(1 - s) * (one draw per head)."""
+        c = self.cfg
+        own = torch.randn(c.B, c.Hq, c.d, generator=self._g, device=self.dev, dtype=torch.float32)
+        if c.group_share <= 0.0:
+            return own
+        grp = torch.randn(c.B, c.Hkv, c.d, generator=self._g, device=self.dev,
+                          dtype=torch.float32).repeat_interleave(c.G, dim=1)
+        return math.sqrt(c.group_share) * grp + math.sqrt(1.0 - c.group_share) * own
 
     def theta(self) -> torch.Tensor:
         """Current phase of the planted query component, [B,Hq] fp64."""
@@ -172,8 +208,7 @@ class QueryStream:
     def next(self):
         c = self.cfg
         if self.t > 0:
-            eps = torch.randn(c.B, c.Hq, c.d, generator=self._g, device=self.dev,
-                              dtype=torch.float32)
+            eps = self._draw_background()
             self._bg = c.rho * self._bg + math.sqrt(max(0.0, 1.0 - c.rho * c.rho)) * eps
         th = self.theta()
         ct = (c.gamma * torch.cos(th)).to(torch.float32).to(self.dev)[..., None]

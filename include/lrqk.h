@@ -399,18 +399,27 @@ int lrqk_prefill_factorize(const lrqk_shape* shape, const void* Q, const void* K
                            int32_t n_iter, void* workspace, size_t ws_bytes, void* stream);
 
 /*
- * Instrumentation (not part of the method): per-phase GPU time of lrqk_decode_step,
- * taken with HIP events recorded on the caller's stream around each phase.
- * lrqk_plan_profile(plan, n) arms the next n calls of lrqk_decode_step on this plan
- * (n = 0 switches it off); lrqk_plan_profile_read waits for the recorded steps, adds
- * up the time between consecutive marks into ms_sum[LRQK_PROFILE_MARKS - 1]
- * (milliseconds, summed over steps) and re-arms.  Intervals, in order:
- *   0 sampled threshold estimate (0 when the shape does not use it) | 1 proxy-score pass |
- *   2 selection (with the resolution when both run in one launch) | 3 separate resolution |
- *   4 fetch kernel (DIRECT) or miss-list copy + host synchronisation (STAGED) |
- *   5 attention partials (STAGED: includes the wait for the side-stream copy) | 6 merge
+ * Instrumentation (not part of the method): GPU time of the kernels of lrqk_decode_step, each
+ * taken from a pair of HIP events attached to the kernel itself (they hold its own start and
+ * end, so neither the gaps between launches nor the events' own cost are included).
+ * lrqk_plan_profile(plan, n) arms the next n calls of lrqk_decode_step on this plan (n = 0
+ * switches it off); lrqk_plan_profile_read waits for the recorded steps, adds up every
+ * slot's kernel time into ms_sum[LRQK_PROFILE_SLOTS] (milliseconds, summed over the steps;
+ * 0 for kernels the steps did not launch) and re-arms.  Slots:
  */
-#define LRQK_PROFILE_MARKS 8
+enum {
+  LRQK_SLOT_SAMPLE = 0,      /* threshold estimate: scores of the sampled rows          */
+  LRQK_SLOT_THRESHOLD = 1,   /* threshold estimate: histogram of the samples            */
+  LRQK_SLOT_PROXY = 2,       /* a1, the pass over A_K                                   */
+  LRQK_SLOT_SELECT = 3,      /* a2 (+ a3 where one kernel does both; of the multi-launch
+                                selection of very long contexts only the first kernel)  */
+  LRQK_SLOT_RESOLVE = 4,     /* a3 as a kernel of its own                               */
+  LRQK_SLOT_FETCH = 5,       /* STAGED: scatter of the copied rows into the cache slots */
+  LRQK_SLOT_ATTEND = 6,      /* a5 partials (DIRECT: with the fetch; STAGED: hit rows)  */
+  LRQK_SLOT_ATTEND_MISS = 7, /* STAGED: a5 partials over the rows that were fetched     */
+  LRQK_SLOT_COMBINE = 8,     /* a5 merge of the partials                                */
+  LRQK_PROFILE_SLOTS = 9
+};
 int lrqk_plan_profile(lrqk_plan* plan, int n_steps);
 int lrqk_plan_profile_read(lrqk_plan* plan, double* ms_sum, int* n_steps_out);
 

@@ -131,6 +131,40 @@ def fetch(K_store, V_store, miss_tok, miss_slot, n_miss, cacheK, cacheV):
                        _p(miss_slot), _p(n_miss), _p(cacheK), _p(cacheV))
 
 
+def group_fetch(K_store, V_store, miss_tok, miss_slot, n_miss, cacheK, cacheV):
+    """Alg. 2 fetch + merge with the host link shared inside a KV group.  K and V are stored
+    once per KV head and the paper aligns heads by repeating them (Sec. 4, preliminaries), so a
+    position that several query heads of one group miss in the same step is the SAME host row:
+    it is read from the store once and written into the slot each of those heads gave it.
+    The caches end up exactly as with `fetch`; what changes is the number of rows that cross
+    the link: the size of the union of the group's miss lists instead of their total length
+    (Sec. 5.3 counts fetched rows; this is the count per KV head).
+
+    Plain loops over (batch, KV head), positions in ascending order.  Updates cacheK, cacheV in
+    place.  Returns (link_rows int64 [B,Hkv], union: list over (b, kv) of the sorted positions)."""
+    B, Hkv, l, d = K_store.shape
+    Hq = cacheK.shape[1]
+    G = Hq // Hkv
+    assert Hq == G * Hkv and cacheK.shape == cacheV.shape and cacheK.dtype == K_store.dtype
+    link_rows = np.zeros((B, Hkv), np.int64)
+    union = []
+    for b in range(B):
+        for kv in range(Hkv):
+            wanted = {}                              # position -> [(head, slot), ...]
+            for h in range(kv * G, (kv + 1) * G):
+                for j in range(max(int(n_miss[b, h]), 0)):
+                    wanted.setdefault(int(miss_tok[b, h, j]), []).append((h, int(miss_slot[b, h, j])))
+            positions = sorted(wanted)
+            for pos in positions:
+                k_row, v_row = K_store[b, kv, pos].copy(), V_store[b, kv, pos].copy()  # one read
+                for h, slot in wanted[pos]:
+                    cacheK[b, h, slot] = k_row
+                    cacheV[b, h, slot] = v_row
+            link_rows[b, kv] = len(positions)
+            union.append(np.array(positions, np.int64))
+    return link_rows, union
+
+
 def sparse_attend(q, cacheK, cacheV, sel_slot, liteK, liteV, scale: float) -> np.ndarray:
     """Sec. 4.3 attention over the k cache rows + w lite rows. float64 [B,Hq,d]."""
     B, Hq, d = q.shape

@@ -263,20 +263,20 @@ class Plan:
         _check(load_library().lrqk_plan_create(C.byref(max_shape), C.byref(h)), "lrqk_plan_create")
         self.handle = h
 
-    PHASES = ("threshold_estimate", "proxy_scores", "select_and_resolve", "separate_resolve",
-              "fetch_or_sync", "attend", "combine")
+    KERNELS = ("sample", "threshold", "proxy_scores", "select", "resolve", "fetch_scatter",
+               "attend", "attend_missed_rows", "combine")
 
     def profile(self, n_steps: int):
-        """lrqk_plan_profile: time the phases of the next n_steps fused steps (0 = off)."""
+        """lrqk_plan_profile: time the kernels of the next n_steps fused steps (0 = off)."""
         _check(load_library().lrqk_plan_profile(self.handle, int(n_steps)), "lrqk_plan_profile")
 
     def profile_read(self):
-        """lrqk_plan_profile_read -> (dict phase -> summed ms, number of steps)."""
-        ms = (C.c_double * 7)()
+        """lrqk_plan_profile_read -> (dict kernel slot -> summed ms, number of steps)."""
+        ms = (C.c_double * len(self.KERNELS))()
         n = C.c_int(0)
         _check(load_library().lrqk_plan_profile_read(self.handle, ms, C.byref(n)),
                "lrqk_plan_profile_read")
-        return dict(zip(self.PHASES, list(ms))), n.value
+        return dict(zip(self.KERNELS, list(ms))), n.value
 
     def time_proxy_pass(self, shape, A_K_list, q_hat, n_launches, sel_thr=None,
                         stream=None) -> float:

@@ -18,6 +18,11 @@ namespace lrqk {
 
 static thread_local int g_last_hip_error = 0;
 
+LaunchTimer& launch_timer() {
+  static thread_local LaunchTimer t;
+  return t;
+}
+
 int record_hip_error(hipError_t e) {
   g_last_hip_error = static_cast<int>(e);
   (void)hipGetLastError();  // clear the sticky slot so later calls report their own errors
@@ -136,27 +141,40 @@ struct lrqk_plan {
   size_t stage_rows;
   hipStream_t side;
   hipEvent_t ev_main, ev_side;
-  // optional per-phase timing of lrqk_decode_step (lrqk_plan_profile)
+  // optional per-kernel timing of lrqk_decode_step (lrqk_plan_profile)
   int prof_cap, prof_n;
-  hipEvent_t* prof_ev;  // [prof_cap][LRQK_PROFILE_MARKS]
+  hipEvent_t* prof_ev;   // [prof_cap][LRQK_PROFILE_SLOTS][start, stop]
+  unsigned* prof_used;   // [prof_cap] bit i: slot i was recorded in that step
   HostPool* pool;       // host threads of the staged fetch (created on first use)
   int64_t* h_rowbase;   // [BHq + 1] first staging row of each head (host, not pinned)
 };
 
 static void prof_free(lrqk_plan* p) {
   if (p->prof_ev) {
-    for (int i = 0; i < p->prof_cap * LRQK_PROFILE_MARKS; ++i)
+    for (int i = 0; i < p->prof_cap * LRQK_PROFILE_SLOTS * 2; ++i)
       if (p->prof_ev[i]) (void)hipEventDestroy(p->prof_ev[i]);
     std::free(p->prof_ev);
   }
+  std::free(p->prof_used);
   p->prof_ev = nullptr;
+  p->prof_used = nullptr;
   p->prof_cap = p->prof_n = 0;
 }
 
-// Record mark `m` of the current profiled step, if profiling is on and a slot is left.
-static inline hipError_t prof_mark(lrqk_plan* p, int m, hipStream_t st) {
-  if (!p->prof_ev || p->prof_n >= p->prof_cap) return hipSuccess;
-  return hipEventRecord(p->prof_ev[p->prof_n * LRQK_PROFILE_MARKS + m], st);
+// The next `count` kernels launched by this thread go to the slots slot, slot + 1, ... of the
+// current profiled step (nothing happens when profiling is off or no step is left).
+static inline void prof_arm(lrqk_plan* p, int slot, int count) {
+  LaunchTimer& t = launch_timer();
+  t = LaunchTimer{};
+  if (!p->prof_ev || p->prof_n >= p->prof_cap) return;
+  t.ev = p->prof_ev + ((size_t)p->prof_n * LRQK_PROFILE_SLOTS + slot) * 2;
+  t.pairs_left = count;
+  t.recorded = p->prof_used + p->prof_n;
+  t.next = slot;
+}
+static inline void prof_step_done(lrqk_plan* p) {
+  launch_timer() = LaunchTimer{};
+  if (p->prof_ev && p->prof_n < p->prof_cap) ++p->prof_n;
 }
 
 extern "C" {
@@ -556,7 +574,7 @@ int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
   if (!all_aligned16({sel_idx, sel_slot, hit, miss_tok, miss_slot, n_miss})) return LRQK_EINVAL;
 
   const SelectWs ws = carve_select_ws(plan->select_ws, BHq, s.k);
-  LRQK_HIP(prof_mark(plan, 0, st));
+  if (plan->prof_ev && plan->prof_n < plan->prof_cap) plan->prof_used[plan->prof_n] = 0u;
   const bool packed = select_packed_fits(s) && proxy_filter_supported(s);
   const bool one_wg = packed || select_resolve_fits(s, true);
   const bool filtered = one_wg && proxy_filter_supported(s);
@@ -565,79 +583,83 @@ int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
     // sample of this step's scores; then one pass over A_K that leaves only the candidate
     // bitmap and the candidates' scores
     const bool fresh = !packed || !L->sel_thr || (mode_flags & LRQK_SELECT_FRESH);
-    if (fresh) LRQK_HIP(launch_proxy_threshold(s, L->A_K, q_hat, plan->samples, plan->thr, st));
-    LRQK_HIP(prof_mark(plan, 1, st));
+    if (fresh) {
+      prof_arm(plan, LRQK_SLOT_SAMPLE, 2);
+      LRQK_HIP(launch_proxy_threshold(s, L->A_K, q_hat, plan->samples, plan->thr, st));
+    }
+    prof_arm(plan, LRQK_SLOT_PROXY, 1);
     LRQK_HIP(launch_proxy_scores_filter(s, L->A_K, q_hat, plan->scores,
                                         fresh ? plan->thr : nullptr, fresh ? nullptr : L->sel_thr,
                                         plan->thr_used, plan->filter, plan->cand_scores, st));
   } else {
-    LRQK_HIP(prof_mark(plan, 1, st));
+    prof_arm(plan, LRQK_SLOT_PROXY, 1);
     LRQK_HIP(launch_proxy_scores(s, L->A_K, q_hat, plan->scores, st));
   }
-  LRQK_HIP(prof_mark(plan, 2, st));
+  prof_arm(plan, LRQK_SLOT_SELECT, 1);
   if (packed) {
-    // selection and resolution in one launch; the profile books it all under "selection"
+    // selection and resolution in one launch
     LRQK_HIP(launch_select_packed(s, plan->filter, plan->cand_scores, plan->thr_used, L->A_K,
                                   q_hat, plan->scores, L->sel_thr, sel_idx, step, L->slot_of,
                                   L->token_of, L->last_used, sel_slot, hit, miss_tok, miss_slot,
                                   n_miss, st));
-    LRQK_HIP(prof_mark(plan, 3, st));
   } else if (one_wg) {
-    // selection and resolution in one launch; the profile books it all under "selection"
     LRQK_HIP(launch_select_resolve(s, plan->scores, filtered ? plan->filter : nullptr,
                                    plan->cand_scores, L->A_K, q_hat, sel_idx, step, L->slot_of,
                                    L->token_of, L->last_used, sel_slot, hit, miss_tok, miss_slot,
                                    n_miss, st));
-    LRQK_HIP(prof_mark(plan, 3, st));
   } else {
+    // several launches; only the first is timed when profiling
     LRQK_HIP(launch_select_topk(s, plan->scores, sel_idx, ws, st));
-    LRQK_HIP(prof_mark(plan, 3, st));
+    prof_arm(plan, LRQK_SLOT_RESOLVE, 1);
     LRQK_HIP(launch_cache_resolve(s, sel_idx, step, L->slot_of, L->token_of, L->last_used,
                                   sel_slot, hit, miss_tok, miss_slot, n_miss, st));
   }
-  LRQK_HIP(prof_mark(plan, 4, st));
   const AttendGeom g = attend_geometry(BHq, s.k, s.w);
   const int parts_per_head = g.nsplit + ceil_div(s.k, g.rows_per_block);
 
   if (mode == LRQK_FETCH_DIRECT) {
     // fetch and attention in one kernel: a row that missed is read from the pinned host store,
     // used, and written into its slot, while the other rows stream from HBM
-    LRQK_HIP(prof_mark(plan, 5, st));
+    prof_arm(plan, LRQK_SLOT_ATTEND, 1);
     LRQK_HIP(launch_attend_partial(s, kAttendAllFetch, q, L->cacheK, L->cacheV, sel_slot, hit,
                                    nullptr, nullptr, L->liteK, L->liteV, plan->partials, g.nsplit,
                                    g.rows_per_block, parts_per_head, 0, st, L->K_host, L->V_host,
                                    sel_idx));
-    LRQK_HIP(prof_mark(plan, 6, st));
+    prof_arm(plan, LRQK_SLOT_COMBINE, 1);
     LRQK_HIP(launch_attend_combine(s, plan->partials, parts_per_head, g.nsplit, out, st));
-    LRQK_HIP(prof_mark(plan, 7, st));
-    if (plan->prof_ev && plan->prof_n < plan->prof_cap) ++plan->prof_n;
+    prof_step_done(plan);
     if (total_miss_out) *total_miss_out = -1;
     return LRQK_OK;
   }
 
   // STAGED: bring the miss list to the host (the one synchronisation of the step) ...
+  launch_timer() = LaunchTimer{};
   const size_t nb = (size_t)BHq;
   LRQK_HIP(hipMemcpyAsync(plan->h_nmiss, n_miss, nb * 4, hipMemcpyDeviceToHost, st));
   LRQK_HIP(hipMemcpyAsync(plan->h_miss_tok, miss_tok, nb * s.k * 4, hipMemcpyDeviceToHost, st));
   LRQK_HIP(hipMemcpyAsync(plan->h_miss_slot, miss_slot, nb * s.k * 4, hipMemcpyDeviceToHost, st));
   LRQK_HIP(hipStreamSynchronize(st));
-  LRQK_HIP(prof_mark(plan, 5, st));
   // ... attend the rows already resident and the lite rows while the host packs the misses
+  prof_arm(plan, LRQK_SLOT_ATTEND, 1);
   LRQK_HIP(launch_attend_partial(s, kAttendHitsAndLite, q, L->cacheK, L->cacheV, sel_slot, hit,
                                  nullptr, nullptr, L->liteK, L->liteV, plan->partials, g.nsplit,
                                  g.rows_per_block, parts_per_head, 0, st));
   int max_nmiss = 0;
+  prof_arm(plan, LRQK_SLOT_FETCH, 1);   // the scatter kernel on the side stream
   rc = staged_fetch(plan, s, L->K_host, L->V_host, miss_tok, miss_slot, n_miss, L->cacheK,
                     L->cacheV, st, false, total_miss_out, &max_nmiss);
-  if (rc != LRQK_OK) return rc;
+  if (rc != LRQK_OK) {
+    launch_timer() = LaunchTimer{};
+    return rc;
+  }
   const int nblk_miss = ceil_div(max_nmiss, g.rows_per_block);
+  prof_arm(plan, LRQK_SLOT_ATTEND_MISS, 1);
   LRQK_HIP(launch_attend_partial(s, kAttendMisses, q, L->cacheK, L->cacheV, sel_slot, hit,
                                  miss_slot, n_miss, L->liteK, L->liteV, plan->partials, nblk_miss,
                                  g.rows_per_block, parts_per_head, g.nsplit, st));
-  LRQK_HIP(prof_mark(plan, 6, st));
+  prof_arm(plan, LRQK_SLOT_COMBINE, 1);
   LRQK_HIP(launch_attend_combine(s, plan->partials, parts_per_head, g.nsplit + nblk_miss, out, st));
-  LRQK_HIP(prof_mark(plan, 7, st));
-  if (plan->prof_ev && plan->prof_n < plan->prof_cap) ++plan->prof_n;
+  prof_step_done(plan);
   return LRQK_OK;
 }
 
@@ -694,10 +716,13 @@ int lrqk_plan_time_proxy_pass(lrqk_plan* plan, const lrqk_shape* shape,
   e = hipSuccess;
   for (int i = 0; i < 2 * n2 && e == hipSuccess; ++i) e = hipEventCreate(&ev[i]);
   for (int i = 0; i < n2 && e == hipSuccess; ++i) {
-    proxy_filter_time_next_launch(ev[2 * i], ev[2 * i + 1]);
+    LaunchTimer& lt = launch_timer();
+    lt = LaunchTimer{};
+    lt.ev = &ev[2 * i];
+    lt.pairs_left = 1;
     e = pass(A_K_list[i % n_list]);
   }
-  proxy_filter_time_next_launch(nullptr, nullptr);
+  launch_timer() = LaunchTimer{};
   if (e == hipSuccess) e = hipStreamSynchronize(st);
   double sum_us = 0.0;
   for (int i = 0; i < n2 && e == hipSuccess; ++i) {
@@ -720,24 +745,35 @@ int lrqk_plan_profile(lrqk_plan* plan, int n_steps) {
   if (!plan || n_steps < 0 || n_steps > 65536) return LRQK_EINVAL;
   prof_free(plan);
   if (n_steps == 0) return LRQK_OK;
-  const size_t n = (size_t)n_steps * LRQK_PROFILE_MARKS;
+  const size_t n = (size_t)n_steps * LRQK_PROFILE_SLOTS * 2;
   plan->prof_ev = static_cast<hipEvent_t*>(std::calloc(n, sizeof(hipEvent_t)));
-  if (!plan->prof_ev) return LRQK_ENOMEM;
+  plan->prof_used = static_cast<unsigned*>(std::calloc((size_t)n_steps, sizeof(unsigned)));
+  if (!plan->prof_ev || !plan->prof_used) {
+    prof_free(plan);
+    return LRQK_ENOMEM;
+  }
   plan->prof_cap = n_steps;
-  for (size_t i = 0; i < n; ++i) LRQK_HIP(hipEventCreate(&plan->prof_ev[i]));
+  for (size_t i = 0; i < n; ++i) {
+    const hipError_t e = hipEventCreate(&plan->prof_ev[i]);
+    if (e != hipSuccess) {
+      prof_free(plan);
+      return record_hip_error(e);
+    }
+  }
   return LRQK_OK;
 }
 
 int lrqk_plan_profile_read(lrqk_plan* plan, double* ms_sum, int* n_steps_out) {
   if (!plan || !ms_sum || !n_steps_out) return LRQK_EINVAL;
-  for (int m = 0; m < LRQK_PROFILE_MARKS - 1; ++m) ms_sum[m] = 0.0;
+  for (int m = 0; m < LRQK_PROFILE_SLOTS; ++m) ms_sum[m] = 0.0;
   *n_steps_out = plan->prof_n;
   for (int i = 0; i < plan->prof_n; ++i) {
-    hipEvent_t* ev = plan->prof_ev + (size_t)i * LRQK_PROFILE_MARKS;
-    LRQK_HIP(hipEventSynchronize(ev[LRQK_PROFILE_MARKS - 1]));
-    for (int m = 0; m < LRQK_PROFILE_MARKS - 1; ++m) {
+    hipEvent_t* ev = plan->prof_ev + (size_t)i * LRQK_PROFILE_SLOTS * 2;
+    for (int m = 0; m < LRQK_PROFILE_SLOTS; ++m) {
+      if (!(plan->prof_used[i] & (1u << m))) continue;
+      LRQK_HIP(hipEventSynchronize(ev[2 * m + 1]));
       float ms = 0.f;
-      LRQK_HIP(hipEventElapsedTime(&ms, ev[m], ev[m + 1]));
+      LRQK_HIP(hipEventElapsedTime(&ms, ev[2 * m], ev[2 * m + 1]));
       ms_sum[m] += ms;
     }
   }

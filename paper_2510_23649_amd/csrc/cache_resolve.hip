@@ -137,7 +137,7 @@ __global__ __launch_bounds__(kResThreads) void cache_resolve_kernel(
 
 hipError_t launch_fill_i32(int32_t* p, size_t n, int32_t v, hipStream_t st) {
   if (n == 0) return hipSuccess;
-  hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, n, v);
+  LRQK_LAUNCH(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, n, v);
   return hipGetLastError();
 }
 
@@ -145,11 +145,11 @@ hipError_t launch_cache_init(const lrqk_shape& s, int32_t* slot_of, int32_t* tok
                              int32_t* last_used, hipStream_t st) {
   const size_t BHq = (size_t)s.B * s.Hq;
   const size_t n1 = BHq * row_cap(s), n2 = BHq * s.C;
-  hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n1 + 255) / 256)), dim3(256), 0, st,
+  LRQK_LAUNCH(fill_i32_kernel, dim3((unsigned)((n1 + 255) / 256)), dim3(256), 0, st,
                      slot_of, n1, -1);
-  hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n2 + 255) / 256)), dim3(256), 0, st,
+  LRQK_LAUNCH(fill_i32_kernel, dim3((unsigned)((n2 + 255) / 256)), dim3(256), 0, st,
                      token_of, n2, -1);
-  hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n2 + 255) / 256)), dim3(256), 0, st,
+  LRQK_LAUNCH(fill_i32_kernel, dim3((unsigned)((n2 + 255) / 256)), dim3(256), 0, st,
                      last_used, n2, -1);
   return hipGetLastError();
 }
@@ -170,7 +170,7 @@ hipError_t launch_cache_resolve(const lrqk_shape& s, const int32_t* sel_idx, int
       raised = true;
     }
   }
-  hipLaunchKernelGGL(cache_resolve_kernel, dim3(s.B * s.Hq), dim3(kResThreads), lds, st, sel_idx,
+  LRQK_LAUNCH(cache_resolve_kernel, dim3(s.B * s.Hq), dim3(kResThreads), lds, st, sel_idx,
                      step, s.l, row_cap(s), s.C, Cpad, s.k, slot_of, token_of, last_used, sel_slot, hit,
                      miss_tok, miss_slot, n_miss);
   return hipGetLastError();

@@ -72,12 +72,12 @@ hipError_t launch_fetch_direct(const lrqk_shape& s, const void* K_host, const vo
   const int rows_per_block = 64;
   const dim3 grid(ceil_div(s.k, rows_per_block), s.B * s.Hq);
   if (s.kv_dtype == LRQK_KV_BF16)
-    hipLaunchKernelGGL((fetch_direct_kernel<16>), grid, dim3(kFetchThreads), 0, st,
+    LRQK_LAUNCH((fetch_direct_kernel<16>), grid, dim3(kFetchThreads), 0, st,
                        (const uint4*)K_host, (const uint4*)V_host, miss_tok, miss_slot, n_miss,
                        (uint4*)cacheK, (uint4*)cacheV, s.Hq, s.Hkv, s.l, row_cap(s), s.C, s.k,
                        rows_per_block);
   else
-    hipLaunchKernelGGL((fetch_direct_kernel<32>), grid, dim3(kFetchThreads), 0, st,
+    LRQK_LAUNCH((fetch_direct_kernel<32>), grid, dim3(kFetchThreads), 0, st,
                        (const uint4*)K_host, (const uint4*)V_host, miss_tok, miss_slot, n_miss,
                        (uint4*)cacheK, (uint4*)cacheV, s.Hq, s.Hkv, s.l, row_cap(s), s.C, s.k,
                        rows_per_block);
@@ -90,10 +90,10 @@ hipError_t launch_scatter_staged(const lrqk_shape& s, const void* staging, const
   int64_t nb = (n_rows + 15) / 16;
   if (nb > 4096) nb = 4096;
   if (s.kv_dtype == LRQK_KV_BF16)
-    hipLaunchKernelGGL((scatter_staged_kernel<16>), dim3((unsigned)nb), dim3(kFetchThreads), 0, st,
+    LRQK_LAUNCH((scatter_staged_kernel<16>), dim3((unsigned)nb), dim3(kFetchThreads), 0, st,
                        (const uint4*)staging, row_dst, n_rows, (uint4*)cacheK, (uint4*)cacheV);
   else
-    hipLaunchKernelGGL((scatter_staged_kernel<32>), dim3((unsigned)nb), dim3(kFetchThreads), 0, st,
+    LRQK_LAUNCH((scatter_staged_kernel<32>), dim3((unsigned)nb), dim3(kFetchThreads), 0, st,
                        (const uint4*)staging, row_dst, n_rows, (uint4*)cacheK, (uint4*)cacheV);
   return hipGetLastError();
 }

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "lrqk.h"
@@ -25,6 +26,31 @@ int record_hip_error(hipError_t e);
   do {                                                          \
     hipError_t e__ = (call);                                    \
     if (e__ != hipSuccess) return ::lrqk::record_hip_error(e__); \
+  } while (0)
+
+// Instrumentation: kernel launches made through LRQK_LAUNCH by the calling thread attach the
+// next pair of these events to the kernel (they then hold the kernel's own start and end) for
+// as long as pairs are left; with none left a launch is a plain launch.
+struct LaunchTimer {
+  hipEvent_t* ev = nullptr;  // pairs: start, stop, start, stop, ...
+  int pairs_left = 0;
+  unsigned* recorded = nullptr;  // bit i set when pair i of the armed sequence was used
+  int next = 0;
+};
+LaunchTimer& launch_timer();
+#define LRQK_LAUNCH(kern, grid, block, lds, st, ...)                                        \
+  do {                                                                                      \
+    ::lrqk::LaunchTimer& lt__ = ::lrqk::launch_timer();                                     \
+    if (lt__.pairs_left > 0) {                                                              \
+      hipExtLaunchKernelGGL(kern, grid, block, lds, st, lt__.ev[0], lt__.ev[1], 0,          \
+                            __VA_ARGS__);                                                   \
+      if (lt__.recorded) *lt__.recorded |= 1u << lt__.next;                                 \
+      lt__.ev += 2;                                                                         \
+      ++lt__.next;                                                                          \
+      --lt__.pairs_left;                                                                    \
+    } else {                                                                                \
+      hipLaunchKernelGGL(kern, grid, block, lds, st, __VA_ARGS__);                          \
+    }                                                                                       \
   } while (0)
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -73,9 +99,6 @@ hipError_t launch_proxy_threshold(const lrqk_shape& s, const float* A_K, const f
                                   float* samples, uint32_t* thr, hipStream_t st);
 constexpr int kCandPerGroup = 8;  // candidate scores kept per head and 64-row group
 // cand_scores: [BHq][words64][kCandPerGroup] floats
-// Timing aid: the next filtered proxy-score launches of the calling thread record the
-// kernel's own start and end in these events (both null: back to plain launches).
-void proxy_filter_time_next_launch(hipEvent_t start, hipEvent_t stop);
 // The threshold key of each head comes from `thr` (keys, e.g. from launch_proxy_threshold) or,
 // if `thr` is null, from thr_norm[head] * |q_hat[head]| (the value the previous step's
 // selection left for this layer).  Exactly one of the two is given.  thr_out [BHq] receives

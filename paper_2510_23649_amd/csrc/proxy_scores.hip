@@ -19,7 +19,6 @@
 // workgroups that loop over tiles with a register prefetch.
 // The chain order (j ascending from 0.0f) makes the scores bit-reproducible.
 #include <hip/hip_runtime.h>
-#include <hip/hip_ext.h>
 
 #include "lrqk_device.h"
 #include "lrqk_internal.h"
@@ -332,9 +331,6 @@ __global__ __launch_bounds__(256) void proxy_scores_generic_kernel(
   }
 }
 
-// Events that the next filtered launch of this thread attaches to its kernel (null: none).
-thread_local hipEvent_t g_time_start = nullptr, g_time_stop = nullptr;
-
 struct FilterOut {
   const uint32_t* thr;    // threshold keys (null: take them from thr_norm)
   const float* thr_norm;  // carried thresholds / |q_hat| (null: take the keys in thr)
@@ -348,17 +344,12 @@ hipError_t launch_fast(const lrqk_shape& s, const float* A_K, const float* q_hat
                        const FilterOut* f, hipStream_t st) {
   dim3 grid(ceil_div(s.l, kTileRows), s.B * s.Hkv);
   const int n = s.l - s.w;
-  if (f && g_time_start)  // timing run: the events take the kernel's own start and end
-    hipExtLaunchKernelGGL((proxy_scores_kernel<R, G, true>), grid, dim3(kTileRows), 0, st,
-                          g_time_start, g_time_stop, 0, A_K, q_hat, scores, s.l, row_cap(s), s.Hq,
-                          s.Hkv, n, f->thr, f->thr_norm, f->thr_out, f->bitmap, f->cand_scores,
-                          filter_words64(n));
-  else if (f)
-    hipLaunchKernelGGL((proxy_scores_kernel<R, G, true>), grid, dim3(kTileRows), 0, st, A_K,
+  if (f)
+    LRQK_LAUNCH((proxy_scores_kernel<R, G, true>), grid, dim3(kTileRows), 0, st, A_K,
                        q_hat, scores, s.l, row_cap(s), s.Hq, s.Hkv, n, f->thr, f->thr_norm,
                        f->thr_out, f->bitmap, f->cand_scores, filter_words64(n));
   else
-    hipLaunchKernelGGL((proxy_scores_kernel<R, G, false>), grid, dim3(kTileRows), 0, st, A_K,
+    LRQK_LAUNCH((proxy_scores_kernel<R, G, false>), grid, dim3(kTileRows), 0, st, A_K,
                        q_hat, scores, s.l, row_cap(s), s.Hq, s.Hkv, n, nullptr, nullptr, nullptr,
                        nullptr, nullptr, 0);
   return hipGetLastError();
@@ -397,16 +388,11 @@ hipError_t launch_proxy_threshold(const lrqk_shape& s, const float* A_K, const f
   int parts = ceil_div(ns, 512);
   if (parts > kThrParts) parts = kThrParts;
   if (parts < 1) parts = 1;
-  hipLaunchKernelGGL(proxy_sample_kernel, dim3(parts, s.B * s.Hq), dim3(kThrThreads), 0, st, A_K,
+  LRQK_LAUNCH(proxy_sample_kernel, dim3(parts, s.B * s.Hq), dim3(kThrThreads), 0, st, A_K,
                      q_hat, row_cap(s), s.r, s.Hq, s.Hkv, SS, ns, parts, samples);
-  hipLaunchKernelGGL(proxy_threshold_kernel, dim3(s.B * s.Hq), dim3(kThrThreads), 0, st, samples,
+  LRQK_LAUNCH(proxy_threshold_kernel, dim3(s.B * s.Hq), dim3(kThrThreads), 0, st, samples,
                      n, s.k, SS, ns, thr);
   return hipGetLastError();
-}
-
-void proxy_filter_time_next_launch(hipEvent_t start, hipEvent_t stop) {
-  g_time_start = start;
-  g_time_stop = stop;
 }
 
 hipError_t launch_proxy_scores_filter(const lrqk_shape& s, const float* A_K, const float* q_hat,
@@ -444,7 +430,7 @@ hipError_t launch_proxy_scores(const lrqk_shape& s, const float* A_K, const floa
     tiles_per_block >>= 1;
   dim3 grid(ceil_div(n_tiles, tiles_per_block), bkv);
   const size_t lds = (size_t)kGenRows * (s.r / 4 + 1) * sizeof(float4);
-  hipLaunchKernelGGL(proxy_scores_generic_kernel, grid, dim3(256), lds, st, A_K, q_hat, scores,
+  LRQK_LAUNCH(proxy_scores_generic_kernel, grid, dim3(256), lds, st, A_K, q_hat, scores,
                      s.l, row_cap(s), s.r, s.Hq, s.Hkv, s.Hq / s.Hkv, tiles_per_block);
   return hipGetLastError();
 }

@@ -761,7 +761,7 @@ hipError_t launch_inst(const PackedArgs& a, int BHq, size_t lds, hipStream_t st)
     if (e != hipSuccess) return e;
     raised = true;
   }
-  hipLaunchKernelGGL((select_packed_kernel<GPT, SPT>), dim3(BHq), dim3(kT), lds, st, a);
+  LRQK_LAUNCH((select_packed_kernel<GPT, SPT>), dim3(BHq), dim3(kT), lds, st, a);
   return hipGetLastError();
 }
 template <int GPT>

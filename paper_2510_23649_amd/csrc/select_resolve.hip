@@ -489,7 +489,7 @@ hipError_t launch_select_only(const lrqk_shape& s, const float* scores, int32_t*
   const size_t lds = arena_sizes(s.k, n, s.C, false).total;
   hipError_t e = raise_lds_limit<false>();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((select_resolve_kernel<false>), dim3(s.B * s.Hq), dim3(kT), lds, st, scores,
+  LRQK_LAUNCH((select_resolve_kernel<false>), dim3(s.B * s.Hq), dim3(kT), lds, st, scores,
                      nullptr, 0, nullptr, nullptr, nullptr, nullptr, s.r, s.Hq, s.Hkv, s.l,
                      row_cap(s), n, s.k, sel_idx, 0, s.C, nullptr, nullptr, nullptr, nullptr,
                      nullptr, nullptr, nullptr, nullptr);
@@ -507,7 +507,7 @@ hipError_t launch_select_resolve(const lrqk_shape& s, float* scores,
   const size_t lds = arena_sizes(s.k, n, s.C, true).total;
   hipError_t e = raise_lds_limit<true>();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((select_resolve_kernel<true>), dim3(s.B * s.Hq), dim3(kT), lds, st, scores,
+  LRQK_LAUNCH((select_resolve_kernel<true>), dim3(s.B * s.Hq), dim3(kT), lds, st, scores,
                      reinterpret_cast<const uint32_t*>(ext_bitmap), 2 * filter_words64(n),
                      cand_scores, ext_bitmap ? A_K : nullptr, q_hat, scores, s.r, s.Hq, s.Hkv, s.l,
                      row_cap(s), n, s.k, sel_idx, step, s.C, slot_of, token_of, last_used,

@@ -282,14 +282,14 @@ hipError_t launch_select_topk(const lrqk_shape& s, const float* scores, int32_t*
   const int BHq = s.B * s.Hq;
   const int n = s.l - s.w;
   const int n_hist = BHq * kBins, n_cnt = BHq * 8;
-  hipLaunchKernelGGL(select_zero_kernel, dim3(ceil_div(n_hist, 256)), dim3(256), 0, st, ws.hist,
+  LRQK_LAUNCH(select_zero_kernel, dim3(ceil_div(n_hist, 256)), dim3(256), 0, st, ws.hist,
                      ws.counters, n_hist, n_cnt);
   const dim3 grid(ceil_div(n, kSelChunk), BHq);
-  hipLaunchKernelGGL(select_hist_kernel, grid, dim3(kSelThreads), 0, st, scores, s.l, n, s.k,
+  LRQK_LAUNCH(select_hist_kernel, grid, dim3(kSelThreads), 0, st, scores, s.l, n, s.k,
                      ws.hist, ws.counters);
-  hipLaunchKernelGGL(select_collect_kernel, grid, dim3(kSelThreads), 0, st, scores, s.l, n, s.k,
+  LRQK_LAUNCH(select_collect_kernel, grid, dim3(kSelThreads), 0, st, scores, s.l, n, s.k,
                      ws.counters, ws.out_list, ws.cand);
-  hipLaunchKernelGGL(select_finalize_kernel, dim3(BHq), dim3(kFinThreads), 0, st, scores, s.l, n,
+  LRQK_LAUNCH(select_finalize_kernel, dim3(BHq), dim3(kFinThreads), 0, st, scores, s.l, n,
                      s.k, ws.counters, ws.out_list, ws.cand, sel_idx);
   return hipGetLastError();
 }

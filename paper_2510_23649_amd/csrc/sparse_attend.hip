@@ -367,12 +367,12 @@ hipError_t launch_attend_partial(const lrqk_shape& s, int mode, const float* q, 
                     s.l, row_cap(s)};
   const dim3 grid(nblocks, s.B * s.Hq);
   if (s.kv_dtype == LRQK_KV_BF16)
-    hipLaunchKernelGGL((attend_partial_kernel<true>), grid, dim3(kAttThreads), 0, st, mode, fs, q,
+    LRQK_LAUNCH((attend_partial_kernel<true>), grid, dim3(kAttThreads), 0, st, mode, fs, q,
                        cacheK, cacheV, sel_slot, hit, miss_slot, n_miss, liteK, liteV, partials,
                        s.Hq, s.Hkv, s.C, s.k, s.w, rows_per_block, parts_per_head, part_offset,
                        s.scale);
   else
-    hipLaunchKernelGGL((attend_partial_kernel<false>), grid, dim3(kAttThreads), 0, st, mode, fs, q,
+    LRQK_LAUNCH((attend_partial_kernel<false>), grid, dim3(kAttThreads), 0, st, mode, fs, q,
                        cacheK, cacheV, sel_slot, hit, miss_slot, n_miss, liteK, liteV, partials,
                        s.Hq, s.Hkv, s.C, s.k, s.w, rows_per_block, parts_per_head, part_offset,
                        s.scale);
@@ -382,7 +382,7 @@ hipError_t launch_attend_partial(const lrqk_shape& s, int mode, const float* q, 
 hipError_t launch_attend_combine(const lrqk_shape& s, const float* partials, int parts_per_head,
                                  int nparts, float* out, hipStream_t st) {
   if (nparts > kCombMaxParts) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(attend_combine_kernel, dim3(s.B * s.Hq), dim3(kCombThreads), 0, st,
+  LRQK_LAUNCH(attend_combine_kernel, dim3(s.B * s.Hq), dim3(kCombThreads), 0, st,
                      partials, parts_per_head, nparts, out);
   return hipGetLastError();
 }

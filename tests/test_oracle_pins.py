@@ -372,3 +372,121 @@ def test_window_always_attended_and_heavy_tokens_are_found():
     sel = orc.select_topk(orc.proxy_scores(a["A_K"], a["q_hat"])[1], cfg.k, cfg.w)
     for h in range(cfg.Hq):
         assert set(data.pool_pos[0, h].tolist()) <= set(sel[0, h].tolist())
+
+
+# --------------------------------------------------------------------------- fetch shared by a KV group
+
+def _miss_lists(rng, B, Hq, l, k, n_each, shared_with_first=0.0, G=1):
+    """Ascending miss lists per head with distinct slots; a fraction of the entries of the heads
+    h % G != 0 is taken from the list of their group's first head."""
+    miss_tok = np.full((B, Hq, k), -1, np.int32)
+    miss_slot = np.full((B, Hq, k), -1, np.int32)
+    n_miss = np.zeros((B, Hq), np.int32)
+    for b in range(B):
+        for h in range(Hq):
+            n = int(n_each[b, h])
+            toks = rng.choice(l, size=n, replace=False)
+            if h % G and shared_with_first > 0 and n:
+                first = miss_tok[b, h - h % G, :n_miss[b, h - h % G]]
+                take = rng.choice(first, size=min(len(first), int(shared_with_first * n)), replace=False)
+                rest = np.setdiff1d(toks, take)[: n - len(take)]
+                toks = np.concatenate([take, rest])
+            toks = np.unique(toks)
+            n_miss[b, h] = len(toks)
+            miss_tok[b, h, :len(toks)] = toks
+            miss_slot[b, h, :len(toks)] = rng.permutation(k)[:len(toks)]
+    return miss_tok, miss_slot, n_miss
+
+
+@pytest.mark.parametrize("kvd", ["bf16", "f32"])
+def test_group_fetch_leaves_the_caches_of_the_per_head_fetch_and_counts_the_union(kvd):
+    rng = np.random.default_rng(77)
+    B, Hkv, G, l, d, k = 2, 2, 4, 300, 128, 40
+    Hq = Hkv * G
+    if kvd == "bf16":
+        K = f32_to_bf16_bits(rng.standard_normal((B, Hkv, l, d)).astype(np.float32))
+        V = f32_to_bf16_bits(rng.standard_normal((B, Hkv, l, d)).astype(np.float32))
+    else:
+        K = rng.standard_normal((B, Hkv, l, d)).astype(np.float32)
+        V = rng.standard_normal((B, Hkv, l, d)).astype(np.float32)
+    n_each = rng.integers(0, k + 1, size=(B, Hq))
+    n_each[0, 1] = 0                                           # a head that misses nothing
+    miss_tok, miss_slot, n_miss = _miss_lists(rng, B, Hq, l, k, n_each, 0.6, G)
+    cK1, cV1 = np.zeros((B, Hq, k, d), K.dtype), np.zeros((B, Hq, k, d), K.dtype)
+    cK2, cV2 = cK1.copy(), cV1.copy()
+    orc.fetch(K, V, miss_tok, miss_slot, n_miss, cK1, cV1)
+    link_rows, union = orc.group_fetch(K, V, miss_tok, miss_slot, n_miss, cK2, cV2)
+    assert np.array_equal(cK1, cK2) and np.array_equal(cV1, cV2)
+    # every fetched slot holds the bits of its host row (head h reads KV head h // G)
+    for b in range(B):
+        for h in range(Hq):
+            for j in range(n_miss[b, h]):
+                assert np.array_equal(cK2[b, h, miss_slot[b, h, j]], K[b, h // G, miss_tok[b, h, j]])
+                assert np.array_equal(cV2[b, h, miss_slot[b, h, j]], V[b, h // G, miss_tok[b, h, j]])
+    # rows over the link = size of the union of the group's lists (numpy's set union)
+    shared_somewhere = False
+    for b in range(B):
+        for kv in range(Hkv):
+            lists = [miss_tok[b, h, :n_miss[b, h]] for h in range(kv * G, (kv + 1) * G)]
+            want = np.unique(np.concatenate(lists))
+            assert np.array_equal(union[b * Hkv + kv], want)
+            assert link_rows[b, kv] == len(want) <= sum(len(x) for x in lists)
+            shared_somewhere |= len(want) < sum(len(x) for x in lists)
+    assert shared_somewhere
+
+
+def test_group_fetch_special_cases():
+    rng = np.random.default_rng(78)
+    B, l, d, k = 1, 200, 128, 30
+    K = rng.standard_normal((B, 1, l, d)).astype(np.float32)
+    V = rng.standard_normal((B, 1, l, d)).astype(np.float32)
+    # G = 1: nothing to share, the count is the list length
+    mt, ms, nm = _miss_lists(rng, B, 1, l, k, np.array([[17]]))
+    cK, cV = np.zeros((B, 1, k, d), np.float32), np.zeros((B, 1, k, d), np.float32)
+    rows, _ = orc.group_fetch(K, V, mt, ms, nm, cK, cV)
+    assert rows[0, 0] == 17
+    # G = 3, identical lists: one list's worth of rows, all three caches filled
+    mt3 = np.repeat(mt, 3, axis=1)
+    ms3 = np.stack([rng.permutation(k) for _ in range(3)])[None].astype(np.int32)
+    nm3 = np.repeat(nm, 3, axis=1)
+    cK, cV = np.zeros((B, 3, k, d), np.float32), np.zeros((B, 3, k, d), np.float32)
+    rows, _ = orc.group_fetch(K, V, mt3, ms3, nm3, cK, cV)
+    assert rows[0, 0] == 17
+    for h in range(3):
+        for j in range(17):
+            assert np.array_equal(cK[0, h, ms3[0, h, j]], K[0, 0, mt3[0, h, j]])
+    # G = 2, disjoint lists: the counts add up
+    mt2 = np.full((B, 2, k), -1, np.int32)
+    mt2[0, 0, :5] = [1, 3, 5, 7, 9]
+    mt2[0, 1, :4] = [0, 2, 4, 6]
+    ms2 = np.tile(np.arange(k, dtype=np.int32), (B, 2, 1))
+    cK, cV = np.zeros((B, 2, k, d), np.float32), np.zeros((B, 2, k, d), np.float32)
+    rows, _ = orc.group_fetch(K, V, mt2, ms2, np.array([[5, 4]], np.int32), cK, cV)
+    assert rows[0, 0] == 9
+
+
+def test_group_share_knob_makes_heads_of_a_group_miss_the_same_rows():
+    """The generator's group_share: with 0 the heads of a group miss (almost) disjoint rows, with
+    1 the rows fetched for one head are mostly wanted by the others in the same step."""
+    def union_over_total(share):
+        cfg = get_config("c2").with_(B=1, Hq=8, Hkv=2, l=6000, r=16, k=256, w=16, C=512,
+                                     n_heavy=64, pool_mult=4, group_share=share)
+        data = make_layer(cfg)
+        qs = QueryStream(data)
+        A_K, K, V = as_numpy(data.A_K), as_numpy(data.K), as_numpy(data.V)
+        st = orc.CacheState(cfg.B, cfg.Hq, cfg.l, cfg.C)
+        cK = np.zeros((cfg.B, cfg.Hq, cfg.C, cfg.d), K.dtype)
+        cV = np.zeros_like(cK)
+        tot = uni = 0
+        for step in range(1, 7):
+            q, q_hat = qs.next()
+            s64, s32 = orc.proxy_scores(A_K, as_numpy(q_hat))
+            sel = orc.select_topk(s32, cfg.k, cfg.w)
+            res = orc.cache_resolve(sel, step, st)
+            rows, _ = orc.group_fetch(K, V, res["miss_tok"], res["miss_slot"], res["n_miss"], cK, cV)
+            if step > 2:
+                tot += int(res["n_miss"].sum())
+                uni += int(rows.sum())
+        return uni / tot
+    assert union_over_total(0.0) > 0.9
+    assert union_over_total(1.0) < 0.75
