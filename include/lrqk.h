@@ -66,11 +66,20 @@ enum {
   LRQK_FETCH_STAGED = 0, /* miss list -> host, host gathers rows into a pinned staging
                             buffer, one hipMemcpyAsync on the plan's side stream, then a
                             scatter kernel into the cache slots                        */
-  LRQK_FETCH_DIRECT = 1  /* the GPU reads the rows straight out of the pinned host store
+  LRQK_FETCH_DIRECT = 1, /* the GPU reads the rows straight out of the pinned host store
                             (device-visible host memory) and writes the cache slots; no host
                             synchronisation.  lrqk_fetch_misses does it in a kernel of its
                             own; lrqk_decode_step does it inside the attention kernel, so the
                             host-link reads overlap the HBM reads of the rows that hit      */
+  LRQK_FETCH_GROUP = 2   /* as DIRECT, with the host link shared inside a KV group: K and V
+                            exist once per KV head (Sec. 4, preliminaries), so a position that
+                            several query heads of a group miss in the same step is one host
+                            row; it is read once and written into the slot of each of those
+                            heads.  The caches end up exactly as with the other modes; fewer
+                            rows cross the link when the heads of a group want the same
+                            tokens.  lrqk_decode_step: the shared fetch runs in one launch
+                            with the attention over the rows that hit, the fetched rows are
+                            attended by a second launch                                     */
 };
 /* May be OR-ed into the `mode` of lrqk_decode_step: estimate the candidate thresholds of the
  * selection from a sample of this step's proxy scores even though the layer carries thresholds
@@ -238,8 +247,10 @@ int lrqk_plan_destroy(lrqk_plan* plan);
  *   miss_tok, miss_slot, n_miss  device, as written by lrqk_cache_resolve
  *   mode  LRQK_FETCH_STAGED: synchronises `stream` once to read the miss list on the
  *         host, then copies on the plan's side stream and makes `stream` wait for it.
- *         LRQK_FETCH_DIRECT: one kernel on `stream`, no host synchronisation.
- *   total_miss_out  host int64*, optional: total rows fetched (STAGED only; DIRECT writes -1).
+ *         LRQK_FETCH_DIRECT, LRQK_FETCH_GROUP: one kernel on `stream`, no host
+ *         synchronisation (GROUP needs the miss lists ascending, as lrqk_cache_resolve and
+ *         lrqk_decode_step write them).
+ *   total_miss_out  host int64*, optional: total rows fetched (STAGED only; the others write -1).
  * Heads with n_miss < 0 are skipped.
  */
 int lrqk_fetch_misses(lrqk_plan* plan, const lrqk_shape* shape, const void* K_host,
@@ -279,6 +290,9 @@ typedef struct lrqk_step_debug {
   int32_t* miss_tok;  /* [B,Hq,k] */
   int32_t* miss_slot; /* [B,Hq,k] */
   int32_t* n_miss;    /* [B,Hq]   */
+  int32_t* link_rows; /* [B,Hkv]  LRQK_FETCH_GROUP only: rows read from the host store per KV
+                         head = size of the union of its group's miss lists (cleared and
+                         counted only when this pointer is given) */
 } lrqk_step_debug;
 
 /*
@@ -302,9 +316,10 @@ typedef struct lrqk_step_debug {
  *   q_hat  device fp32 [B,Hq,r];  q  device fp32 [B,Hq,d];  out  device fp32 [B,Hq,d]
  *   step   as in lrqk_cache_resolve
  *   mode   LRQK_FETCH_STAGED (one host synchronisation per call, to read the miss
- *          list) or LRQK_FETCH_DIRECT (fully asynchronous), optionally | LRQK_SELECT_FRESH
+ *          list), LRQK_FETCH_DIRECT or LRQK_FETCH_GROUP (fully asynchronous), optionally
+ *          | LRQK_SELECT_FRESH
  *   dbg    optional
- *   total_miss_out  host int64*, optional (STAGED: rows fetched; DIRECT: -1)
+ *   total_miss_out  host int64*, optional (STAGED: rows fetched; DIRECT, GROUP: -1)
  */
 int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
                      const lrqk_layer* layer, const float* q_hat, const float* q, float* out,

@@ -1,7 +1,7 @@
 """Hit/miss ablation and miss-rate grid on the synthetic workloads (needs a GPU).
 
-    python -m paper_2510_23649_amd.ablation [--grid] [--no-hit-miss] [--end-to-end]
-                                             [--steps N] [--drift F]
+    python -m paper_2510_23649_amd.ablation [--grid] [--no-hit-miss] [--group-fetch]
+                                             [--end-to-end] [--steps N] [--drift F]
 
 Two experiments of the paper, re-run on seeded synthetic inputs (its prompts and models are
 not available; the generator's query drift is what sets the level of the miss rate, so the
@@ -15,6 +15,9 @@ lite tokens, not what a language model would produce):
   --no-hit-miss  App. C.2, "LRQK no hit/miss": the same decode steps with the cache emptied
                  before every step, so that every selected row crosses the host link, against
                  the default (only the missing rows do).
+  --group-fetch  the fetch leg per head against the fetch shared by the query heads of a KV
+                 group (a row missed by several heads crosses the host link once), for heads
+                 that want the same tokens to different degrees.
   --end-to-end   the whole method in sequence: prefill factorisation of a synthetic prompt,
                  then decode steps (factor update, append, proxy top-k, fetch, attention) on
                  the factors it produced; reports the recall of the exact top-k and the
@@ -132,6 +135,61 @@ def no_hit_miss(steps: int, layers: int, out=sys.stdout):
     plan.close()
 
 
+def group_fetch_ab(steps: int, layers: int, out=sys.stdout):
+    """Per-head fetch (LRQK_FETCH_DIRECT) against the fetch shared inside a KV group
+    (LRQK_FETCH_GROUP) on workload 3, for query heads of a group that want the same tokens to
+    different degrees (the generator's group_share): time per layer-step and rows / MB over the
+    host link per step (DIRECT: every head's misses; GROUP: the union per KV head)."""
+    from gen import get_config, make_layer, QueryStream
+    print("| group_share | fetch | us per layer-step | rows missed per step | rows over the host "
+          "link per step | MB over the link per step |", file=out)
+    print("|---|---|---|---|---|---|", file=out)
+    for share in (0.0, 0.5, 1.0):
+        cfg = get_config("c3").with_(layers=layers, group_share=share)
+        shape = _shape(cfg)
+        row_bytes = 2 * cfg.d * 2
+        for name, mode in (("per head (DIRECT)", L.LRQK_FETCH_DIRECT),
+                           ("shared in the group (GROUP)", L.LRQK_FETCH_GROUP)):
+            lbs, streams = [], []
+            for li in range(layers):
+                data = make_layer(cfg, li, device="cuda")
+                lbs.append(LayerBuffers(shape, data.A_K, data.K, data.V))
+                streams.append(QueryStream(data))
+            plan = L.Plan(shape)
+            out_t = torch.empty((cfg.B, cfg.Hq, cfg.d), device="cuda")
+            n_miss = torch.zeros((cfg.B, cfg.Hq), dtype=torch.int32, device="cuda")
+            link = torch.zeros((cfg.B, cfg.Hkv), dtype=torch.int32, device="cuda")
+            step_no = [0] * layers
+
+            def run(n, dbg):
+                qs = [streams[i % layers].next() for i in range(n)]
+                torch.cuda.synchronize()
+                missed = linked = 0
+                t0 = time.perf_counter()
+                for i in range(n):
+                    li = i % layers
+                    step_no[li] += 1
+                    flags = L.LRQK_SELECT_FRESH if step_no[li] == 1 else 0
+                    L.lrqk_decode_step(plan, shape, step_no[li], lbs[li].struct, qs[i][1], qs[i][0],
+                                       out_t, mode | flags,
+                                       dict(n_miss=n_miss, link_rows=link) if dbg else None)
+                    if dbg:
+                        missed += n_miss.clamp(min=0).sum().item()
+                        linked += link.sum().item()
+                torch.cuda.synchronize()
+                return (time.perf_counter() - t0) / n * 1e6, missed / n, linked / n
+
+            run(2 * layers, False)                    # warm the caches
+            _, missed, linked = run(steps, True)
+            us, _, _ = run(steps, False)
+            if mode == L.LRQK_FETCH_DIRECT:
+                linked = missed                       # every head fetches its own misses
+            print(f"| {share} | {name} | {us:.1f} | {missed:.0f} | {linked:.0f} | "
+                  f"{linked * row_bytes / 1e6:.2f} |", file=out)
+            plan.close()
+            del lbs, streams
+
+
 def end_to_end(steps: int, out=sys.stdout):
     """Prefill factorisation, then Alg. 2 decode steps on the factors it produced; reports how
     much of the exact top-k of q K^T the proxy selects and how far the sparse attention output
@@ -222,6 +280,7 @@ def main():
     ap.add_argument("--grid", action="store_true")
     ap.add_argument("--no-hit-miss", action="store_true")
     ap.add_argument("--end-to-end", action="store_true")
+    ap.add_argument("--group-fetch", action="store_true")
     ap.add_argument("--steps", type=int, default=64)
     ap.add_argument("--warm", type=int, default=8)
     ap.add_argument("--layers", type=int, default=8)
@@ -231,7 +290,7 @@ def main():
     args = ap.parse_args()
     if not torch.cuda.is_available():
         sys.exit("ablation: needs a GPU")
-    both = not (args.grid or args.no_hit_miss or args.end_to_end)
+    both = not (args.grid or args.no_hit_miss or args.end_to_end or args.group_fetch)
     if args.grid or both:
         print("## Miss-rate grid (Sec. 5.3), l = 4096, 32 q / 8 kv heads, cache of k slots, "
               f"query drift {args.drift} of the heavy window per step\n")
@@ -240,6 +299,10 @@ def main():
         print("\n## Hit/miss ablation (App. C.2), workload 3 (l = 131072, r = 32, k = 2048), "
               f"{args.layers} layers rotated\n")
         no_hit_miss(args.steps, args.layers)
+    if args.group_fetch or both:
+        print("\n## Fetch per head against fetch shared inside a KV group, workload 3, "
+              f"{args.layers} layers rotated\n")
+        group_fetch_ab(args.steps, args.layers)
     if args.end_to_end or both:
         print("\n## Prefill factorisation, then Alg. 2 decode steps on its factors: 8 q / 2 kv "
               "heads, l = 8192, r = 32, k = 512, w = 16\n")

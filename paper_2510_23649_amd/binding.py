@@ -12,7 +12,7 @@ _LIB_PATH = os.path.join(_PKG, "liblrqk.so")
 _lib = None
 
 LRQK_KV_BF16, LRQK_KV_F32 = 0, 1
-LRQK_FETCH_STAGED, LRQK_FETCH_DIRECT = 0, 1
+LRQK_FETCH_STAGED, LRQK_FETCH_DIRECT, LRQK_FETCH_GROUP = 0, 1, 2
 LRQK_SELECT_FRESH = 0x100
 LRQK_WS_SELECT, LRQK_WS_ATTEND, LRQK_WS_UPDATE, LRQK_WS_PREFILL = 1, 2, 3, 4
 
@@ -57,7 +57,7 @@ class Layer(C.Structure):
 
 class _StepDebug(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("sel_idx", "sel_slot", "hit", "miss_tok", "miss_slot",
-                                          "n_miss")]
+                                          "n_miss", "link_rows")]
 
 
 def library_path() -> str:
@@ -325,7 +325,7 @@ def lrqk_decode_step(plan: Plan, shape, step, layer: Layer, q_hat, q, out,
     dbg = None
     if debug is not None:
         dbg = _StepDebug(*[_dev(debug.get(n)) for n in ("sel_idx", "sel_slot", "hit", "miss_tok",
-                                                        "miss_slot", "n_miss")])
+                                                        "miss_slot", "n_miss", "link_rows")])
     total = C.c_int64(0)
     _check(load_library().lrqk_decode_step(
         plan.handle, C.byref(shape), int(step), C.byref(layer), _dev(q_hat, torch.float32),

@@ -529,7 +529,8 @@ int lrqk_fetch_misses(lrqk_plan* plan, const lrqk_shape* shape, const void* K_ho
                       int64_t* total_miss_out, void* stream) {
   int rc = check_shape(shape);
   if (rc != LRQK_OK) return rc;
-  if (mode != LRQK_FETCH_STAGED && mode != LRQK_FETCH_DIRECT) return LRQK_EINVAL;
+  if (mode != LRQK_FETCH_STAGED && mode != LRQK_FETCH_DIRECT && mode != LRQK_FETCH_GROUP)
+    return LRQK_EINVAL;
   if (!all_aligned16({K_host, V_host, miss_tok, miss_slot, n_miss, cacheK, cacheV}))
     return LRQK_EINVAL;
   rc = check_plan_fits(plan, shape);
@@ -538,6 +539,12 @@ int lrqk_fetch_misses(lrqk_plan* plan, const lrqk_shape* shape, const void* K_ho
   if (mode == LRQK_FETCH_DIRECT) {
     LRQK_HIP(launch_fetch_direct(*shape, K_host, V_host, miss_tok, miss_slot, n_miss, cacheK,
                                  cacheV, st));
+    if (total_miss_out) *total_miss_out = -1;
+    return LRQK_OK;
+  }
+  if (mode == LRQK_FETCH_GROUP) {
+    LRQK_HIP(launch_group_fetch(*shape, K_host, V_host, miss_tok, miss_slot, n_miss, cacheK,
+                                cacheV, nullptr, st));
     if (total_miss_out) *total_miss_out = -1;
     return LRQK_OK;
   }
@@ -553,7 +560,9 @@ int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
   if (rc != LRQK_OK) return rc;
   if (!L || step < 0 || step == INT32_MAX) return LRQK_EINVAL;
   const int mode = mode_flags & ~LRQK_SELECT_FRESH;
-  if (mode != LRQK_FETCH_STAGED && mode != LRQK_FETCH_DIRECT) return LRQK_EINVAL;
+  if (mode != LRQK_FETCH_STAGED && mode != LRQK_FETCH_DIRECT && mode != LRQK_FETCH_GROUP)
+    return LRQK_EINVAL;
+  if (dbg && dbg->link_rows && !aligned16(dbg->link_rows)) return LRQK_EINVAL;
   if (L->sel_thr && !aligned16(L->sel_thr)) return LRQK_EINVAL;
   if (!all_aligned16({L->A_K, L->K_host, L->V_host, L->slot_of, L->token_of, L->last_used,
                       L->cacheK, L->cacheV, q_hat, q, out}))
@@ -627,6 +636,32 @@ int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
                                    sel_idx));
     prof_arm(plan, LRQK_SLOT_COMBINE, 1);
     LRQK_HIP(launch_attend_combine(s, plan->partials, parts_per_head, g.nsplit, out, st));
+    prof_step_done(plan);
+    if (total_miss_out) *total_miss_out = -1;
+    return LRQK_OK;
+  }
+
+  if (mode == LRQK_FETCH_GROUP) {
+    // the group's shared fetch in one launch with the attention over the rows that hit; then
+    // the fetched rows (at most k of them per head: the launch covers the longest possible list)
+    int32_t* link_rows = dbg ? dbg->link_rows : nullptr;
+    if (link_rows) {
+      launch_timer() = LaunchTimer{};
+      LRQK_HIP(launch_fill_i32(link_rows, (size_t)s.B * s.Hkv, 0, st));
+    }
+    prof_arm(plan, LRQK_SLOT_ATTEND, 1);
+    LRQK_HIP(launch_attend_hits_group_fetch(s, q, L->cacheK, L->cacheV, sel_slot, hit, L->liteK,
+                                            L->liteV, plan->partials, g.nsplit, g.rows_per_block,
+                                            parts_per_head, L->K_host, L->V_host, miss_tok,
+                                            miss_slot, n_miss, link_rows, st));
+    const int nblk_miss = ceil_div(s.k, g.rows_per_block);
+    prof_arm(plan, LRQK_SLOT_ATTEND_MISS, 1);
+    LRQK_HIP(launch_attend_partial(s, kAttendMisses, q, L->cacheK, L->cacheV, sel_slot, hit,
+                                   miss_slot, n_miss, L->liteK, L->liteV, plan->partials,
+                                   nblk_miss, g.rows_per_block, parts_per_head, g.nsplit, st));
+    prof_arm(plan, LRQK_SLOT_COMBINE, 1);
+    LRQK_HIP(launch_attend_combine(s, plan->partials, parts_per_head, g.nsplit + nblk_miss, out,
+                                   st));
     prof_step_done(plan);
     if (total_miss_out) *total_miss_out = -1;
     return LRQK_OK;

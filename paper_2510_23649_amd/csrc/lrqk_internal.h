@@ -154,6 +154,22 @@ hipError_t launch_attend_partial(const lrqk_shape& s, int mode, const float* q, 
                                  int nblocks, int rows_per_block, int parts_per_head,
                                  int part_offset, hipStream_t st, const void* K_host = nullptr,
                                  const void* V_host = nullptr, const int32_t* sel_idx = nullptr);
+// The fetch shared by the query heads of a KV group (one host read per position the group
+// misses), alone or in one launch with the attention over the rows that hit.
+// link_rows [B,Hkv] (may be null): incremented by the rows read from the host store.
+hipError_t launch_group_fetch(const lrqk_shape& s, const void* K_host, const void* V_host,
+                              const int32_t* miss_tok, const int32_t* miss_slot,
+                              const int32_t* n_miss, void* cacheK, void* cacheV,
+                              int32_t* link_rows, hipStream_t st);
+hipError_t launch_attend_hits_group_fetch(const lrqk_shape& s, const float* q, void* cacheK,
+                                          void* cacheV, const int32_t* sel_slot,
+                                          const uint8_t* hit, const void* liteK,
+                                          const void* liteV, float* partials, int nblocks,
+                                          int rows_per_block, int parts_per_head,
+                                          const void* K_host, const void* V_host,
+                                          const int32_t* miss_tok, const int32_t* miss_slot,
+                                          const int32_t* n_miss, int32_t* link_rows,
+                                          hipStream_t st);
 hipError_t launch_attend_combine(const lrqk_shape& s, const float* partials, int parts_per_head,
                                  int nparts, float* out, hipStream_t st);
 hipError_t launch_fetch_direct(const lrqk_shape& s, const void* K_host, const void* V_host,

@@ -103,19 +103,46 @@ struct FetchSrc {
   int lrows;                // rows allocated per (batch, KV head)
 };
 
+struct AttendArgs {
+  int mode;
+  FetchSrc fs;
+  const float* q;
+  const void* cacheK;
+  const void* cacheV;
+  const int32_t* sel_slot;
+  const uint8_t* hit;
+  const int32_t* miss_slot;
+  const int32_t* n_miss;
+  const void* liteK;
+  const void* liteV;
+  float* partials;
+  int Hq, Hkv, C, k, w, rows_per_block, parts_per_head, part_offset;
+  float scale;
+};
+
+// One workgroup's share of a head's row list: block bx of head bh.
 template <bool BF16>
-__global__ __launch_bounds__(kAttThreads) void attend_partial_kernel(
-    int mode, FetchSrc fs, const float* __restrict__ q, const void* cacheK,
-    const void* cacheV, const int32_t* __restrict__ sel_slot,
-    const uint8_t* __restrict__ hit, const int32_t* __restrict__ miss_slot,
-    const int32_t* __restrict__ n_miss, const void* __restrict__ liteK,
-    const void* __restrict__ liteV, float* __restrict__ partials, int Hq, int Hkv, int C, int k,
-    int w, int rows_per_block, int parts_per_head, int part_offset, float scale) {
+__device__ __forceinline__ void attend_partial_body(const AttendArgs& a, int bx, int bh) {
+  const int mode = a.mode;
+  const FetchSrc fs = a.fs;
+  const float* __restrict__ q = a.q;
+  const void* cacheK = a.cacheK;
+  const void* cacheV = a.cacheV;
+  const int32_t* __restrict__ sel_slot = a.sel_slot;
+  const uint8_t* __restrict__ hit = a.hit;
+  const int32_t* __restrict__ miss_slot = a.miss_slot;
+  const int32_t* __restrict__ n_miss = a.n_miss;
+  const void* __restrict__ liteK = a.liteK;
+  const void* __restrict__ liteV = a.liteV;
+  float* __restrict__ partials = a.partials;
+  const int Hq = a.Hq, Hkv = a.Hkv, C = a.C, k = a.k, w = a.w;
+  const int rows_per_block = a.rows_per_block, parts_per_head = a.parts_per_head;
+  const int part_offset = a.part_offset;
+  const float scale = a.scale;
   constexpr size_t ROWB = kD * (BF16 ? 2 : 4);
   __shared__ float wm[4], wsum[4];
   __shared__ float wacc[4][kD];
 
-  const int bh = blockIdx.y;
   const int b = bh / Hq, h = bh - b * Hq;
   const int kvh = h / (Hq / Hkv);
   const int t = threadIdx.x, lane = t & 63, wv = t >> 6;
@@ -159,7 +186,7 @@ __global__ __launch_bounds__(kAttThreads) void attend_partial_kernel(
   float m = -INFINITY, ssum = 0.0f;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-  const int row_begin = blockIdx.x * rows_per_block;
+  const int row_begin = bx * rows_per_block;
   const int row_end = min(n_rows, row_begin + rows_per_block);
   for (int base = row_begin; base < row_end; base += kRowsPerPass * kUnroll) {
     const void* kp[kUnroll];
@@ -263,13 +290,109 @@ __global__ __launch_bounds__(kAttThreads) void attend_partial_kernel(
       s += wsum[i] * g;
     }
     float* __restrict__ P =
-        partials + ((size_t)bh * parts_per_head + part_offset + blockIdx.x) * kPartialStride;
+        partials + ((size_t)bh * parts_per_head + part_offset + bx) * kPartialStride;
     P[4 + t] = a;
     if (t == 0) {
       P[0] = M;
       P[1] = s;
     }
   }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kAttThreads) void attend_partial_kernel(const AttendArgs a) {
+  attend_partial_body<BF16>(a, blockIdx.x, blockIdx.y);
+}
+
+// Fetch shared by the query heads of a KV group (K and V exist once per KV head, Sec. 4
+// preliminaries; Alg. 2 "Fetch missing", "merge"): the missing rows of head bh, 16 lanes a row.
+// A position that several heads of the group miss is read from the host store once, by the
+// lowest of those heads, and written into the slot each of them gave it; the other heads skip
+// it.  The heads' miss lists are ascending, so "does head g2 miss this position, and where" is
+// a binary search, run by lane g2 of the 16-lane group for its head.
+struct GroupFetchArgs {
+  FetchSrc fs;          // sel_idx unused
+  void* cacheK;
+  void* cacheV;
+  const int32_t* miss_tok;
+  const int32_t* miss_slot;
+  const int32_t* n_miss;
+  int32_t* link_rows;   // [B,Hkv] rows read from the host store, or null (not counted)
+  int Hq, Hkv, C, k;
+};
+template <bool BF16>
+__device__ __forceinline__ void group_fetch_body(const GroupFetchArgs& a, int fx, int nfx, int bh) {
+  constexpr size_t ROWB = kD * (BF16 ? 2 : 4);
+  const int Hq = a.Hq, Hkv = a.Hkv, C = a.C, k = a.k;
+  const int G = Hq / Hkv;
+  const int b = bh / Hq, h = bh - b * Hq, kvh = h / G, g = h - kvh * G;
+  const int bh0 = bh - g;  // first head of the group
+  const int t = threadIdx.x, lane = t & 63, sub = t & 15, rgrp = t >> 4;
+  const int nm = max(0, min(a.n_miss[bh], k));
+  const int32_t* __restrict__ mt = a.miss_tok + (size_t)bh * k;
+  const int32_t* __restrict__ ms = a.miss_slot + (size_t)bh * k;
+  const char* __restrict__ Kh = a.fs.K_host + ((size_t)b * Hkv + kvh) * (size_t)a.fs.lrows * ROWB;
+  const char* __restrict__ Vh = a.fs.V_host + ((size_t)b * Hkv + kvh) * (size_t)a.fs.lrows * ROWB;
+  // lane `sub` < G looks positions up in the list of head bh0 + sub
+  const int32_t* __restrict__ ot = a.miss_tok + (size_t)(bh0 + min(sub, G - 1)) * k;
+  const int32_t* __restrict__ os = a.miss_slot + (size_t)(bh0 + min(sub, G - 1)) * k;
+  const int onm = sub < G ? max(0, min(a.n_miss[bh0 + sub], k)) : 0;
+  for (int j0 = fx * 16; j0 < nm; j0 += nfx * 16) {  // uniform trip count over the wavefront
+    const int j = j0 + rgrp;
+    const bool have = j < nm;
+    const int32_t tok = have ? mt[j] : -1;
+    const int32_t slot = have ? ms[j] : -1;
+    const bool ok = tok >= 0 && tok < a.fs.l && slot >= 0 && slot < C;
+    // where, if anywhere, head bh0 + sub lists this position
+    int32_t oslot = -1;
+    if (ok && sub < G && sub != g) {
+      int lo = 0, hi = onm;
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (ot[mid] < tok) lo = mid + 1; else hi = mid;
+      }
+      if (lo < onm && ot[lo] == tok) {
+        const int32_t s2 = os[lo];
+        oslot = (s2 >= 0 && s2 < C) ? s2 : -2;  // -2: listed, but with an unusable slot
+      }
+    }
+    // the lowest head that lists the position fetches it
+    const unsigned long long listed = __ballot(oslot != -1);
+    const unsigned mine16 = (unsigned)(listed >> (lane & 48)) & 0xffffu;
+    const bool owner = ok && (mine16 & ((1u << g) - 1u)) == 0u;
+    RowChunk<BF16> kc, vc;
+    if (owner) {
+      kc.load(Kh + (size_t)tok * ROWB, sub);
+      vc.load(Vh + (size_t)tok * ROWB, sub);
+      kc.store(static_cast<char*>(a.cacheK) + ((size_t)bh * C + slot) * ROWB, sub);
+      vc.store(static_cast<char*>(a.cacheV) + ((size_t)bh * C + slot) * ROWB, sub);
+      if (sub == 0 && a.link_rows) atomicAdd(&a.link_rows[b * Hkv + kvh], 1);
+    }
+    for (int g2 = g + 1; g2 < G; ++g2) {  // uniform
+      const int32_t s2 = __shfl(oslot, (lane & 48) + g2);
+      if (owner && s2 >= 0) {
+        kc.store(static_cast<char*>(a.cacheK) + ((size_t)(bh0 + g2) * C + s2) * ROWB, sub);
+        vc.store(static_cast<char*>(a.cacheV) + ((size_t)(bh0 + g2) * C + s2) * ROWB, sub);
+      }
+    }
+  }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kAttThreads) void group_fetch_kernel(const GroupFetchArgs a) {
+  group_fetch_body<BF16>(a, blockIdx.x, gridDim.x, blockIdx.y);
+}
+
+// The attention over the rows that hit and the lite rows (blocks [0, n_attend) of a head) and
+// the group's shared fetch (the remaining blocks) in one launch: the two do not depend on each
+// other, so the host-link reads run beside the HBM reads.
+template <bool BF16>
+__global__ __launch_bounds__(kAttThreads) void attend_hits_group_fetch_kernel(
+    const AttendArgs a, const GroupFetchArgs f, int n_attend) {
+  if ((int)blockIdx.x < n_attend)
+    attend_partial_body<BF16>(a, blockIdx.x, blockIdx.y);
+  else
+    group_fetch_body<BF16>(f, blockIdx.x - n_attend, gridDim.x - n_attend, blockIdx.y);
 }
 
 constexpr int kCombThreads = 512;
@@ -353,6 +476,60 @@ size_t attend_ws_bytes(int BHq, int k, int w, int phases) {
   return round_up((size_t)BHq * parts * kPartialStride * sizeof(float), 256);
 }
 
+static AttendArgs make_attend_args(const lrqk_shape& s, int mode, const float* q,
+                                   const void* cacheK, const void* cacheV,
+                                   const int32_t* sel_slot, const uint8_t* hit,
+                                   const int32_t* miss_slot, const int32_t* n_miss,
+                                   const void* liteK, const void* liteV, float* partials,
+                                   int rows_per_block, int parts_per_head, int part_offset,
+                                   const void* K_host, const void* V_host,
+                                   const int32_t* sel_idx) {
+  AttendArgs a;
+  a.mode = mode;
+  a.fs = FetchSrc{static_cast<const char*>(K_host), static_cast<const char*>(V_host), sel_idx,
+                  s.l, row_cap(s)};
+  a.q = q;
+  a.cacheK = cacheK;
+  a.cacheV = cacheV;
+  a.sel_slot = sel_slot;
+  a.hit = hit;
+  a.miss_slot = miss_slot;
+  a.n_miss = n_miss;
+  a.liteK = liteK;
+  a.liteV = liteV;
+  a.partials = partials;
+  a.Hq = s.Hq;
+  a.Hkv = s.Hkv;
+  a.C = s.C;
+  a.k = s.k;
+  a.w = s.w;
+  a.rows_per_block = rows_per_block;
+  a.parts_per_head = parts_per_head;
+  a.part_offset = part_offset;
+  a.scale = s.scale;
+  return a;
+}
+
+static GroupFetchArgs make_group_fetch_args(const lrqk_shape& s, const void* K_host,
+                                            const void* V_host, const int32_t* miss_tok,
+                                            const int32_t* miss_slot, const int32_t* n_miss,
+                                            void* cacheK, void* cacheV, int32_t* link_rows) {
+  GroupFetchArgs f;
+  f.fs = FetchSrc{static_cast<const char*>(K_host), static_cast<const char*>(V_host), nullptr,
+                  s.l, row_cap(s)};
+  f.cacheK = cacheK;
+  f.cacheV = cacheV;
+  f.miss_tok = miss_tok;
+  f.miss_slot = miss_slot;
+  f.n_miss = n_miss;
+  f.link_rows = link_rows;
+  f.Hq = s.Hq;
+  f.Hkv = s.Hkv;
+  f.C = s.C;
+  f.k = s.k;
+  return f;
+}
+
 hipError_t launch_attend_partial(const lrqk_shape& s, int mode, const float* q, const void* cacheK,
                                  const void* cacheV, const int32_t* sel_slot, const uint8_t* hit,
                                  const int32_t* miss_slot, const int32_t* n_miss,
@@ -363,19 +540,55 @@ hipError_t launch_attend_partial(const lrqk_shape& s, int mode, const float* q, 
   if (nblocks <= 0) return hipSuccess;
   if (mode == kAttendAllFetch && (!K_host || !V_host || !sel_idx || !hit))
     return hipErrorInvalidValue;
-  const FetchSrc fs{static_cast<const char*>(K_host), static_cast<const char*>(V_host), sel_idx,
-                    s.l, row_cap(s)};
+  const AttendArgs a = make_attend_args(s, mode, q, cacheK, cacheV, sel_slot, hit, miss_slot,
+                                        n_miss, liteK, liteV, partials, rows_per_block,
+                                        parts_per_head, part_offset, K_host, V_host, sel_idx);
   const dim3 grid(nblocks, s.B * s.Hq);
   if (s.kv_dtype == LRQK_KV_BF16)
-    LRQK_LAUNCH((attend_partial_kernel<true>), grid, dim3(kAttThreads), 0, st, mode, fs, q,
-                       cacheK, cacheV, sel_slot, hit, miss_slot, n_miss, liteK, liteV, partials,
-                       s.Hq, s.Hkv, s.C, s.k, s.w, rows_per_block, parts_per_head, part_offset,
-                       s.scale);
+    LRQK_LAUNCH((attend_partial_kernel<true>), grid, dim3(kAttThreads), 0, st, a);
   else
-    LRQK_LAUNCH((attend_partial_kernel<false>), grid, dim3(kAttThreads), 0, st, mode, fs, q,
-                       cacheK, cacheV, sel_slot, hit, miss_slot, n_miss, liteK, liteV, partials,
-                       s.Hq, s.Hkv, s.C, s.k, s.w, rows_per_block, parts_per_head, part_offset,
-                       s.scale);
+    LRQK_LAUNCH((attend_partial_kernel<false>), grid, dim3(kAttThreads), 0, st, a);
+  return hipGetLastError();
+}
+
+// workgroups per head that the shared fetch is spread over (16 rows per pass each)
+static int group_fetch_blocks(const lrqk_shape& s) { return min(ceil_div(s.k, 16), 32); }
+
+hipError_t launch_group_fetch(const lrqk_shape& s, const void* K_host, const void* V_host,
+                              const int32_t* miss_tok, const int32_t* miss_slot,
+                              const int32_t* n_miss, void* cacheK, void* cacheV,
+                              int32_t* link_rows, hipStream_t st) {
+  const GroupFetchArgs f = make_group_fetch_args(s, K_host, V_host, miss_tok, miss_slot, n_miss,
+                                                 cacheK, cacheV, link_rows);
+  const dim3 grid(group_fetch_blocks(s), s.B * s.Hq);
+  if (s.kv_dtype == LRQK_KV_BF16)
+    LRQK_LAUNCH((group_fetch_kernel<true>), grid, dim3(kAttThreads), 0, st, f);
+  else
+    LRQK_LAUNCH((group_fetch_kernel<false>), grid, dim3(kAttThreads), 0, st, f);
+  return hipGetLastError();
+}
+
+hipError_t launch_attend_hits_group_fetch(const lrqk_shape& s, const float* q, void* cacheK,
+                                          void* cacheV, const int32_t* sel_slot,
+                                          const uint8_t* hit, const void* liteK,
+                                          const void* liteV, float* partials, int nblocks,
+                                          int rows_per_block, int parts_per_head,
+                                          const void* K_host, const void* V_host,
+                                          const int32_t* miss_tok, const int32_t* miss_slot,
+                                          const int32_t* n_miss, int32_t* link_rows,
+                                          hipStream_t st) {
+  const AttendArgs a = make_attend_args(s, kAttendHitsAndLite, q, cacheK, cacheV, sel_slot, hit,
+                                        nullptr, nullptr, liteK, liteV, partials, rows_per_block,
+                                        parts_per_head, 0, nullptr, nullptr, nullptr);
+  const GroupFetchArgs f = make_group_fetch_args(s, K_host, V_host, miss_tok, miss_slot, n_miss,
+                                                 cacheK, cacheV, link_rows);
+  const dim3 grid(nblocks + group_fetch_blocks(s), s.B * s.Hq);
+  if (s.kv_dtype == LRQK_KV_BF16)
+    LRQK_LAUNCH((attend_hits_group_fetch_kernel<true>), grid, dim3(kAttThreads), 0, st, a, f,
+                nblocks);
+  else
+    LRQK_LAUNCH((attend_hits_group_fetch_kernel<false>), grid, dim3(kAttThreads), 0, st, a, f,
+                nblocks);
   return hipGetLastError();
 }
 

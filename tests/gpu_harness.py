@@ -104,15 +104,17 @@ class StepBuffers:
         self.miss_tok = torch.full((B, Hq, k), -7, **i32)
         self.miss_slot = torch.full((B, Hq, k), -7, **i32)
         self.n_miss = torch.full((B, Hq), -7, **i32)
+        self.link_rows = torch.full((B, cfg.Hkv), -7, **i32)
 
     def debug(self):
         return dict(sel_idx=self.sel_idx, sel_slot=self.sel_slot, hit=self.hit,
-                    miss_tok=self.miss_tok, miss_slot=self.miss_slot, n_miss=self.n_miss)
+                    miss_tok=self.miss_tok, miss_slot=self.miss_slot, n_miss=self.n_miss,
+                    link_rows=self.link_rows)
 
     def to_np(self):
         torch.cuda.synchronize()
         return {n: getattr(self, n).cpu().numpy() for n in
-                ("sel_idx", "sel_slot", "hit", "miss_tok", "miss_slot", "n_miss")}
+                ("sel_idx", "sel_slot", "hit", "miss_tok", "miss_slot", "n_miss", "link_rows")}
 
 
 def compare_resolution(got: dict, ref: dict, where: str = ""):

@@ -151,6 +151,12 @@ def test_resolve_and_fetch_over_steps(kvd, C, mode):
         compare_state(dl, f"step {step}")
         if mode == "staged":
             assert total == int(ref["n_miss"].sum())
+        if mode == "group":     # rows over the host link: the oracle's shared fetch of the same lists
+            scratchK, scratchV = np.zeros_like(dl.ocK), np.zeros_like(dl.ocV)
+            want_rows, _ = orc.group_fetch(dl.np["K"], dl.np["V"], ref["miss_tok"], ref["miss_slot"],
+                                           ref["n_miss"], scratchK, scratchV)
+            assert np.array_equal(got["link_rows"], want_rows), f"step {step}: rows over the link"
+            link_rows_seen.append((int(want_rows.sum()), int(ref["n_miss"].sum())))
         if step > 0:
             assert 0 < ref["n_miss"].sum() < sel.size     # the case has both hits and misses
     plan.close()
@@ -252,8 +258,10 @@ def run_steps_against_oracle(cfg, n_steps, mode, identity=False, data=None, chec
     qs = QueryStream(data)
     sb = StepBuffers(cfg)
     out = torch.empty((cfg.B, cfg.Hq, cfg.d), device=DEV)
-    fmode = L.LRQK_FETCH_STAGED if mode == "staged" else L.LRQK_FETCH_DIRECT
+    fmode = {"staged": L.LRQK_FETCH_STAGED, "direct": L.LRQK_FETCH_DIRECT,
+             "group": L.LRQK_FETCH_GROUP}[mode]
     miss_rates = []
+    link_rows_seen = []
     for step in range(1, n_steps + 1):
         q, q_hat = qs.next()
         qd, qhd = q.to(DEV), q_hat.to(DEV)
@@ -276,12 +284,20 @@ def run_steps_against_oracle(cfg, n_steps, mode, identity=False, data=None, chec
         assert err <= TOL[cfg.kv_dtype], f"step {step}: attention error {err}"
         if mode == "staged":
             assert total == int(ref["n_miss"].sum())
+        if mode == "group":     # rows over the host link: the oracle's shared fetch of the same lists
+            scratchK, scratchV = np.zeros_like(dl.ocK), np.zeros_like(dl.ocV)
+            want_rows, _ = orc.group_fetch(dl.np["K"], dl.np["V"], ref["miss_tok"], ref["miss_slot"],
+                                           ref["n_miss"], scratchK, scratchV)
+            assert np.array_equal(got["link_rows"], want_rows), f"step {step}: rows over the link"
+            link_rows_seen.append((int(want_rows.sum()), int(ref["n_miss"].sum())))
         if check_unfused and step == 1:
             for name in ("sel_idx", "sel_slot", "hit", "n_miss"):
                 assert np.array_equal(unfused[name], got[name]), f"fused/unfused {name} differ"
             assert np.abs(unfused["out"] - out.cpu().numpy()).max() <= 1e-5
         miss_rates.append(ref["miss_rate"])
     plan.close()
+    if mode == "group":
+        return miss_rates, link_rows_seen
     return miss_rates
 
 
@@ -314,6 +330,56 @@ def test_decode_step_small(kvd, mode):
     say(f"decode_step small kv={kvd} mode={mode}")
     rates = run_steps_against_oracle(small_cfg(kv_dtype=kvd), 5, mode)
     assert rates[0] == 1.0 and rates[-1] < 1.0
+
+
+@pytest.mark.parametrize("share,kvd", [(0.0, "bf16"), (0.5, "bf16"), (1.0, "f32")])
+def test_decode_step_group_shared_fetch(share, kvd):
+    say(f"decode_step, fetch shared inside the KV groups, group_share={share} kv={kvd}")
+    cfg = small_cfg(kv_dtype=kvd, group_share=share, Hq=8, Hkv=2)
+    rates, link = run_steps_against_oracle(cfg, 6, "group", check_unfused=False)
+    union, total = sum(u for u, _ in link[1:]), sum(t for _, t in link[1:])
+    say(f"   rows over the link / rows missed (after the first step): {union} / {total}")
+    if share == 0.0:
+        assert union > 0.9 * total
+    if share == 1.0:
+        assert union * cfg.G == total        # identical queries in a group: one fetch serves all
+
+
+def test_group_fetch_alone_fills_the_same_caches_as_the_oracle():
+    say("lrqk_fetch_misses, LRQK_FETCH_GROUP: caches and shared rows vs the oracle")
+    rng = np.random.default_rng(31)
+    B, Hkv, G, l, C, k, d = 2, 2, 4, 5000, 600, 500, 128
+    Hq = Hkv * G
+    K = torch.randn(B, Hkv, l, d, generator=torch.Generator().manual_seed(1)).bfloat16()
+    V = torch.randn(B, Hkv, l, d, generator=torch.Generator().manual_seed(2)).bfloat16()
+    miss_tok = np.full((B, Hq, k), -1, np.int32)
+    miss_slot = np.full((B, Hq, k), -1, np.int32)
+    n_miss = rng.integers(0, k + 1, size=(B, Hq)).astype(np.int32)
+    n_miss[1, 2] = 0
+    for b in range(B):
+        for kv in range(Hkv):
+            common = rng.choice(l, size=k, replace=False)          # what the group tends to want
+            for h in range(kv * G, (kv + 1) * G):
+                n = n_miss[b, h]
+                mix = np.unique(np.concatenate([rng.choice(common, size=n // 2, replace=False),
+                                                rng.choice(l, size=n - n // 2, replace=False)]))
+                n_miss[b, h] = len(mix)
+                miss_tok[b, h, :len(mix)] = mix
+                miss_slot[b, h, :len(mix)] = rng.permutation(C)[:len(mix)]
+    shp = L.Shape.make(B=B, Hq=Hq, Hkv=Hkv, l=l, r=4, k=k, w=0, C_slots=C)
+    plan = L.Plan(shp)
+    cK = torch.zeros(B, Hq, C, d, dtype=torch.bfloat16, device=DEV)
+    cV = torch.zeros_like(cK)
+    L.lrqk_fetch_misses(plan, shp, K.pin_memory(), V.pin_memory(), torch.from_numpy(miss_tok).to(DEV),
+                        torch.from_numpy(miss_slot).to(DEV), torch.from_numpy(n_miss).to(DEV),
+                        cK, cV, L.LRQK_FETCH_GROUP)
+    torch.cuda.synchronize()
+    oK = np.zeros((B, Hq, C, d), np.uint16)
+    oV = np.zeros_like(oK)
+    rows, _ = orc.group_fetch(as_numpy(K), as_numpy(V), miss_tok, miss_slot, n_miss, oK, oV)
+    assert np.array_equal(as_numpy(cK), oK) and np.array_equal(as_numpy(cV), oV)
+    assert rows.sum() < n_miss.sum()             # the lists do overlap
+    plan.close()
 
 
 @pytest.mark.parametrize("carry", ["off", "unknown_first"])
@@ -409,7 +475,7 @@ def test_config1_all_hits():
     assert rates == [0.0, 0.0]
 
 
-@pytest.mark.parametrize("mode", ["staged", "direct"])
+@pytest.mark.parametrize("mode", ["staged", "direct", "group"])
 def test_config2_shape(mode):
     say(f"config 2: l=32768 k=1024 w=64 C=2048 ({mode})")
     run_steps_against_oracle(get_config("c2"), 4, mode, check_unfused=False)
