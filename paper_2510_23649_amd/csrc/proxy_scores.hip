@@ -96,13 +96,16 @@ __global__ __launch_bounds__(kTileRows) void proxy_scores_kernel(
   // (the tile's loads stay ahead of what follows: it is meant to run in their shadow)
   __builtin_amdgcn_sched_barrier(0);
   // Threshold key of each head of the group.  With carried thresholds |q_hat| is needed:
-  // q_hat is wave-uniform (scalar loads, the same ones the products below use), so the first
-  // wavefront sums the squares with no memory instruction of its own while the tile's loads are
-  // in flight, and hands the keys to the others through LDS (published by the barrier that
-  // follows the tile store).
-  if (FILTER && t < 64) {
+  // q_hat is wave-uniform (scalar loads, the same ones the products below use), so the squares
+  // are summed with no memory instruction of their own while the tile's loads are in flight --
+  // the heads dealt out over the four wavefronts, which keeps this off the workgroup's
+  // critical path -- and the keys are handed to everyone through LDS (published by the
+  // barrier that follows the tile store).
+  if (FILTER) {
+    const int wv = t >> 6;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
+      if ((g & 3) != wv) continue;  // wave-uniform
       uint32_t key;
       if (thr_norm != nullptr) {
         float q2 = 0.0f;
@@ -113,7 +116,7 @@ __global__ __launch_bounds__(kTileRows) void proxy_scores_kernel(
       } else {
         key = thr[bh0 + g];
       }
-      if (t == 0) *thr_slot(g) = key;
+      if ((t & 63) == 0) *thr_slot(g) = key;
     }
   }
 
@@ -154,25 +157,33 @@ __global__ __launch_bounds__(kTileRows) void proxy_scores_kernel(
     // The 64 rows of the tile that this wavefront owns are read by no other wavefront, so
     // their LDS space can stage the packed candidate scores without a workgroup barrier.
     float* stage = reinterpret_cast<float*>(&tile[(t & ~63) * ROW4]);
+    // The packed scores of all G heads are staged together and leave with one store
+    // instruction (lane = head * 8 + entry), the G ballots with another (lane = head): the
+    // per-head part is the compare, the ballot and one LDS write.
+    static_assert(G * kCandPerGroup <= 64, "one lane per packed entry");
+    if (lane < G * kCandPerGroup) stage[lane] = 0.0f;
+    __builtin_amdgcn_wave_barrier();
+    const unsigned long long below = (1ull << lane) - 1ull;
+    const int my_head = lane >> 3;       // head of this lane in the two stores below
+    unsigned long long mask_of_my_head = 0ull, mask_of_lane_head = 0ull;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      const size_t bh = bh0 + g;
       const uint32_t thr_g = *thr_slot(g);
-      if (blockIdx.x == 0 && t == 0) thr_out[bh] = thr_g;
+      if (blockIdx.x == 0 && t == 0) thr_out[bh0 + g] = thr_g;
       const bool in = row < n && dev::order_key(acc[g]) >= thr_g;
       const unsigned long long mask = __ballot(in);
-      if (lane == 0 && wrow < n) bitmap[bh * words64 + (wrow >> 6)] = mask;
-      if (mask != 0ull) {  // wave-uniform
-        const int rank = __popcll(mask & ((1ull << lane) - 1ull));
-        if (lane < kCandPerGroup) stage[g * kCandPerGroup + lane] = 0.0f;
-        __builtin_amdgcn_wave_barrier();
-        if (in && rank < kCandPerGroup) stage[g * kCandPerGroup + rank] = acc[g];
-        __builtin_amdgcn_wave_barrier();
-        // one 32-byte store per wavefront and head instead of scattered 4-byte ones
-        if (lane < kCandPerGroup)
-          cand_scores[(bh * words64 + (wrow >> 6)) * kCandPerGroup + lane] =
-              stage[g * kCandPerGroup + lane];
-      }
+      const int rank = __popcll(mask & below);
+      if (in && rank < kCandPerGroup) stage[g * kCandPerGroup + rank] = acc[g];
+      if (my_head == g) mask_of_my_head = mask;
+      if (lane == g) mask_of_lane_head = mask;
+    }
+    __builtin_amdgcn_wave_barrier();
+    if (wrow < n) {
+      const size_t grp = (size_t)(wrow >> 6);
+      if (lane < G) bitmap[(bh0 + lane) * words64 + grp] = mask_of_lane_head;
+      // a head without candidates in this group leaves its entries alone (they are not read)
+      if (lane < G * kCandPerGroup && mask_of_my_head != 0ull)
+        cand_scores[((bh0 + my_head) * words64 + grp) * kCandPerGroup + (lane & 7)] = stage[lane];
     }
   }
 }

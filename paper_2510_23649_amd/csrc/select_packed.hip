@@ -40,10 +40,10 @@
 #include "select_common.h"
 
 #ifdef LRQK_KPROF
-__device__ unsigned long long g_kprof[32 + 2 * 64];
-#define KPROF(i)                                                          \
-  do {                                                                    \
-    if (blockIdx.x == 0 && threadIdx.x == 0) g_kprof[i] = wall_clock64(); \
+__device__ unsigned long long g_kprof[64 * 16];
+#define KPROF(i)                                                                        \
+  do {                                                                                  \
+    if (blockIdx.x < 64 && threadIdx.x == 0) g_kprof[blockIdx.x * 16 + i] = wall_clock64(); \
   } while (0)
 extern "C" __attribute__((visibility("default"))) int lrqk_kprof_read(unsigned long long* out) {
   return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_kprof), sizeof(g_kprof));
@@ -745,9 +745,6 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
   }
   lds_barrier();
   KPROF(11);
-#ifdef LRQK_KPROF
-  if (threadIdx.x == 0 && blockIdx.x < 64) g_kprof[32 + 2 * blockIdx.x + 1] = wall_clock64();
-#endif
   if (t == 0) a.n_miss[bh] = sh_bad ? -1 : nm;
 }
 
