@@ -134,22 +134,27 @@ class Workload:
 
     def kernel_times(self, queries, repeat_each=False):
         """Microseconds per step of every kernel of the step (events attached to the kernels).
-        repeat_each: every query is stepped twice and only the second step is timed -- its
-        selection is the one just made, so nothing misses."""
+        repeat_each: the queries are stepped in rounds over the layers, every round twice, and
+        only the second time is timed -- its selections are the ones just made, so nothing
+        misses, while a whole round over the other layers lies between the two visits of a
+        layer (no cache holds its rows)."""
         cfg = self.cfg
         self.plan.profile(len(queries))
-        miss = 0
-        for i, (q, q_hat) in enumerate(queries):
-            li = i % self.nl
+        miss = counted = 0
+        for r0 in range(0, len(queries), self.nl):
+            chunk = queries[r0:r0 + self.nl]
             if repeat_each:
-                self._untimed_step(li, q, q_hat)
-            self.step(li, q, q_hat, debug=dict(n_miss=self.n_miss))
-            miss += int(self.n_miss.clamp(min=0).sum().item()) if i < 8 or repeat_each else 0
+                for i, (q, q_hat) in enumerate(chunk):
+                    self._untimed_step(i % self.nl, q, q_hat)
+            for i, (q, q_hat) in enumerate(chunk):
+                self.step(i % self.nl, q, q_hat, debug=dict(n_miss=self.n_miss))
+                if repeat_each or counted < 8:
+                    miss += int(self.n_miss.clamp(min=0).sum().item())
+                    counted += 1
         ms, n = self.plan.profile_read()
         self.plan.profile(0)
         us = {k: 1e3 * v / max(n, 1) for k, v in ms.items() if v > 0.0}
-        counted = len(queries) if repeat_each else min(len(queries), 8)
-        return us, miss / (counted * cfg.B * cfg.Hq * cfg.k)
+        return us, miss / (max(counted, 1) * cfg.B * cfg.Hq * cfg.k)
 
     def _untimed_step(self, li, q, q_hat):
         # a step that takes no slot of the armed profile: it runs on a second plan

@@ -220,7 +220,7 @@ int lrqk_sparse_attend(const lrqk_shape* shape, const float* q, const void* cach
  * the library (one copy per GPU, held until the process ends).  The call allocates and frees
  * nothing, on the host side of HIP or the device.
  *   LRQK_ENOMEM if lrqk_workspace_bytes(shape, LRQK_WS_ATTEND) exceeds the array (nothing is
- *   enqueued).  At the headline shape (32 heads, k = 2048, w = 64) the call needs 0.6 MB.
+ *   enqueued).  At the headline shape (32 heads, k = 2048, w = 64) the call needs 1.2 MB.
  * Every call on a GPU uses that GPU's one array: two calls whose work overlaps on the same
  * GPU (different streams, or threads) race.  Calls on one stream are ordered and safe.
  */

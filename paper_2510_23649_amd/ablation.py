@@ -18,6 +18,8 @@ lite tokens, not what a language model would produce):
   --group-fetch  the fetch leg per head against the fetch shared by the query heads of a KV
                  group (a row missed by several heads crosses the host link once), for heads
                  that want the same tokens to different degrees.
+  --attend-all-hit  step a5 alone (lrqk_sparse_attend) on caches that hold every selected row,
+                 for profiling the attention kernels with nothing to fetch.
   --end-to-end   the whole method in sequence: prefill factorisation of a synthetic prompt,
                  then decode steps (factor update, append, proxy top-k, fetch, attention) on
                  the factors it produced; reports the recall of the exact top-k and the
@@ -190,6 +192,45 @@ def group_fetch_ab(steps: int, layers: int, out=sys.stdout):
             del lbs, streams
 
 
+def attend_all_hit(steps: int, layers: int, out=sys.stdout):
+    """Step a5 alone on caches that hold every selected row (lrqk_sparse_attend on the slots of
+    each layer's last selection, layers in rotation): the attention kernels with nothing to
+    fetch, e.g. to profile them."""
+    from gen import get_config, make_layer, QueryStream
+    cfg = get_config("c3").with_(layers=layers)
+    shape = _shape(cfg)
+    lbs, sel, qs = [], [], []
+    plan = L.Plan(shape)
+    out_t = torch.empty((cfg.B, cfg.Hq, cfg.d), device="cuda")
+    for li in range(layers):
+        data = make_layer(cfg, li, device="cuda")
+        lb = LayerBuffers(shape, data.A_K, data.K, data.V)
+        stream = QueryStream(data)
+        sel_slot = torch.zeros((cfg.B, cfg.Hq, cfg.k), dtype=torch.int32, device="cuda")
+        for step in range(1, 3):
+            q, q_hat = stream.next()
+            L.lrqk_decode_step(plan, shape, step, lb.struct, q_hat, q, out_t,
+                               L.LRQK_FETCH_DIRECT | (L.LRQK_SELECT_FRESH if step == 1 else 0),
+                               dict(sel_slot=sel_slot))
+        lbs.append(lb)
+        sel.append(sel_slot)
+        qs.append(q)
+    ws = torch.empty(L.lrqk_workspace_bytes(shape, L.LRQK_WS_ATTEND), dtype=torch.uint8,
+                     device="cuda")
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        li = i % layers
+        L.lrqk_sparse_attend(shape, qs[li], lbs[li].cacheK, lbs[li].cacheV, sel[li], lbs[li].liteK,
+                             lbs[li].liteV, out_t, ws)
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t0) / steps * 1e6
+    nbytes = 2 * 2 * cfg.d * (cfg.B * cfg.Hq * cfg.k + cfg.B * cfg.Hkv * cfg.w)
+    print(f"{steps} calls of lrqk_sparse_attend, {layers} layers in rotation: {us:.1f} us per call "
+          f"(host loop included), {nbytes / 1e6:.1f} MB of K/V rows per call", file=out)
+    plan.close()
+
+
 def end_to_end(steps: int, out=sys.stdout):
     """Prefill factorisation, then Alg. 2 decode steps on the factors it produced; reports how
     much of the exact top-k of q K^T the proxy selects and how far the sparse attention output
@@ -281,6 +322,7 @@ def main():
     ap.add_argument("--no-hit-miss", action="store_true")
     ap.add_argument("--end-to-end", action="store_true")
     ap.add_argument("--group-fetch", action="store_true")
+    ap.add_argument("--attend-all-hit", action="store_true")
     ap.add_argument("--steps", type=int, default=64)
     ap.add_argument("--warm", type=int, default=8)
     ap.add_argument("--layers", type=int, default=8)
@@ -290,7 +332,10 @@ def main():
     args = ap.parse_args()
     if not torch.cuda.is_available():
         sys.exit("ablation: needs a GPU")
-    both = not (args.grid or args.no_hit_miss or args.end_to_end or args.group_fetch)
+    both = not (args.grid or args.no_hit_miss or args.end_to_end or args.group_fetch
+                or args.attend_all_hit)
+    if args.attend_all_hit:
+        attend_all_hit(args.steps, args.layers)
     if args.grid or both:
         print("## Miss-rate grid (Sec. 5.3), l = 4096, 32 q / 8 kv heads, cache of k slots, "
               f"query drift {args.drift} of the heavy window per step\n")

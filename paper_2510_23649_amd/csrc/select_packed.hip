@@ -39,21 +39,6 @@
 #include "lrqk_internal.h"
 #include "select_common.h"
 
-#ifdef LRQK_KPROF
-__device__ unsigned long long g_kprof[64 * 16];
-#define KPROF(i)                                                                        \
-  do {                                                                                  \
-    if (blockIdx.x < 64 && threadIdx.x == 0) g_kprof[blockIdx.x * 16 + i] = wall_clock64(); \
-  } while (0)
-extern "C" __attribute__((visibility("default"))) int lrqk_kprof_read(unsigned long long* out) {
-  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_kprof), sizeof(g_kprof));
-}
-#else
-#define KPROF(i) \
-  do {           \
-  } while (0)
-#endif
-
 namespace lrqk {
 namespace {
 
@@ -94,6 +79,21 @@ __device__ __forceinline__ void lds_barrier() {
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
+// Prefix sum over the 16 wave totals held in wt[0..16): returns the sum of the totals of the
+// wavefronts before this one, and the grand total.  Lanes 0..15 of every wavefront read one
+// total each and scan them with DPP row shifts (one LDS read instead of sixteen per thread).
+__device__ __forceinline__ uint32_t waves_before(const uint32_t* wt, uint32_t* total) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  uint32_t v = wt[lane & 15];
+  uint32_t incl = v;
+  incl += dpp_zero_fill<0x111, 0xf>(incl);  // row_shr:1
+  incl += dpp_zero_fill<0x112, 0xf>(incl);  // row_shr:2
+  incl += dpp_zero_fill<0x114, 0xf>(incl);  // row_shr:4
+  incl += dpp_zero_fill<0x118, 0xf>(incl);  // row_shr:8
+  *total = (uint32_t)__builtin_amdgcn_readlane((int)incl, 15);
+  return (uint32_t)__builtin_amdgcn_readlane((int)(incl - v), wv);
+}
+
 // Exclusive prefix sum over the 1024 threads and the total, with LDS-only barriers.
 // wt: 16 words of LDS.
 __device__ __forceinline__ uint32_t scan1(uint32_t v, uint32_t* wt, uint32_t* total) {
@@ -102,15 +102,7 @@ __device__ __forceinline__ uint32_t scan1(uint32_t v, uint32_t* wt, uint32_t* to
   lds_barrier();  // wt may still be read from an earlier call
   if (lane == 63) wt[wv] = incl;
   lds_barrier();
-  uint32_t before = 0, tot = 0;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    const uint32_t c = wt[i];
-    before += i < wv ? c : 0u;
-    tot += c;
-  }
-  *total = tot;
-  return before + incl - v;
+  return waves_before(wt, total) + incl - v;
 }
 // The same for two values at once (shared barriers).  wt: 32 words of LDS.
 __device__ __forceinline__ void scan2(uint32_t v0, uint32_t v1, uint32_t* wt, uint32_t* ex0,
@@ -123,19 +115,8 @@ __device__ __forceinline__ void scan2(uint32_t v0, uint32_t v1, uint32_t* wt, ui
     wt[16 + wv] = i1;
   }
   lds_barrier();
-  uint32_t b0 = 0, b1 = 0, t0 = 0, t1 = 0;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    const uint32_t c0 = wt[i], c1 = wt[16 + i];
-    b0 += i < wv ? c0 : 0u;
-    b1 += i < wv ? c1 : 0u;
-    t0 += c0;
-    t1 += c1;
-  }
-  *ex0 = b0 + i0 - v0;
-  *ex1 = b1 + i1 - v1;
-  *tot0 = t0;
-  *tot1 = t1;
+  *ex0 = waves_before(wt, tot0) + i0 - v0;
+  *ex1 = waves_before(wt + 16, tot1) + i1 - v1;
 }
 
 // Scan of a 2048-bin histogram from the top (thread t owns bins 2t, 2t+1) for two ranks at
@@ -226,8 +207,6 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
   int32_t* __restrict__ to = a.token_of + (size_t)bh * C;
   int32_t* __restrict__ lu = a.last_used + (size_t)bh * C;
   const int32_t step = a.step;
-
-  KPROF(0);
   // ---- 0. every load that does not depend on the selection -----------------------------------
   const int ngroups = (n + 63) >> 6;
   const unsigned long long* __restrict__ bm = a.bitmap + (size_t)bh * a.words64;
@@ -271,7 +250,6 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
     sh_clip = 0u;
   }
   lds_barrier();
-  KPROF(1);
 
   // ---- 1. the thread's candidates: key and position of each, histogram of the keys ---------------
   // Every candidate's key is >= thr_key.  Bin of a key: (key - thr_key) >> s, the top bin
@@ -376,9 +354,7 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
   float thr_next;
 
   lds_barrier();
-  KPROF(2);
   uint32_t m = find_two_from_top(hist0, (uint32_t)k, rank_next, wave_tot, res);
-  KPROF(3);
   uint32_t d0 = res[0], above0 = res[1], d_next = res[3];
   const bool fast = m >= (uint32_t)k && sh_ov <= (uint32_t)kOvCap;
 
@@ -530,7 +506,6 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
       a.sel_thr[bh] = (nrm > 0.0f && isfinite(v)) ? v : __uint_as_float(0x7fc00000u);
     }
   }
-  KPROF(4);
 
   // slot_of of the thread's selected positions (selected packed candidates: in registers)
   int32_t slot[GPT][kCandPerGroup];
@@ -560,11 +535,9 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
       tb &= tb - 1ull;
     }
   }
-  KPROF(5);
   // ---- 3. places in the outputs: one prefix count over (selected, missing) ---------------------------
   uint32_t j, mrank, tot_sel, tot_miss;
   scan2(nsel, nmiss, wave_tot, &j, &mrank, &tot_sel, &tot_miss);
-  KPROF(6);
   const int nm = (int)tot_miss;
   int32_t* __restrict__ out = a.sel_idx + (size_t)bh * k;
   int32_t* __restrict__ ss = a.sel_slot + (size_t)bh * k;
@@ -621,7 +594,6 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
     }
   }
   lds_barrier();
-  KPROF(7);
 
   // ---- 4. victims ------------------------------------------------------------------------------------
   if (nm > 0) {
@@ -640,7 +612,6 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
       }
     }
     lds_barrier();
-    KPROF(8);
     // scan the age classes from the oldest: eligible slots above each class, and the number of
     // non-empty classes above it.  A non-empty class with fewer than nm slots above it holds
     // victims; its number among those classes is its index in cls_age / cls_base.
@@ -669,7 +640,6 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
       }
       lds_barrier();
     }
-    KPROF(9);
     const int ncls = (int)sh_ncls;
     // ages beyond the histogram's range share its last class, which then does not order them
     const bool clipped = sh_clip != 0u && step > kAgeBins - 1;
@@ -724,7 +694,6 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
       for (int jj = t; jj < nv; jj += kT) vsorted[jj] = (int32_t)(uint32_t)vlist[jj];
       __syncthreads();
     }
-    KPROF(10);
     for (int jj = t; jj < nm; jj += kT) {
       if (jj >= nv) {  // ran out of victims (the caller reused `step`)
         atomicOr(&sh_bad, 1u);
@@ -744,7 +713,6 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
     }
   }
   lds_barrier();
-  KPROF(11);
   if (t == 0) a.n_miss[bh] = sh_bad ? -1 : nm;
 }
 
