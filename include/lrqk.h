@@ -56,7 +56,7 @@ typedef enum lrqk_status {
   LRQK_ESHAPE = -2, /* sizes inconsistent or outside the supported range         */
   LRQK_EHIP = -3,   /* a HIP runtime call failed; see lrqk_last_hip_error()      */
   LRQK_ENOMEM = -4, /* workspace too small, or an allocation in plan_create failed */
-  LRQK_ESTATE = -5  /* the cache state handed in is unusable (see cache_resolve)  */
+  LRQK_ESTATE = -5  /* the cache state handed in is unusable (see lrqk_fetch_misses)   */
 } lrqk_status;
 
 enum { LRQK_KV_BF16 = 0, LRQK_KV_F32 = 1 };
@@ -251,7 +251,9 @@ int lrqk_plan_destroy(lrqk_plan* plan);
  *         synchronisation (GROUP needs the miss lists ascending, as lrqk_cache_resolve and
  *         lrqk_decode_step write them).
  *   total_miss_out  host int64*, optional: total rows fetched (STAGED only; the others write -1).
- * Heads with n_miss < 0 are skipped.
+ * A head with n_miss < 0 (lrqk_cache_resolve could not place its misses): STAGED returns
+ * LRQK_ESTATE after the synchronisation, with nothing copied; DIRECT and GROUP, which never see
+ * the lists on the host, skip that head (its n_miss stays the only report).
  */
 int lrqk_fetch_misses(lrqk_plan* plan, const lrqk_shape* shape, const void* K_host,
                       const void* V_host, const int32_t* miss_tok, const int32_t* miss_slot,

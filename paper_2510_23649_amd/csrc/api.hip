@@ -468,6 +468,10 @@ static int staged_fetch(lrqk_plan* p, const lrqk_shape& s, const void* K_host, c
   }
   int64_t total = 0;
   int mx = 0;
+  // a head whose resolution failed (out of victims, reused step, unusable map) reports -1: its
+  // missing rows cannot be fetched, so nothing further is enqueued
+  for (size_t bh = 0; bh < BHq; ++bh)
+    if (p->h_nmiss[bh] < 0) return LRQK_ESTATE;
   for (size_t bh = 0; bh < BHq; ++bh) {
     const int nm = p->h_nmiss[bh];
     const int cnt = nm <= 0 ? 0 : (nm < s.k ? nm : s.k);

@@ -161,14 +161,9 @@ hipError_t launch_cache_resolve(const lrqk_shape& s, const int32_t* sel_idx, int
   const int Cpad = next_pow2(s.C < 2 ? 2 : s.C);
   const size_t lds = (size_t)Cpad * sizeof(uint64_t);
   if (lds > 48 * 1024) {  // large caches need the dynamic-LDS ceiling raised once
-    static bool raised = false;
-    if (!raised) {
-      const hipError_t e =
-          hipFuncSetAttribute(reinterpret_cast<const void*>(cache_resolve_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024);
-      if (e != hipSuccess) return e;
-      raised = true;
-    }
+    static std::atomic<uint64_t> raised{0};
+    const hipError_t e = raise_dynamic_lds_once(cache_resolve_kernel, 64 * 1024, raised);
+    if (e != hipSuccess) return e;
   }
   LRQK_LAUNCH(cache_resolve_kernel, dim3(s.B * s.Hq), dim3(kResThreads), lds, st, sel_idx,
                      step, s.l, row_cap(s), s.C, Cpad, s.k, slot_of, token_of, last_used, sel_slot, hit,

@@ -5,6 +5,8 @@
 #include <hip/hip_ext.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "lrqk.h"
 
 namespace lrqk {
@@ -52,6 +54,21 @@ LaunchTimer& launch_timer();
       hipLaunchKernelGGL(kern, grid, block, lds, st, __VA_ARGS__);                          \
     }                                                                                       \
   } while (0)
+
+// Raises a kernel's dynamic-LDS ceiling once per device (bit d of `done` = done on device d);
+// safe to call from several threads (a repeated call is harmless).
+template <typename K>
+inline hipError_t raise_dynamic_lds_once(K kernel, size_t bytes, std::atomic<uint64_t>& done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const uint64_t bit = 1ull << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+  return e;
+}
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }

@@ -718,14 +718,10 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
 
 template <int GPT, int SPT>
 hipError_t launch_inst(const PackedArgs& a, int BHq, size_t lds, hipStream_t st) {
-  static bool raised = false;  // the dynamic-LDS ceiling of this instantiation, raised once
-  if (!raised) {
-    const hipError_t e = hipFuncSetAttribute(
-        reinterpret_cast<const void*>(select_packed_kernel<GPT, SPT>),
-        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kPackedLdsLimit);
-    if (e != hipSuccess) return e;
-    raised = true;
-  }
+  static std::atomic<uint64_t> raised{0};  // devices on which this instantiation's ceiling is up
+  const hipError_t e =
+      raise_dynamic_lds_once(select_packed_kernel<GPT, SPT>, kPackedLdsLimit, raised);
+  if (e != hipSuccess) return e;
   LRQK_LAUNCH((select_packed_kernel<GPT, SPT>), dim3(BHq), dim3(kT), lds, st, a);
   return hipGetLastError();
 }

@@ -466,13 +466,8 @@ constexpr size_t kLdsLimit = 150 * 1024;
 
 template <bool RESOLVE>
 hipError_t raise_lds_limit() {
-  static bool done = false;
-  if (done) return hipSuccess;
-  const hipError_t e = hipFuncSetAttribute(
-      reinterpret_cast<const void*>(select_resolve_kernel<RESOLVE>),
-      hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsLimit);
-  if (e == hipSuccess) done = true;
-  return e;
+  static std::atomic<uint64_t> done{0};
+  return raise_dynamic_lds_once(select_resolve_kernel<RESOLVE>, kLdsLimit, done);
 }
 
 }  // namespace

@@ -182,6 +182,17 @@ def test_resolve_contract_violations_do_not_fault():
     got = sb.to_np()
     assert got["n_miss"][0, 0] == -1           # every slot is protected: no victims
     assert (got["sel_slot"][0, 0] == -1).all()
+    # the staged fetch sees the lists on the host and refuses them; the device-side fetches skip
+    plan = L.Plan(shp)
+    with pytest.raises(L.LrqkError) as e:
+        L.lrqk_fetch_misses(plan, shp, dl.K_host, dl.V_host, sb.miss_tok, sb.miss_slot, sb.n_miss,
+                            dl.cacheK, dl.cacheV, L.LRQK_FETCH_STAGED)
+    assert e.value.status == -5
+    for mode in (L.LRQK_FETCH_DIRECT, L.LRQK_FETCH_GROUP):
+        L.lrqk_fetch_misses(plan, shp, dl.K_host, dl.V_host, sb.miss_tok, sb.miss_slot, sb.n_miss,
+                            dl.cacheK, dl.cacheV, mode)
+    torch.cuda.synchronize()
+    plan.close()
 
 
 # ------------------------------------------------------------------------------- a5
@@ -460,7 +471,7 @@ def test_decode_step_misleading_threshold_sample(factor):
 
 
 def test_decode_step_clustered_candidates():
-    say("decode_step with > 16 candidates inside single 64-position groups")
+    say("decode_step with more than 8 candidates inside single 64-position groups")
     cfg = small_cfg(B=1, Hq=8, Hkv=2, l=70000, r=32, k=1024, w=64, C=2048, n_heavy=64)
     data = make_layer(cfg)
     data.A_K[:, :, 5000:5200, :] *= 6.0          # 200 consecutive rows with large |score|
