@@ -94,22 +94,22 @@ __device__ __forceinline__ uint32_t waves_before(const uint32_t* wt, uint32_t* t
   return (uint32_t)__builtin_amdgcn_readlane((int)(incl - v), wv);
 }
 
-// Exclusive prefix sum over the 1024 threads and the total, with LDS-only barriers.
-// wt: 16 words of LDS.
+// Exclusive prefix sum over the 1024 threads and the total, with ONE LDS-only barrier.
+// wt: 16 words of LDS that no thread may still be reading from an earlier scan: consecutive
+// scans take different areas (scan_area), and an area comes round again only after two
+// other barriers.
 __device__ __forceinline__ uint32_t scan1(uint32_t v, uint32_t* wt, uint32_t* total) {
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const uint32_t incl = wave_inclusive_scan(v);
-  lds_barrier();  // wt may still be read from an earlier call
   if (lane == 63) wt[wv] = incl;
   lds_barrier();
   return waves_before(wt, total) + incl - v;
 }
-// The same for two values at once (shared barriers).  wt: 32 words of LDS.
+// The same for two values at once.  wt: 32 words of LDS, as above.
 __device__ __forceinline__ void scan2(uint32_t v0, uint32_t v1, uint32_t* wt, uint32_t* ex0,
                                       uint32_t* ex1, uint32_t* tot0, uint32_t* tot1) {
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const uint32_t i0 = wave_inclusive_scan(v0), i1 = wave_inclusive_scan(v1);
-  lds_barrier();
   if (lane == 63) {
     wt[wv] = i0;
     wt[16 + wv] = i1;
@@ -176,7 +176,8 @@ struct PackedArgs {
 template <int GPT, int SPT>
 __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  __shared__ uint32_t wave_tot[2 * kWaves];
+  __shared__ uint32_t wave_tot[4 * 2 * kWaves];  // four areas of 32 words, used in rotation
+  auto scan_area = [&](int i) { return wave_tot + (i & 3) * 2 * kWaves; };
   __shared__ uint32_t res[4];
   __shared__ uint32_t sh_ov, sh_small_n, sh_bad, sh_ncls, sh_clip;
   __shared__ uint64_t sh_cut;
@@ -354,7 +355,7 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
   float thr_next;
 
   lds_barrier();
-  uint32_t m = find_two_from_top(hist0, (uint32_t)k, rank_next, wave_tot, res);
+  uint32_t m = find_two_from_top(hist0, (uint32_t)k, rank_next, scan_area(0), res);
   uint32_t d0 = res[0], above0 = res[1], d_next = res[3];
   const bool fast = m >= (uint32_t)k && sh_ov <= (uint32_t)kOvCap;
 
@@ -367,28 +368,33 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
       lds_barrier();
       for_each_candidate([&](uint32_t kk, int, int) { atomicAdd(&hist0[bin_of(kk)], 1u); });
       lds_barrier();
-      m = find_two_from_top(hist0, (uint32_t)k, rank_next, wave_tot, res);
+      m = find_two_from_top(hist0, (uint32_t)k, rank_next, scan_area(1), res);
       d0 = res[0];
       above0 = res[1];
       d_next = res[3];
     }
     const uint32_t c0 = hist0[d0];
     const uint32_t want1 = (uint32_t)k - above0;  // how many of bin d0 are selected
+    uint64_t cut;
     if (c0 <= (uint32_t)kSmall) {
-      // the few candidates of bin d0 are ranked on (key, position) by the first wavefront; the
-      // want1-th of them is the cut
+      // the few candidates of bin d0 are ranked on (key, position); the want1-th of them is
+      // the cut
       for_each_candidate([&](uint32_t kk, int g, int bp) {
         if (bin_of(kk) == d0) small[atomicAdd(&sh_small_n, 1u)] = value_of(kk, g, bp);
       });
       lds_barrier();
-      if (wv == 0) {
+      {
+        // every wavefront ranks the bin for itself (no second barrier to hand the cut over)
         const uint64_t mine = lane < (int)c0 ? small[lane] : 0ull;
         uint32_t larger = 0;
 #pragma unroll 8
         for (uint32_t jj = 0; jj < c0; ++jj) larger += small[jj] > mine ? 1u : 0u;
-        if (lane < (int)c0 && larger == want1 - 1u) sh_cut = mine;
+        const unsigned long long is_cut = __ballot(lane < (int)c0 && larger == want1 - 1u);
+        const int src = __builtin_ctzll(is_cut);  // exactly one entry has that rank
+        const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(mine >> 32), src);
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)mine, src);
+        cut = ((uint64_t)hi << 32) | lo;
       }
-      lds_barrier();
     } else {
       // many candidates in the bin (ties): further histogram levels over the low s bits give
       // the exact key tau of the k-th largest; of the candidates with that key the first
@@ -445,8 +451,8 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
         }
       }
       __syncthreads();
+      cut = sh_cut;
     }
-    const uint64_t cut = sh_cut;
     // ---- 2. the selection = candidates at or above the cut; their slot_of look-ups ---------------
 #pragma unroll
     for (int g = 0; g < GPT; ++g) {
@@ -537,7 +543,7 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
   }
   // ---- 3. places in the outputs: one prefix count over (selected, missing) ---------------------------
   uint32_t j, mrank, tot_sel, tot_miss;
-  scan2(nsel, nmiss, wave_tot, &j, &mrank, &tot_sel, &tot_miss);
+  scan2(nsel, nmiss, scan_area(2), &j, &mrank, &tot_sel, &tot_miss);
   const int nm = (int)tot_miss;
   int32_t* __restrict__ out = a.sel_idx + (size_t)bh * k;
   int32_t* __restrict__ ss = a.sel_slot + (size_t)bh * k;
@@ -546,8 +552,8 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
   int32_t* __restrict__ ms = a.miss_slot + (size_t)bh * k;
   {
     // staged in LDS in output order (the thread's own entries are scattered lanes of many
-    // predicated stores); the global stores follow, coalesced
-    lds_barrier();  // every thread has made its decisions: the selection's LDS is free
+    // predicated stores); the global stores follow, coalesced.  (Every thread has made its
+    // decisions before the barrier of the prefix count above: the selection's LDS is free.)
     auto emit = [&](int p, int32_t sl) {
       if (j >= (uint32_t)k) return;  // cannot happen: exactly k positions are selected
       sel_o[j] = p;
@@ -620,7 +626,7 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
       const uint32_t c0b = ahist[2 * t], c1b = ahist[2 * t + 1];
       const uint32_t e0 = c0b ? 1u : 0u, e1 = c1b ? 1u : 0u;
       uint32_t bc, be, ne;
-      scan2(c0b + c1b, e0 + e1, wave_tot, &bc, &be, &n_elig, &ne);
+      scan2(c0b + c1b, e0 + e1, scan_area(3), &bc, &be, &n_elig, &ne);
       const uint32_t above1 = n_elig - bc - c0b - c1b, ne_above1 = ne - be - e0 - e1;
       const uint32_t above0 = above1 + c1b, ne_above0 = ne_above1 + e1;
       if (c1b && above1 < (uint32_t)nm) {
@@ -662,7 +668,7 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
             hi += (age[u] == ca[2] ? 1u : 0u) + (age[u] == ca[3] ? 1u << 16 : 0u);
           }
         uint32_t exlo, exhi, tl, th;
-        scan2(lo, hi, wave_tot, &exlo, &exhi, &tl, &th);
+        scan2(lo, hi, scan_area(c4 >> 2), &exlo, &exhi, &tl, &th);
         uint32_t before[4] = {cb[0] + (exlo & 0xffffu), cb[1] + (exlo >> 16),
                               cb[2] + (exhi & 0xffffu), cb[3] + (exhi >> 16)};
 #pragma unroll
