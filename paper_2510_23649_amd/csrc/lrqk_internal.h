@@ -110,7 +110,7 @@ hipError_t launch_proxy_scores(const lrqk_shape& s, const float* A_K, const floa
 // head, then scores plus a bitmap of the positions at or above that bin.
 inline int filter_words64(int n) { return (n + 63) / 64; }
 bool proxy_filter_supported(const lrqk_shape& s);
-constexpr int kThrMaxSamples = 8192;  // sample scores kept per head
+constexpr int kThrMaxSamples = 16384;  // sample scores kept per head
 // samples: [BHq][kThrMaxSamples] floats
 hipError_t launch_proxy_threshold(const lrqk_shape& s, const float* A_K, const float* q_hat,
                                   float* samples, uint32_t* thr, hipStream_t st);

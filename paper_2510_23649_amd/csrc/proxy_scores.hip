@@ -390,8 +390,10 @@ bool proxy_filter_supported(const lrqk_shape& s) {
 hipError_t launch_proxy_threshold(const lrqk_shape& s, const float* A_K, const float* q_hat,
                                   float* samples, uint32_t* thr, hipStream_t st) {
   const int n = s.l - s.w;
-  int SS = 1;  // every SS-th row, about 4096 samples per head once the context is long enough
-  while (SS < 256 && n / (SS * 2) >= 2048) SS *= 2;
+  // every SS-th row, 8192 .. 16384 samples per head once the context is long enough (with
+  // fewer, the six-sigma margin of the estimate lets more than the selection's capacity through)
+  int SS = 1;
+  while (SS < 256 && n / (SS * 2) >= 8192) SS *= 2;
   if (n / SS >= kThrMaxSamples) SS *= 2;  // very long contexts: stay inside the sample buffer
   while (n / SS >= kThrMaxSamples) SS *= 2;
   const int off = SS >> 1;
