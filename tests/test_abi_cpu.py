@@ -89,6 +89,13 @@ def test_entry_points_reject_bad_arguments_before_any_device_work(lib):
     assert raw.lrqk_decode_step(None, C.byref(s), 0, None, A, A, A, 0, None, None, None) == -1
     assert raw.lrqk_decode_step(None, C.byref(s), 0, C.byref(lay), A, A, A, 7, None, None, None) == -1
     assert raw.lrqk_fetch_misses(None, C.byref(s), A, A, A, A, A, A, A, 0, None, None) == -1
+    assert raw.lrqk_fetch_misses(None, C.byref(s), A, A, A, A, A, A, A, 3, None, None) == -1   # mode
+    assert raw.lrqk_select_state_init(C.byref(s), None, None) == -1
+    assert raw.lrqk_select_state_init(C.byref(s), A + 4, None) == -1
+    assert raw.lrqk_select_state_init(C.byref(b), A, None) == -2
+    lay_bad = lib.Layer(*([A] * 10 + [A + 4]))                      # misaligned sel_thr
+    assert raw.lrqk_decode_step(None, C.byref(s), 0, C.byref(lay_bad), A, A, A,
+                                lib.LRQK_FETCH_DIRECT | lib.LRQK_SELECT_FRESH, None, None, None) == -1
     assert raw.lrqk_plan_destroy(None) == -1
     assert raw.lrqk_plan_create(C.byref(b), C.byref(C.c_void_p())) == -2
 
