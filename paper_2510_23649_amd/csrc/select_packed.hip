@@ -173,7 +173,7 @@ struct PackedArgs {
   int32_t* n_miss;
 };
 
-template <int GPT, int SPT>
+template <int GPT, int SPT, int SLOTS>
 __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
   extern __shared__ __align__(16) unsigned char lds_raw[];
   __shared__ uint32_t wave_tot[4 * 2 * kWaves];  // four areas of 32 words, used in rotation
@@ -262,45 +262,51 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
   auto value_of = [&](uint32_t kk, int g, int bpos) {
     return ((uint64_t)kk << 32) | (uint32_t) ~(uint32_t)((t * GPT + g) * 64 + bpos);
   };
-  uint32_t key[GPT][kCandPerGroup];
-  unsigned long long bpos6[GPT];  // bit positions of the packed candidates, 6 bits each
+  // The first SLOTS candidates of a group stay in registers; the others (packed entries beyond
+  // SLOTS, and candidates beyond the 8 packed ones, whose scores are computed again from A_K)
+  // are parked in LDS, in position order, in a run the thread reserves.
+  uint32_t key[GPT][SLOTS];
+  unsigned long long bpos6[GPT];  // bit positions of the candidates in registers, 6 bits each
   auto bpos_of = [&](int g, int i) { return (int)((bpos6[g] >> (6 * i)) & 63ull); };
   int cnt[GPT];
   int extra = 0;
 #pragma unroll
   for (int g = 0; g < GPT; ++g) {
     cnt[g] = __popcll(mask[g]);
-    extra += max(cnt[g] - kCandPerGroup, 0);
-    const float v[kCandPerGroup] = {sc[g][0].x, sc[g][0].y, sc[g][0].z, sc[g][0].w,
-                                    sc[g][1].x, sc[g][1].y, sc[g][1].z, sc[g][1].w};
-    unsigned long long mb = mask[g];
-    bpos6[g] = 0ull;
-#pragma unroll
-    for (int i = 0; i < kCandPerGroup; ++i) {
-      key[g][i] = 0u;
-      if (i < cnt[g]) {
-        key[g][i] = order_key(v[i]);
-        bpos6[g] |= (unsigned long long)__builtin_ctzll(mb) << (6 * i);
-        mb &= mb - 1ull;
-        atomicAdd(&hist0[bin_of(key[g][i])], 1u);
-      }
-    }
+    extra += max(cnt[g] - SLOTS, 0);
   }
-  // a group with more candidates than the proxy pass packed: the others' scores again, from A_K
   int ov_base = 0;
   bool ov_ok = true;
   if (extra > 0) {
     ov_base = (int)atomicAdd(&sh_ov, (uint32_t)extra);
     ov_ok = ov_base + extra <= kOvCap;
-    if (ov_ok) {
-      int idx = ov_base;
+  }
+  {
+    int idx = ov_base;
 #pragma unroll
-      for (int g = 0; g < GPT; ++g) {
-        if (cnt[g] <= kCandPerGroup) continue;
-        unsigned long long mb = mask[g];
+    for (int g = 0; g < GPT; ++g) {
+      const float v[kCandPerGroup] = {sc[g][0].x, sc[g][0].y, sc[g][0].z, sc[g][0].w,
+                                      sc[g][1].x, sc[g][1].y, sc[g][1].z, sc[g][1].w};
+      unsigned long long mb = mask[g];
+      bpos6[g] = 0ull;
 #pragma unroll
-        for (int i = 0; i < kCandPerGroup; ++i) mb &= mb - 1ull;  // the packed ones
-        while (mb) {
+      for (int i = 0; i < kCandPerGroup; ++i) {
+        if (i < SLOTS) key[g][i] = 0u;
+        if (i < cnt[g]) {
+          const uint32_t kk = order_key(v[i]);
+          if (i < SLOTS) {
+            key[g][i] = kk;
+            bpos6[g] |= (unsigned long long)__builtin_ctzll(mb) << (6 * (i < SLOTS ? i : 0));
+            atomicAdd(&hist0[bin_of(kk)], 1u);
+          } else if (ov_ok) {
+            ov_key[idx++] = kk;
+            atomicAdd(&hist0[bin_of(kk)], 1u);
+          }
+          mb &= mb - 1ull;
+        }
+      }
+      if (cnt[g] > kCandPerGroup && ov_ok) {
+        while (mb) {  // more candidates than the proxy pass packed
           const int bp = __builtin_ctzll(mb);
           mb &= mb - 1ull;
           const uint32_t kk = order_key(proxy_score_of_row(Arow, qh, r, (t * GPT + g) * 64 + bp));
@@ -310,16 +316,16 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
       }
     }
   }
-  // Calls f(key, group, bit) for each of the thread's candidates beyond the packed ones.
+  // Calls f(key, group, bit) for each of the thread's candidates beyond those in registers.
   auto for_each_extra = [&](auto&& f) {
     if (extra == 0) return;
     int idx = ov_base;
 #pragma unroll
     for (int g = 0; g < GPT; ++g) {
-      if (cnt[g] <= kCandPerGroup) continue;
+      if (cnt[g] <= SLOTS) continue;
       unsigned long long mb = mask[g];
 #pragma unroll
-      for (int i = 0; i < kCandPerGroup; ++i) mb &= mb - 1ull;
+      for (int i = 0; i < SLOTS; ++i) mb &= mb - 1ull;
       while (mb) {
         const int bp = __builtin_ctzll(mb);
         mb &= mb - 1ull;
@@ -327,12 +333,12 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
       }
     }
   };
-  // ... and for all of them, packed ones first (any order will do for the callers)
+  // ... and for all of them, those in registers first (any order will do for the callers)
   auto for_each_candidate = [&](auto&& f) {
 #pragma unroll
     for (int g = 0; g < GPT; ++g)
 #pragma unroll
-      for (int i = 0; i < kCandPerGroup; ++i)
+      for (int i = 0; i < SLOTS; ++i)
         if (i < cnt[g]) f(key[g][i], g, bpos_of(g, i));
     for_each_extra(f);
   };
@@ -426,7 +432,7 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
 #pragma unroll
       for (int g = 0; g < GPT; ++g) {
 #pragma unroll
-        for (int i = 0; i < kCandPerGroup; ++i) neq += (i < cnt[g] && key[g][i] == tau) ? 1u : 0u;
+        for (int i = 0; i < SLOTS; ++i) neq += (i < cnt[g] && key[g][i] == tau) ? 1u : 0u;
       }
       for_each_extra([&](uint32_t kk, int, int) { neq += kk == tau ? 1u : 0u; });
       uint32_t tot;
@@ -442,9 +448,9 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
             mb &= mb - 1ull;
             uint32_t kk = 0u;
 #pragma unroll
-            for (int ii = 0; ii < kCandPerGroup; ++ii)
+            for (int ii = 0; ii < SLOTS; ++ii)
               if (ii == i) kk = key[g][ii];
-            if (i >= kCandPerGroup) kk = ov_key[idx++];
+            if (i >= SLOTS) kk = ov_key[idx++];
             ++i;
             if (kk == tau && ++eq_rank == need_eq) sh_cut = value_of(kk, g, bp);
           }
@@ -457,7 +463,7 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
 #pragma unroll
     for (int g = 0; g < GPT; ++g) {
 #pragma unroll
-      for (int i = 0; i < kCandPerGroup; ++i)
+      for (int i = 0; i < SLOTS; ++i)
         if (i < cnt[g] && value_of(key[g][i], g, bpos_of(g, i)) >= cut) selm[g] |= 1u << i;
     }
     for_each_extra([&](uint32_t kk, int g, int bp) {
@@ -488,7 +494,7 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
     uint32_t bin_next;
     exact_select_from_scores<false>(sw, n, k, (l & 3) == 0, rank_next, hist, bitmap_l, nullptr,
                                     wave_tot, res, &bin_next);
-    // the selection as bits of the thread's groups; none of it is a "packed candidate"
+    // the selection as bits of the thread's groups; none of it is a candidate in registers
 #pragma unroll
     for (int g = 0; g < GPT; ++g) {
       const int gi = t * GPT + g;
@@ -514,13 +520,13 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
   }
 
   // slot_of of the thread's selected positions (selected packed candidates: in registers)
-  int32_t slot[GPT][kCandPerGroup];
+  int32_t slot[GPT][SLOTS];
   uint32_t nsel = 0, nmiss = 0;
 #pragma unroll
   for (int g = 0; g < GPT; ++g) {
     const int base = (t * GPT + g) * 64;
 #pragma unroll
-    for (int i = 0; i < kCandPerGroup; ++i) {
+    for (int i = 0; i < SLOTS; ++i) {
       slot[g][i] = 0;
       if (selm[g] & (1u << i)) slot[g][i] = so[base + bpos_of(g, i)];
     }
@@ -529,7 +535,7 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
   for (int g = 0; g < GPT; ++g) {
     nsel += (uint32_t)__popc(selm[g]) + (uint32_t)__popcll(take_x[g]);
 #pragma unroll
-    for (int i = 0; i < kCandPerGroup; ++i)
+    for (int i = 0; i < SLOTS; ++i)
       if (selm[g] & (1u << i)) {
         if (slot[g][i] >= C) slot[g][i] = -1;  // corrupt map entry: treat as absent
         nmiss += slot[g][i] < 0 ? 1u : 0u;
@@ -570,10 +576,10 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
 #pragma unroll
     for (int g = 0; g < GPT; ++g) {
       const int base = (t * GPT + g) * 64;
-      // position order inside the group: packed candidates come first, in position order;
-      // the ones beyond them lie at higher positions
+      // position order inside the group: the candidates in registers come first, in position
+      // order; the ones beyond them lie at higher positions
 #pragma unroll
-      for (int i = 0; i < kCandPerGroup; ++i)
+      for (int i = 0; i < SLOTS; ++i)
         if (selm[g] & (1u << i)) emit(base + bpos_of(g, i), slot[g][i]);
       unsigned long long tb = take_x[g];
       while (tb) {
@@ -722,13 +728,23 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
   if (t == 0) a.n_miss[bh] = sh_bad ? -1 : nm;
 }
 
+// Candidates of a group kept in registers: all 8 packed ones where a thread owns one or two
+// groups, 4 where it owns three or four (the registers would not hold more; at one or two
+// groups per thread 4, 6 or 8 measure the same).
+template <int GPT>
+constexpr int slots_in_registers() {
+  return GPT <= 2 ? kCandPerGroup : 4;
+}
+
 template <int GPT, int SPT>
 hipError_t launch_inst(const PackedArgs& a, int BHq, size_t lds, hipStream_t st) {
   static std::atomic<uint64_t> raised{0};  // devices on which this instantiation's ceiling is up
   const hipError_t e =
-      raise_dynamic_lds_once(select_packed_kernel<GPT, SPT>, kPackedLdsLimit, raised);
+      raise_dynamic_lds_once(select_packed_kernel<GPT, SPT, slots_in_registers<GPT>()>,
+                             kPackedLdsLimit, raised);
   if (e != hipSuccess) return e;
-  LRQK_LAUNCH((select_packed_kernel<GPT, SPT>), dim3(BHq), dim3(kT), lds, st, a);
+  LRQK_LAUNCH((select_packed_kernel<GPT, SPT, slots_in_registers<GPT>()>), dim3(BHq), dim3(kT), lds,
+              st, a);
   return hipGetLastError();
 }
 template <int GPT>
@@ -787,6 +803,7 @@ hipError_t launch_select_packed(const lrqk_shape& s, const unsigned long long* b
   const int BHq = s.B * s.Hq;
   if (groups <= kT) return launch_gpt<1>(a, BHq, lds, st);
   if (groups <= 2 * kT) return launch_gpt<2>(a, BHq, lds, st);
+  if (groups <= 3 * kT) return launch_gpt<3>(a, BHq, lds, st);
   return launch_gpt<4>(a, BHq, lds, st);
 }
 
