@@ -393,6 +393,23 @@ def test_group_fetch_alone_fills_the_same_caches_as_the_oracle():
     plan.close()
 
 
+@pytest.mark.parametrize("shape", [
+    dict(B=1, Hq=1, Hkv=1, l=300, r=16, k=1, w=0, C=1),             # one token, one slot
+    dict(B=1, Hq=2, Hkv=2, l=777, r=64, k=700, w=77, C=700),        # k + w = l: dense selection
+    dict(B=3, Hq=8, Hkv=1, l=5000, r=32, k=64, w=1, C=64),          # G = 8, cache of exactly k slots
+    dict(B=1, Hq=4, Hkv=2, l=9000, r=16, k=1500, w=1000, C=8192),   # largest cache, widest window
+    dict(B=2, Hq=7, Hkv=1, l=4097, r=32, k=333, w=5, C=400),        # G = 7, ragged everything
+    dict(B=1, Hq=2, Hkv=1, l=150000, r=16, k=4096, w=64, C=4096),   # largest k, three groups per thread
+    dict(B=1, Hq=2, Hkv=2, l=70000, r=8, k=500, w=16, C=1000),      # rank outside the filtered pass
+    dict(B=1, Hq=6, Hkv=2, l=3000, r=32, k=100, w=10, C=150),       # G = 3: generic proxy kernel
+])
+def test_decode_step_shape_sweep(shape):
+    say(f"decode_step shape sweep {shape}")
+    n_heavy = max(1, min(64, shape["k"] // 4))
+    cfg = small_cfg(n_heavy=n_heavy, **shape)
+    run_steps_against_oracle(cfg, 4, "direct", check_unfused=False)
+
+
 @pytest.mark.parametrize("carry", ["off", "unknown_first"])
 def test_decode_step_threshold_sources(carry):
     say(f"decode_step small, candidate thresholds: {carry}")
