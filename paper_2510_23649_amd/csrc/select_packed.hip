@@ -9,15 +9,17 @@
 // threads is a count in position order.
 //   * one round of coalesced loads brings the thread's bitmap words and packed scores in
 //     (with what the resolution will need from the cache state: last_used and token_of go
-//     to LDS).  A group with more than 8 candidates recomputes the others from A_K and q_hat
-//     with the proxy pass's fma chain and parks their keys in LDS;
+//     to LDS).  The first 8 (or 4) candidates of a group stay in registers, further ones are
+//     parked in LDS; a group with more than the 8 packed candidates computes the others
+//     again from A_K and q_hat with the proxy pass's fma chain;
 //   * ONE histogram over (key - threshold key) >> s, 2048 bins (the candidates are the tail
 //     of the score distribution above the threshold, so they spread over the bins instead
 //     of piling into the two or three bins that fixed key bits would give), is scanned from
-//     the top: bins above the one that holds the k-th largest are selected outright, and
-//     the few candidates of that bin are ranked on (key, position) by the threads that own
-//     them.  A bin with many candidates (ties) goes through further 11-bit histogram levels
-//     and an ordered cut instead;
+//     the top: it gives the bin that holds the k-th largest.  The few candidates of that bin
+//     are ranked on (key, position) -- every wavefront does it for itself -- and the one
+//     with the right rank is the cut: the selection is every candidate at or above it.  A
+//     bin with many candidates (ties) goes through further 11-bit histogram levels and an
+//     ordered cut instead;
 //   * each thread then looks up slot_of for its own selected positions, and one prefix count
 //     over (selected, missing) gives it its place in the outputs;
 //   * the same histogram yields the key at rank 1.5 k, which (divided by |q_hat|) is handed
