@@ -172,6 +172,10 @@ static inline void prof_arm(lrqk_plan* p, int slot, int count) {
   t.recorded = p->prof_used + p->prof_n;
   t.next = slot;
 }
+// Leaves no events armed for later launches of this thread, whichever way a function returns.
+struct LaunchTimerReset {
+  ~LaunchTimerReset() { launch_timer() = LaunchTimer{}; }
+};
 static inline void prof_step_done(lrqk_plan* p) {
   launch_timer() = LaunchTimer{};
   if (p->prof_ev && p->prof_n < p->prof_cap) ++p->prof_n;
@@ -577,6 +581,7 @@ int lrqk_decode_step(lrqk_plan* plan, const lrqk_shape* shape, int32_t step,
   const lrqk_shape& s = *shape;
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int BHq = s.B * s.Hq;
+  LaunchTimerReset timer_reset;
 
   int32_t* sel_idx = (dbg && dbg->sel_idx) ? dbg->sel_idx : plan->sel_idx;
   int32_t* sel_slot = (dbg && dbg->sel_slot) ? dbg->sel_slot : plan->sel_slot;
@@ -716,7 +721,12 @@ int lrqk_plan_time_proxy_pass(lrqk_plan* plan, const lrqk_shape* shape,
   rc = check_plan_fits(plan, shape);
   if (rc != LRQK_OK) return rc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const bool filtered = select_resolve_fits(*shape, true) && proxy_filter_supported(*shape);
+  LaunchTimerReset timer_reset;
+  // the same choices as lrqk_decode_step makes for this shape
+  const bool packed = select_packed_fits(*shape) && proxy_filter_supported(*shape);
+  const bool filtered =
+      (packed || select_resolve_fits(*shape, true)) && proxy_filter_supported(*shape);
+  if (!packed) sel_thr = nullptr;  // thresholds are carried only into the packed selection
   auto pass = [&](const float* A_K) -> hipError_t {
     if (filtered)
       return launch_proxy_scores_filter(*shape, A_K, q_hat, plan->scores,
