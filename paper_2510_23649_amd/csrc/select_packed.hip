@@ -762,6 +762,10 @@ bool select_packed_fits(const lrqk_shape& s) {
   const int n = s.l - s.w;
   if (((n + 63) >> 6) > 4 * kT) return false;  // at most 4 groups of 64 positions per thread
   if (s.C > kMaxSpt * kT) return false;
+  // Dense selections (k a sizeable fraction of the context) put more than 8 candidates into
+  // most groups: the 1.5 k candidates the threshold aims at, less the 8 per group that the proxy
+  // pass packs, must leave room in the area for the others
+  if ((long)s.k + s.k / 2 - (long)kCandPerGroup * ((n + 63) >> 6) > kOvCap / 2) return false;
   return packed_arena(s.k, n, s.C).total <= kPackedLdsLimit;
 }
 

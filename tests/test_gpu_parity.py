@@ -402,6 +402,8 @@ def test_group_fetch_alone_fills_the_same_caches_as_the_oracle():
     dict(B=1, Hq=2, Hkv=1, l=150000, r=16, k=4096, w=64, C=4096),   # largest k, three groups per thread
     dict(B=1, Hq=2, Hkv=2, l=70000, r=8, k=500, w=16, C=1000),      # rank outside the filtered pass
     dict(B=1, Hq=6, Hkv=2, l=3000, r=32, k=100, w=10, C=150),       # G = 3: generic proxy kernel
+    dict(B=1, Hq=2, Hkv=1, l=16384, r=32, k=4096, w=64, C=4096),    # a quarter of the context selected
+    dict(B=1, Hq=2, Hkv=1, l=12000, r=32, k=1400, w=64, C=2048),    # about 10 candidates per group
 ])
 def test_decode_step_shape_sweep(shape):
     say(f"decode_step shape sweep {shape}")
