@@ -490,3 +490,44 @@ def test_group_share_knob_makes_heads_of_a_group_miss_the_same_rows():
         return uni / tot
     assert union_over_total(0.0) > 0.9
     assert union_over_total(1.0) < 0.75
+
+
+def test_group_fetch_hand_worked_example():
+    lines = [ln.strip() for ln in open(os.path.join(GOLDEN, "group_fetch_worked_example.txt"))
+             if ln.strip() and not ln.startswith("#")]
+    B, Hkv, G, l, C, d, k = 1, 2, 3, 12, 5, 128, 4
+    Hq = Hkv * G
+    miss_tok = np.full((B, Hq, k), -1, np.int32)
+    miss_slot = np.full((B, Hq, k), -1, np.int32)
+    n_miss = np.zeros((B, Hq), np.int32)
+    want_rows, want_cache = None, None
+    for ln in lines:
+        f = [x.split() for x in ln.split("|")]
+        if f[0][0] == "link_rows":
+            want_rows = np.array(f[1], np.int64)
+        elif f[0][0] == "cache":
+            want_cache = [tuple(int(v) for v in x) for x in f[1:]]
+        else:
+            h = int(f[0][0])
+            n_miss[0, h] = len(f[1])
+            miss_tok[0, h, :len(f[1])] = [int(v) for v in f[1]]
+            miss_slot[0, h, :len(f[2])] = [int(v) for v in f[2]]
+    # rows that can be told apart: row p of KV head kv holds the value 100 kv + p in every element
+    K = np.empty((B, Hkv, l, d), np.float32)
+    for kv in range(Hkv):
+        for p in range(l):
+            K[0, kv, p] = 100 * kv + p
+    V = -K
+    cK = np.full((B, Hq, C, d), -7.0, np.float32)
+    cV = np.full((B, Hq, C, d), -7.0, np.float32)
+    rows, union = orc.group_fetch(K, V, miss_tok, miss_slot, n_miss, cK, cV)
+    assert np.array_equal(rows[0], want_rows)
+    assert [list(u) for u in union] == [[2, 5, 9, 11], [0, 1, 7]]
+    touched = set()
+    for h, slot, pos in want_cache:
+        assert np.all(cK[0, h, slot] == 100 * (h // G) + pos) and np.all(cV[0, h, slot] == -(100 * (h // G) + pos))
+        touched.add((h, slot))
+    for h in range(Hq):
+        for slot in range(C):
+            if (h, slot) not in touched:
+                assert np.all(cK[0, h, slot] == -7.0) and np.all(cV[0, h, slot] == -7.0)
