@@ -256,7 +256,7 @@ def test_sparse_attend_closed_forms():
 # ------------------------------------------------------------------------------- a1..a5
 
 def run_steps_against_oracle(cfg, n_steps, mode, identity=False, data=None, check_unfused=True,
-                             carry="fresh_first"):
+                             carry="fresh_first", step_number=None, quiet=False):
     """Drive lrqk_decode_step for n_steps and compare every step with the oracle.
     carry: how the selection's candidate thresholds are obtained -- "off": estimated from a sample
     in every step (no lrqk_layer.sel_thr); "fresh_first": from a sample in the first step
@@ -273,12 +273,13 @@ def run_steps_against_oracle(cfg, n_steps, mode, identity=False, data=None, chec
              "group": L.LRQK_FETCH_GROUP}[mode]
     miss_rates = []
     link_rows_seen = []
-    for step in range(1, n_steps + 1):
+    for index in range(1, n_steps + 1):
+        step = step_number(index) if step_number else index   # the caller's step counter
         q, q_hat = qs.next()
         qd, qhd = q.to(DEV), q_hat.to(DEV)
-        if check_unfused and step == 1:
+        if check_unfused and index == 1:
             unfused = run_unfused(cfg, dl, qd, qhd, step)      # on copies of the state
-        flags = L.LRQK_SELECT_FRESH if (carry == "fresh_first" and step == 1) else 0
+        flags = L.LRQK_SELECT_FRESH if (carry == "fresh_first" and index == 1) else 0
         total = L.lrqk_decode_step(plan, dl.shape, step, lay, qhd, qd, out, fmode | flags,
                                    sb.debug())
         got = sb.to_np()
@@ -291,7 +292,8 @@ def run_steps_against_oracle(cfg, n_steps, mode, identity=False, data=None, chec
         compare_resolution(got, ref, f"step {step}")
         compare_state(dl, f"step {step}")
         err = np.abs(out.cpu().numpy().astype(np.float64) - ref["out"]).max()
-        say(f"   step {step}: miss rate {ref['miss_rate']:.3f}  max abs err {err:.3e}")
+        if not quiet:
+            say(f"   step {step}: miss rate {ref['miss_rate']:.3f}  max abs err {err:.3e}")
         assert err <= TOL[cfg.kv_dtype], f"step {step}: attention error {err}"
         if mode == "staged":
             assert total == int(ref["n_miss"].sum())
@@ -301,7 +303,7 @@ def run_steps_against_oracle(cfg, n_steps, mode, identity=False, data=None, chec
                                            ref["n_miss"], scratchK, scratchV)
             assert np.array_equal(got["link_rows"], want_rows), f"step {step}: rows over the link"
             link_rows_seen.append((int(want_rows.sum()), int(ref["n_miss"].sum())))
-        if check_unfused and step == 1:
+        if check_unfused and index == 1:
             for name in ("sel_idx", "sel_slot", "hit", "n_miss"):
                 assert np.array_equal(unfused[name], got[name]), f"fused/unfused {name} differ"
             assert np.abs(unfused["out"] - out.cpu().numpy()).max() <= 1e-5
@@ -410,6 +412,66 @@ def test_decode_step_shape_sweep(shape):
     n_heavy = max(1, min(64, shape["k"] // 4))
     cfg = small_cfg(n_heavy=n_heavy, **shape)
     run_steps_against_oracle(cfg, 4, "direct", check_unfused=False)
+
+
+def test_decode_step_step_counter_far_ahead_of_the_slots_ages():
+    say("decode_step with step numbers that jump by thousands (ages beyond the victim histogram)")
+    # steps 1, 2, 3, then 5000, 5001, 9000, 9001: the slots' ages exceed the 2048 classes of the
+    # age histogram, which then cannot order them; the all-slots ordering must give the same
+    # least-recently-selected victims as the oracle
+    numbers = {1: 1, 2: 2, 3: 3, 4: 5000, 5: 5001, 6: 9000, 7: 9001}
+    rates = run_steps_against_oracle(small_cfg(), 7, "direct", check_unfused=False,
+                                     step_number=lambda i: numbers[i])
+    assert all(r > 0 for r in rates)
+
+
+@pytest.mark.parametrize("n_classes", [3, 50])
+def test_decode_step_victims_spread_over_age_classes(n_classes):
+    say(f"decode_step: one step with about 300 misses, victims drawn from {n_classes} age classes")
+    # the cache starts full of tokens the step will not select, their slots last used at
+    # n_classes different earlier steps (8 .. 130 slots a class): the victims have to come out in
+    # (last_used, slot) order across all of them
+    cfg = small_cfg(B=1, Hq=4, Hkv=2, l=6000, k=300, w=16, C=400, n_heavy=64)
+    data = make_layer(cfg)
+    dl = DeviceLayer(cfg, data)
+    G = cfg.G
+    slots = np.arange(cfg.C, dtype=np.int32)
+    toks = 5000 + slots                                    # positions the proxy scores rank low
+    data.A_K[:, :, 5000:5000 + cfg.C, :] *= 0.01
+    dl.A_K.copy_(data.A_K)
+    dl.np["A_K"] = as_numpy(data.A_K)
+    last = (1 + (slots * 7) % n_classes).astype(np.int32)
+    for b in range(cfg.B):
+        for h in range(cfg.Hq):
+            dl.ost.token_of[b, h] = toks
+            dl.ost.last_used[b, h] = last
+            dl.ost.slot_of[b, h, toks] = slots
+            dl.ocK[b, h] = dl.np["K"][b, h // G, toks]
+            dl.ocV[b, h] = dl.np["V"][b, h // G, toks]
+    dl.token_of.copy_(torch.from_numpy(dl.ost.token_of))
+    dl.last_used.copy_(torch.from_numpy(dl.ost.last_used))
+    dl.slot_of.copy_(torch.from_numpy(dl.ost.slot_of))
+    dl.cacheK.copy_(torch.from_numpy(dl.ocK.view(np.int16)).view(torch.bfloat16))
+    dl.cacheV.copy_(torch.from_numpy(dl.ocV.view(np.int16)).view(torch.bfloat16))
+    plan = L.Plan(dl.shape)
+    qs = QueryStream(data)
+    sb = StepBuffers(cfg)
+    out = torch.empty((cfg.B, cfg.Hq, cfg.d), device=DEV)
+    for step in (60, 61):
+        q, q_hat = qs.next()
+        L.lrqk_decode_step(plan, dl.shape, step, dl.struct(), q_hat.to(DEV), q.to(DEV), out,
+                           L.LRQK_FETCH_DIRECT | (L.LRQK_SELECT_FRESH if step == 60 else 0),
+                           sb.debug())
+        got = sb.to_np()
+        ref = orc.decode_step(dl.np["A_K"], as_numpy(q_hat), as_numpy(q), dl.np["K"], dl.np["V"],
+                              dl.ost, dl.ocK, dl.ocV, step, cfg.k, cfg.w, cfg.scale)
+        assert np.array_equal(got["sel_idx"], ref["sel_idx"])
+        compare_resolution(got, ref, f"step {step}")
+        compare_state(dl, f"step {step}")
+        assert np.abs(out.cpu().numpy() - ref["out"]).max() <= TOL[cfg.kv_dtype]
+        if step == 60:
+            assert ref["n_miss"].min() > 250          # nearly everything misses
+    plan.close()
 
 
 @pytest.mark.parametrize("carry", ["off", "unknown_first"])
