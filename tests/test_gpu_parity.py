@@ -425,6 +425,66 @@ def test_decode_step_step_counter_far_ahead_of_the_slots_ages():
     assert all(r > 0 for r in rates)
 
 
+def _crafted_steps(cfg, data, queries, mutate=None):
+    """lrqk_decode_step (direct fetch, thresholds sampled in the first step, carried afterwards)
+    against the oracle for the given (q, q_hat) pairs; mutate(i, dl) may change the layer before
+    step i."""
+    dl = DeviceLayer(cfg, data)
+    plan = L.Plan(dl.shape)
+    sb = StepBuffers(cfg)
+    out = torch.empty((cfg.B, cfg.Hq, cfg.d), device=DEV)
+    for i, (q, q_hat) in enumerate(queries, start=1):
+        if mutate:
+            mutate(i, dl)
+        L.lrqk_decode_step(plan, dl.shape, i, dl.struct(), q_hat.to(DEV), q.to(DEV), out,
+                           L.LRQK_FETCH_DIRECT | (L.LRQK_SELECT_FRESH if i == 1 else 0), sb.debug())
+        got = sb.to_np()
+        ref = orc.decode_step(dl.np["A_K"], as_numpy(q_hat), as_numpy(q), dl.np["K"], dl.np["V"],
+                              dl.ost, dl.ocK, dl.ocV, i, cfg.k, cfg.w, cfg.scale)
+        assert np.array_equal(got["sel_idx"], ref["sel_idx"]), f"step {i}: selection differs"
+        compare_resolution(got, ref, f"step {i}")
+        compare_state(dl, f"step {i}")
+        assert np.abs(out.cpu().numpy() - ref["out"]).max() <= TOL[cfg.kv_dtype]
+    plan.close()
+
+
+def test_decode_step_scores_with_massive_ties():
+    say("decode_step: only 97 distinct rows in A_K, every score repeated hundreds of times")
+    cfg = small_cfg(B=1, Hq=4, Hkv=2, l=70000, r=32, k=1024, w=64, C=2048, n_heavy=64)
+    data = make_layer(cfg)
+    n = cfg.l
+    data.A_K[:] = data.A_K[:, :, torch.arange(n) % 97, :]      # the k-th largest sits inside a tie
+    qs = QueryStream(data)
+    _crafted_steps(cfg, data, [qs.next() for _ in range(3)])
+
+
+def test_decode_step_all_scores_negative():
+    say("decode_step: every proxy score negative (threshold keys below zero)")
+    cfg = small_cfg(B=1, Hq=4, Hkv=2, l=70000, r=32, k=1024, w=64, C=2048, n_heavy=64)
+    data = make_layer(cfg)
+    data.A_K.abs_()
+    qs = QueryStream(data)
+    queries = [(q, -q_hat.abs()) for q, q_hat in (qs.next() for _ in range(3))]
+    _crafted_steps(cfg, data, queries)
+
+
+def test_decode_step_selection_far_above_a_stale_threshold():
+    say("decode_step: the k largest scores jump a hundredfold above the carried threshold")
+    cfg = small_cfg(B=1, Hq=4, Hkv=2, l=70000, r=32, k=1024, w=64, C=2048, n_heavy=64)
+    data = make_layer(cfg)
+    qs = QueryStream(data)
+    rng = np.random.default_rng(3)
+    boosted = torch.from_numpy(np.sort(rng.choice(cfg.l - cfg.w, 3500, replace=False)))
+
+    def mutate(i, dl):
+        if i == 2:       # 3500 rows times 100, all others times 0.01: about 1750 positive giants,
+            scale = torch.full((cfg.l, 1), 0.01)           # more than k, few enough to stay candidates
+            scale[boosted] = 100.0
+            dl.A_K.mul_(scale.to(DEV))
+            dl.np["A_K"] = dl.A_K.cpu().numpy()
+    _crafted_steps(cfg, data, [qs.next() for _ in range(3)], mutate)
+
+
 @pytest.mark.parametrize("n_classes", [3, 50])
 def test_decode_step_victims_spread_over_age_classes(n_classes):
     say(f"decode_step: one step with about 300 misses, victims drawn from {n_classes} age classes")
