@@ -12,8 +12,9 @@ default workload is the 128K-context LLaMA-3-8B-shaped decode (32 layers, 32 que
 head, batch 1); consecutive steps walk through the 32 layers, so the data touched
 between two visits of a layer (> 5 GB) is far larger than any on-chip cache.  All
 inputs are seeded synthetic tensors already resident (A_K, caches in HBM; K/V store in
-pinned host memory) when the timed region starts.  The caches are primed with two
-untimed passes over all layers ("seeded from the previous steps' selections"); a layer's
+pinned host memory) when the timed region starts.  The caches are primed with eight
+untimed passes over all layers ("seeded from the previous steps' selections": after them the
+miss rate no longer drifts); a layer's
 first step estimates its selection thresholds from a sample, later steps carry them.
 
 Prints ONE JSON line: metric/value = layer-steps per second of the headline workload, plus
@@ -92,6 +93,7 @@ class Workload:
         self.out = torch.empty((cfg.B, cfg.Hq, cfg.d), device="cuda")
         self.n_miss = torch.zeros((cfg.B, cfg.Hq), dtype=torch.int32, device="cuda")
         self.step_no = [0] * self.nl
+        self._next_layer = 0
         self.oracle_queries = []
 
     def step(self, li, q, q_hat, debug=None, mode=None, shape=None):
@@ -104,7 +106,7 @@ class Workload:
                                   self.layers[li].struct, q_hat, q, self.out,
                                   (self.mode if mode is None else mode) | flags, debug)
 
-    def prime(self, passes=2):
+    def prime(self, passes=8):
         from gen import as_numpy
         for _ in range(passes):
             for li in range(self.nl):
@@ -115,7 +117,12 @@ class Workload:
         self.torch.cuda.synchronize()
 
     def queries(self, n):
-        qs = [self.streams[i % self.nl].next() for i in range(n)]
+        """The next n queries of the rotation over the layers, as (layer, q, q_hat)."""
+        qs = []
+        for _ in range(n):
+            li = self._next_layer
+            self._next_layer = (li + 1) % self.nl
+            qs.append((li, *self.streams[li].next()))
         self.torch.cuda.synchronize()
         return qs
 
@@ -123,12 +130,12 @@ class Workload:
         """Wall-clock time of len(queries) - warmup consecutive steps, layers in rotation."""
         torch = self.torch
         for i in range(warmup):
-            self.step(i % self.nl, *queries[i], mode=mode)
+            self.step(*queries[i], mode=mode)
         torch.cuda.synchronize()
         tot_miss = 0
         t0 = time.perf_counter()
         for i in range(warmup, len(queries)):
-            tot_miss += max(self.step(i % self.nl, *queries[i], mode=mode), 0)
+            tot_miss += max(self.step(*queries[i], mode=mode), 0)
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / (len(queries) - warmup), tot_miss
 
@@ -142,12 +149,12 @@ class Workload:
         self.plan.profile(len(queries))
         miss = counted = 0
         for r0 in range(0, len(queries), self.nl):
-            chunk = queries[r0:r0 + self.nl]
+            chunk = queries[r0:r0 + self.nl]          # at most one visit of every layer
             if repeat_each:
-                for i, (q, q_hat) in enumerate(chunk):
-                    self._untimed_step(i % self.nl, q, q_hat)
-            for i, (q, q_hat) in enumerate(chunk):
-                self.step(i % self.nl, q, q_hat, debug=dict(n_miss=self.n_miss))
+                for li, q, q_hat in chunk:
+                    self._untimed_step(li, q, q_hat)
+            for li, q, q_hat in chunk:
+                self.step(li, q, q_hat, debug=dict(n_miss=self.n_miss))
                 if repeat_each or counted < 8:
                     miss += int(self.n_miss.clamp(min=0).sum().item())
                     counted += 1
@@ -197,8 +204,9 @@ def measure(wl, steps, warmup, with_all_hit):
         miss_rate = tot_miss / (steps * cfg.B * cfg.Hq * cfg.k)
     # the proxy-score pass exactly as the step launches it, back to back over the layers' A_K,
     # events attached to every kernel (a Python loop of single launches is interpreter-bound)
-    k1_us = wl.plan.time_proxy_pass(wl.shape, [lb.A_K for lb in wl.layers], qs[0][1],
-                                    max(steps, 64), sel_thr=wl.layers[0].sel_thr)
+    li0, _, q_hat0 = qs[0]
+    k1_us = wl.plan.time_proxy_pass(wl.shape, [lb.A_K for lb in wl.layers], q_hat0,
+                                    max(steps, 64), sel_thr=wl.layers[li0].sel_thr)
     res = {
         "ms_per_step": 1e3 * sec, "layer_steps_per_s": 1.0 / sec, "steps": steps,
         "layers_rotated": wl.nl, "miss_rate": miss_rate,
@@ -308,6 +316,7 @@ def main():
             B_K.append(Bm.clone().contiguous())
             q, q_hat = streams[li].next()       # leaves this layer's previous selection
             wl.step(li, q, q_hat, debug=dict(sel_idx=sel_idx[li], sel_slot=sel_slot[li]))
+        wl._next_layer = 0
         ws_u = torch.empty(L.lrqk_workspace_bytes(shape.with_l(shape.rows), L.LRQK_WS_UPDATE),
                            dtype=torch.uint8, device=dev)
         q_hat_u = torch.zeros((cfg.B, cfg.Hq, cfg.r), device=dev)
