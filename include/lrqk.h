@@ -48,7 +48,7 @@
 extern "C" {
 #endif
 
-#define LRQK_VERSION 100 /* major*10000 + minor*100 + patch */
+#define LRQK_VERSION 200 /* major*10000 + minor*100 + patch */
 
 typedef enum lrqk_status {
   LRQK_OK = 0,

@@ -35,7 +35,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_version_and_status_strings(lib):
-    assert lib.lrqk_version() == 100
+    assert lib.lrqk_version() == 200
     assert lib.lrqk_status_string(0) == "ok"
     for code in (-1, -2, -3, -4, -5):
         assert lib.lrqk_status_string(code) not in ("ok", "unknown status")
