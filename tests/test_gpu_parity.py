@@ -406,12 +406,16 @@ def test_group_fetch_alone_fills_the_same_caches_as_the_oracle():
     dict(B=1, Hq=6, Hkv=2, l=3000, r=32, k=100, w=10, C=150),       # G = 3: generic proxy kernel
     dict(B=1, Hq=2, Hkv=1, l=16384, r=32, k=4096, w=64, C=4096),    # a quarter of the context selected
     dict(B=1, Hq=2, Hkv=1, l=12000, r=32, k=1400, w=64, C=2048),    # about 10 candidates per group
+    dict(B=2, Hq=4, Hkv=4, l=70, r=16, k=20, w=3, C=25),            # a context of two 64-position groups
+    dict(B=1, Hq=8, Hkv=2, l=64, r=32, k=64, w=0, C=64),            # one group, everything selected, no lite rows
 ])
-def test_decode_step_shape_sweep(shape):
-    say(f"decode_step shape sweep {shape}")
-    n_heavy = max(1, min(64, shape["k"] // 4))
+@pytest.mark.parametrize("mode", ["direct", "group", "staged"])
+def test_decode_step_shape_sweep(shape, mode):
+    say(f"decode_step shape sweep {shape} ({mode})")
+    G = shape["Hq"] // shape["Hkv"]
+    n_heavy = max(1, min(64, shape["k"] // 4, (shape["l"] - shape["w"]) // (4 * G)))
     cfg = small_cfg(n_heavy=n_heavy, **shape)
-    run_steps_against_oracle(cfg, 4, "direct", check_unfused=False)
+    run_steps_against_oracle(cfg, 4, mode, check_unfused=False, quiet=True)
 
 
 def test_decode_step_step_counter_far_ahead_of_the_slots_ages():
