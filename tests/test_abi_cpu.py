@@ -41,6 +41,25 @@ def test_version_and_status_strings(lib):
         assert lib.lrqk_status_string(code) not in ("ok", "unknown status")
 
 
+def test_binding_constants_match_the_header(lib):
+    text = open(os.path.join(ROOT, "include", "lrqk.h")).read()
+    def const(name):
+        m = re.search(r"\b%s\s*=\s*(-?\w+)" % name, text) or re.search(r"#define\s+%s\s+(\w+)" % name, text)
+        return int(m.group(1), 0)
+    from paper_2510_23649_amd import binding
+    assert const("LRQK_PROFILE_SLOTS") == len(binding.Plan.KERNELS)
+    for name in ("LRQK_FETCH_STAGED", "LRQK_FETCH_DIRECT", "LRQK_FETCH_GROUP", "LRQK_SELECT_FRESH",
+                 "LRQK_KV_BF16", "LRQK_KV_F32", "LRQK_WS_SELECT", "LRQK_WS_ATTEND", "LRQK_WS_UPDATE",
+                 "LRQK_WS_PREFILL"):
+        assert const(name) == getattr(binding, name), name
+    assert const("LRQK_VERSION") == lib.lrqk_version()
+    # the structures the binding mirrors
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    n_layer = len(re.search(r"typedef struct lrqk_layer \{(.*?)\} lrqk_layer;", text, re.S).group(1).split(";")) - 1
+    n_dbg = len(re.search(r"typedef struct lrqk_step_debug \{(.*?)\} lrqk_step_debug;", text, re.S).group(1).split(";")) - 1
+    assert n_layer == len(binding.Layer._fields_) and n_dbg == len(binding._StepDebug._fields_)
+
+
 def good(lib, **kw):
     base = dict(B=1, Hq=32, Hkv=8, l=4096, r=32, k=256, w=16, C_slots=4096)
     base.update(kw)

@@ -668,6 +668,38 @@ def test_config5_miss_heavy_full_batch():
     assert 0.30 <= sum(rates[1:]) / len(rates[1:]) <= 0.60
 
 
+def test_per_kernel_timing_of_the_step():
+    say("lrqk_plan_profile: kernel slots of sampled, carried and staged steps")
+    cfg = small_cfg()
+    data = make_layer(cfg)
+    dl = DeviceLayer(cfg, data)
+    plan = L.Plan(dl.shape)
+    qs = QueryStream(data)
+    out = torch.empty((cfg.B, cfg.Hq, cfg.d), device=DEV)
+
+    def timed_step(step, mode):
+        plan.profile(1)
+        q, q_hat = qs.next()
+        L.lrqk_decode_step(plan, dl.shape, step, dl.struct(), q_hat.to(DEV), q.to(DEV), out, mode)
+        ms, n = plan.profile_read()
+        plan.profile(0)
+        assert n == 1
+        return {k for k, v in ms.items() if v > 0.0}, ms
+
+    used, ms = timed_step(1, L.LRQK_FETCH_DIRECT | L.LRQK_SELECT_FRESH)
+    assert used == {"sample", "threshold", "proxy_scores", "select", "attend", "combine"}
+    assert all(0.0 < ms[k] < 5.0 for k in used)              # milliseconds; these are tiny kernels
+    used, _ = timed_step(2, L.LRQK_FETCH_DIRECT)              # thresholds carried: no estimate kernels
+    assert used == {"proxy_scores", "select", "attend", "combine"}
+    used, _ = timed_step(3, L.LRQK_FETCH_STAGED)
+    assert used >= {"proxy_scores", "select", "attend", "fetch_scatter", "attend_missed_rows"}
+    used, _ = timed_step(4, L.LRQK_FETCH_GROUP)
+    assert used == {"proxy_scores", "select", "attend", "attend_missed_rows", "combine"}
+    us = plan.time_proxy_pass(dl.shape, [dl.A_K], qs.next()[1].to(DEV), 8, sel_thr=dl.sel_thr)
+    assert 0.0 < us < 1000.0
+    plan.close()
+
+
 def test_rerun_is_deterministic():
     say("two runs of the same steps give identical bits")
     cfg = small_cfg()
