@@ -538,6 +538,28 @@ def test_decode_step_victims_spread_over_age_classes(n_classes):
     plan.close()
 
 
+@pytest.mark.parametrize("seed", [11, 12])
+def test_decode_step_random_shapes(seed):
+    say(f"decode_step on 30 random shapes, fetch modes and threshold sources (seed {seed})")
+    rng = np.random.default_rng(seed)
+    for it in range(30):
+        G, Hkv, B = int(rng.choice([1, 2, 3, 4, 7, 8])), int(rng.integers(1, 3)), int(rng.integers(1, 3))
+        r = int(rng.choice([8, 16, 32, 64, 12, 48]))
+        l = int(rng.choice([int(rng.integers(70, 400)), int(rng.integers(400, 9000)),
+                            int(rng.integers(9000, 90000))]))
+        w = int(rng.integers(0, min(l // 3, 200)))
+        kmax = min(l - w, 4096)
+        k = int(rng.choice([1, int(rng.integers(1, max(2, kmax // 20))), int(rng.integers(1, kmax + 1))]))
+        C = int(min(8192, k + rng.choice([0, 1, int(rng.integers(0, 2 * k + 2))])))
+        mode = str(rng.choice(["direct", "group", "staged"]))
+        carry = str(rng.choice(["fresh_first", "off", "unknown_first"]))
+        shape = dict(B=B, Hq=G * Hkv, Hkv=Hkv, l=l, r=r, k=k, w=w, C=C,
+                     kv_dtype=str(rng.choice(["bf16", "f32"])))
+        say(f"   {it}: {shape} {mode} {carry}")
+        cfg = small_cfg(n_heavy=max(1, min(64, k // 4, (l - w) // (4 * G))), **shape)
+        run_steps_against_oracle(cfg, 3, mode, check_unfused=False, carry=carry, quiet=True)
+
+
 @pytest.mark.parametrize("carry", ["off", "unknown_first"])
 def test_decode_step_threshold_sources(carry):
     say(f"decode_step small, candidate thresholds: {carry}")
