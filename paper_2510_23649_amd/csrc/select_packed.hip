@@ -154,6 +154,155 @@ __device__ __forceinline__ uint32_t find_two_from_top(const uint32_t* hist, uint
   return total;
 }
 
+// Victim slots for the nm missing positions of a head (Sec. 4.1 hit-and-miss cache; replacement
+// by least recent selection: victims in (last_used, slot) order, the j-th miss taking the j-th
+// victim), then eviction and installation in the maps.  Called by all 1024 threads.
+struct VictimWork {
+  // LDS
+  int32_t* lu_s;          // [C] last_used, already `step` where used in this step
+  const int32_t* to_s;    // [C] token_of before the step
+  const int32_t* mt_s;    // [nm] missing positions, ascending
+  const int32_t* mj_s;    // [nm] their indices in the outputs
+  int32_t* vsorted;       // [nm] receives the victims in rank order
+  uint32_t* ahist;        // [kAgeBins], zero
+  uint32_t* cls_age;      // [kMaxCls]
+  uint32_t* cls_base;     // [kMaxCls]
+  uint32_t* sh_ncls;      // zero
+  uint32_t* sh_clip;      // zero
+  uint32_t* sh_bad;
+  uint32_t* scan_areas;   // four areas of 32 words for the prefix counts
+  unsigned char* sort_area;  // 8 bytes per slot (C rounded up to a power of two): rare cases only
+  // this head's maps and outputs (global)
+  int32_t* so;
+  int32_t* to;
+  int32_t* lu;
+  int32_t* ms;
+  int32_t* ss;
+  int32_t step;
+  int C, l, spt;
+};
+template <int SPT>
+__device__ __forceinline__ void assign_victims(const VictimWork& v, int nm) {
+  const int t = threadIdx.x;
+  const int C = v.C, l = v.l, spt = v.spt;
+  const int32_t step = v.step;
+  auto scan_area = [&](int i) { return v.scan_areas + (i & 3) * 2 * kWaves; };
+  // ages of the slots not used in this step; thread t owns slots [s0, s1)
+  const int s0 = min(C, t * spt), s1 = min(C, s0 + spt);
+  uint32_t age[SPT];
+#pragma unroll
+  for (int u = 0; u < SPT; ++u) {
+    age[u] = 0xffffffffu;  // not eligible
+    if (u < spt && s0 + u < s1) {
+      const int32_t lv = v.lu_s[s0 + u];
+      if (lv != step) {
+        age[u] = min((uint32_t)(step - 1 - lv), (uint32_t)(kAgeBins - 1));
+        atomicAdd(&v.ahist[age[u]], 1u);
+      }
+    }
+  }
+  lds_barrier();
+  // scan the age classes from the oldest: eligible slots above each class, and the number of
+  // non-empty classes above it.  A non-empty class with fewer than nm slots above it holds
+  // victims; its number among those classes is its index in cls_age / cls_base.
+  uint32_t n_elig;
+  {
+    const uint32_t c0b = v.ahist[2 * t], c1b = v.ahist[2 * t + 1];
+    const uint32_t e0 = c0b ? 1u : 0u, e1 = c1b ? 1u : 0u;
+    uint32_t bc, be, ne;
+    scan2(c0b + c1b, e0 + e1, scan_area(3), &bc, &be, &n_elig, &ne);
+    const uint32_t above1 = n_elig - bc - c0b - c1b, ne_above1 = ne - be - e0 - e1;
+    const uint32_t above0 = above1 + c1b, ne_above0 = ne_above1 + e1;
+    if (c1b && above1 < (uint32_t)nm) {
+      if (ne_above1 < (uint32_t)kMaxCls) {
+        v.cls_age[ne_above1] = 2 * t + 1;
+        v.cls_base[ne_above1] = above1;
+      }
+      atomicMax(v.sh_ncls, ne_above1 + 1);
+      if (2 * t + 1 == kAgeBins - 1) *v.sh_clip = 1u;
+    }
+    if (c0b && above0 < (uint32_t)nm) {
+      if (ne_above0 < (uint32_t)kMaxCls) {
+        v.cls_age[ne_above0] = 2 * t;
+        v.cls_base[ne_above0] = above0;
+      }
+      atomicMax(v.sh_ncls, ne_above0 + 1);
+    }
+    lds_barrier();
+  }
+  const int ncls = (int)*v.sh_ncls;
+  // ages beyond the histogram's range share its last class, which then does not order them
+  const bool clipped = *v.sh_clip != 0u && step > kAgeBins - 1;
+  int nv = nm;  // number of victims found (< nm only if the caller reused `step`)
+  if (n_elig >= (uint32_t)nm && ncls <= kMaxCls && !clipped) {
+    // rank of a victim = slots in older classes + its index in its class, in slot order:
+    // four classes per prefix count (16-bit fields)
+    for (int c4 = 0; c4 < ncls; c4 += 4) {
+      uint32_t ca[4], cb[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        ca[c] = c4 + c < ncls ? v.cls_age[c4 + c] : 0xfffffffeu;
+        cb[c] = c4 + c < ncls ? v.cls_base[c4 + c] : 0u;
+      }
+      uint32_t lo = 0, hi = 0;
+#pragma unroll
+      for (int u = 0; u < SPT; ++u)
+        if (u < spt) {
+          lo += (age[u] == ca[0] ? 1u : 0u) + (age[u] == ca[1] ? 1u << 16 : 0u);
+          hi += (age[u] == ca[2] ? 1u : 0u) + (age[u] == ca[3] ? 1u << 16 : 0u);
+        }
+      uint32_t exlo, exhi, tl, th;
+      scan2(lo, hi, scan_area(c4 >> 2), &exlo, &exhi, &tl, &th);
+      uint32_t before[4] = {cb[0] + (exlo & 0xffffu), cb[1] + (exlo >> 16),
+                            cb[2] + (exhi & 0xffffu), cb[3] + (exhi >> 16)};
+#pragma unroll
+      for (int u = 0; u < SPT; ++u)
+        if (u < spt) {
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            if (age[u] == ca[c]) {
+              const uint32_t rk = before[c]++;
+              if (rk < (uint32_t)nm) v.vsorted[rk] = s0 + u;
+            }
+        }
+    }
+    lds_barrier();
+  } else {
+    // out of victims, too many classes, or ages beyond the histogram's range: sort every
+    // slot's (last_used, slot) key
+    uint64_t* const vlist = reinterpret_cast<uint64_t*>(v.sort_area);
+    int Cpad = 2;
+    while (Cpad < C) Cpad <<= 1;
+    for (int i = t; i < Cpad; i += kT) {
+      uint64_t key64 = ~0ull;
+      if (i < C && v.lu_s[i] != step)
+        key64 = (((uint64_t)(uint32_t)(v.lu_s[i] + 1)) << 32) | (uint32_t)i;
+      vlist[i] = key64;
+    }
+    bitonic_sort_lds(vlist, Cpad);
+    nv = (int)min((uint32_t)nm, n_elig);
+    for (int jj = t; jj < nv; jj += kT) v.vsorted[jj] = (int32_t)(uint32_t)vlist[jj];
+    __syncthreads();
+  }
+  for (int jj = t; jj < nm; jj += kT) {
+    if (jj >= nv) {  // ran out of victims (the caller reused `step`)
+      atomicOr(v.sh_bad, 1u);
+      v.ms[jj] = -1;
+      v.ss[v.mj_s[jj]] = -1;
+      continue;
+    }
+    const int32_t slot = v.vsorted[jj];
+    const int32_t tok = v.mt_s[jj];
+    const int32_t old = v.to_s[slot];
+    if (old >= 0 && old < l) v.so[old] = -1;
+    v.to[slot] = tok;
+    v.so[tok] = slot;
+    v.lu[slot] = step;
+    v.ms[jj] = slot;
+    v.ss[v.mj_s[jj]] = slot;
+  }
+}
+
 struct PackedArgs {
   const unsigned long long* bitmap;  // [BHq][words64]
   const float* cand_scores;          // [BHq][words64][kCandPerGroup]
@@ -611,120 +760,30 @@ __global__ __launch_bounds__(kT) void select_packed_kernel(const PackedArgs a) {
 
   // ---- 4. victims ------------------------------------------------------------------------------------
   if (nm > 0) {
-    // ages of the slots not used in this step; thread t owns slots [s0, s1)
-    const int s0 = min(C, t * spt), s1 = min(C, s0 + spt);
-    uint32_t age[SPT];
-#pragma unroll
-    for (int u = 0; u < SPT; ++u) {
-      age[u] = 0xffffffffu;  // not eligible
-      if (u < spt && s0 + u < s1) {
-        const int32_t lv = lu_s[s0 + u];
-        if (lv != step) {
-          age[u] = min((uint32_t)(step - 1 - lv), (uint32_t)(kAgeBins - 1));
-          atomicAdd(&ahist[age[u]], 1u);
-        }
-      }
-    }
-    lds_barrier();
-    // scan the age classes from the oldest: eligible slots above each class, and the number of
-    // non-empty classes above it.  A non-empty class with fewer than nm slots above it holds
-    // victims; its number among those classes is its index in cls_age / cls_base.
-    uint32_t n_elig;
-    {
-      const uint32_t c0b = ahist[2 * t], c1b = ahist[2 * t + 1];
-      const uint32_t e0 = c0b ? 1u : 0u, e1 = c1b ? 1u : 0u;
-      uint32_t bc, be, ne;
-      scan2(c0b + c1b, e0 + e1, scan_area(3), &bc, &be, &n_elig, &ne);
-      const uint32_t above1 = n_elig - bc - c0b - c1b, ne_above1 = ne - be - e0 - e1;
-      const uint32_t above0 = above1 + c1b, ne_above0 = ne_above1 + e1;
-      if (c1b && above1 < (uint32_t)nm) {
-        if (ne_above1 < (uint32_t)kMaxCls) {
-          cls_age[ne_above1] = 2 * t + 1;
-          cls_base[ne_above1] = above1;
-        }
-        atomicMax(&sh_ncls, ne_above1 + 1);
-        if (2 * t + 1 == kAgeBins - 1) sh_clip = 1u;
-      }
-      if (c0b && above0 < (uint32_t)nm) {
-        if (ne_above0 < (uint32_t)kMaxCls) {
-          cls_age[ne_above0] = 2 * t;
-          cls_base[ne_above0] = above0;
-        }
-        atomicMax(&sh_ncls, ne_above0 + 1);
-      }
-      lds_barrier();
-    }
-    const int ncls = (int)sh_ncls;
-    // ages beyond the histogram's range share its last class, which then does not order them
-    const bool clipped = sh_clip != 0u && step > kAgeBins - 1;
-    int nv = nm;  // number of victims found (< nm only if the caller reused `step`)
-    if (n_elig >= (uint32_t)nm && ncls <= kMaxCls && !clipped) {
-      // rank of a victim = slots in older classes + its index in its class, in slot order:
-      // four classes per prefix count (16-bit fields)
-      for (int c4 = 0; c4 < ncls; c4 += 4) {
-        uint32_t ca[4], cb[4];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          ca[c] = c4 + c < ncls ? cls_age[c4 + c] : 0xfffffffeu;
-          cb[c] = c4 + c < ncls ? cls_base[c4 + c] : 0u;
-        }
-        uint32_t lo = 0, hi = 0;
-#pragma unroll
-        for (int u = 0; u < SPT; ++u)
-          if (u < spt) {
-            lo += (age[u] == ca[0] ? 1u : 0u) + (age[u] == ca[1] ? 1u << 16 : 0u);
-            hi += (age[u] == ca[2] ? 1u : 0u) + (age[u] == ca[3] ? 1u << 16 : 0u);
-          }
-        uint32_t exlo, exhi, tl, th;
-        scan2(lo, hi, scan_area(c4 >> 2), &exlo, &exhi, &tl, &th);
-        uint32_t before[4] = {cb[0] + (exlo & 0xffffu), cb[1] + (exlo >> 16),
-                              cb[2] + (exhi & 0xffffu), cb[3] + (exhi >> 16)};
-#pragma unroll
-        for (int u = 0; u < SPT; ++u)
-          if (u < spt) {
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-              if (age[u] == ca[c]) {
-                const uint32_t rk = before[c]++;
-                if (rk < (uint32_t)nm) vsorted[rk] = s0 + u;
-              }
-          }
-      }
-      lds_barrier();
-    } else {
-      // out of victims, too many classes, or ages beyond the histogram's range: sort every
-      // slot's (last_used, slot) key
-      uint64_t* const vlist = reinterpret_cast<uint64_t*>(X);
-      int Cpad = 2;
-      while (Cpad < C) Cpad <<= 1;
-      for (int v = t; v < Cpad; v += kT) {
-        uint64_t key64 = ~0ull;
-        if (v < C && lu_s[v] != step)
-          key64 = (((uint64_t)(uint32_t)(lu_s[v] + 1)) << 32) | (uint32_t)v;
-        vlist[v] = key64;
-      }
-      bitonic_sort_lds(vlist, Cpad);
-      nv = (int)min((uint32_t)nm, n_elig);
-      for (int jj = t; jj < nv; jj += kT) vsorted[jj] = (int32_t)(uint32_t)vlist[jj];
-      __syncthreads();
-    }
-    for (int jj = t; jj < nm; jj += kT) {
-      if (jj >= nv) {  // ran out of victims (the caller reused `step`)
-        atomicOr(&sh_bad, 1u);
-        ms[jj] = -1;
-        ss[mj_s[jj]] = -1;
-        continue;
-      }
-      const int32_t v = vsorted[jj];
-      const int32_t tok = mt_s[jj];
-      const int32_t old = to_s[v];
-      if (old >= 0 && old < l) so[old] = -1;
-      to[v] = tok;
-      so[tok] = v;
-      lu[v] = step;
-      ms[jj] = v;
-      ss[mj_s[jj]] = v;
-    }
+    VictimWork v;
+    v.lu_s = lu_s;
+    v.to_s = to_s;
+    v.mt_s = mt_s;
+    v.mj_s = mj_s;
+    v.vsorted = vsorted;
+    v.ahist = ahist;
+    v.cls_age = cls_age;
+    v.cls_base = cls_base;
+    v.sh_ncls = &sh_ncls;
+    v.sh_clip = &sh_clip;
+    v.sh_bad = &sh_bad;
+    v.scan_areas = wave_tot;
+    v.sort_area = X;
+    v.so = so;
+    v.to = to;
+    v.lu = lu;
+    v.ms = ms;
+    v.ss = ss;
+    v.step = step;
+    v.C = C;
+    v.l = l;
+    v.spt = spt;
+    assign_victims<SPT>(v, nm);
   }
   lds_barrier();
   if (t == 0) a.n_miss[bh] = sh_bad ? -1 : nm;
